@@ -1,0 +1,143 @@
+/*
+ * libesa — the per-step hot path of Efficient Selective Attention (ESA, arXiv 2502.14477)
+ * for AMD MI355X (gfx950).  C ABI; every tensor argument is a DEVICE pointer owned by the
+ * caller.  The library never allocates, frees or keeps a pointer; every call only enqueues
+ * kernels on `stream` (a hipStream_t passed as void*, NULL = the default stream) and
+ * returns without synchronising.
+ *
+ * One ESA step for the current tokens C at positions [t0, t0+l_c) (Section 3.1):
+ *   preceding tokens split into  I = [0, i_end)   i_end   = min(l_i, t0)
+ *                                M = [i_end, l_start)
+ *                                L = [l_start, t0)  l_start = max(t0 - l_l, i_end)
+ *   1. esa_compress     q'_c = f_theta_q(q_c), k'_m = f_theta_k(k_m)            (Eq. 5)
+ *   2. esa_score        F_s(m;C) = max_c ( q'_c.k'_m - max_m' q'_c.k'_m' )      (Eq. 6 in Eq. 4)
+ *   3. esa_select_topk  M_k = the k middle tokens with the highest F_s           (Eq. 2)
+ *   4. esa_gather_kv    full-size keys/values of M_k                             (Section 1, App. B)
+ *   5. esa_attend       O = Attn(Q_C, K_[I,M_k,L,C], V_[I,M_k,L,C])              (Eq. 1)
+ *
+ * Layout conventions: row-major, innermost dimension contiguous, strides in ELEMENTS.
+ * `dtype` is the storage type of Q, K, V, W, bias, K', Q' and O; scores and lse are always
+ * fp32, indices int32.  Arithmetic accumulates in fp32.  `batch` independent sequences are
+ * processed by one call; `*_bs` arguments are the element strides between them.
+ *
+ * Return value: ESA_OK or a negative error code.  Nothing is enqueued when an error is
+ * returned.  esa_last_error() gives a text for the calling thread's last error.
+ * The library never throws, aborts or prints.
+ */
+#ifndef ESA_H
+#define ESA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Exported symbols (the library is built with hidden default visibility). */
+#define ESA_API __attribute__((visibility("default")))
+
+#define ESA_F32 0
+#define ESA_BF16 1
+
+#define ESA_OK 0
+#define ESA_EINVAL (-1)       /* null pointer, non-positive size, bad range, misaligned pointer, H % H_kv != 0 */
+#define ESA_EUNSUPPORTED (-2) /* dtype / head size / compressed size not built */
+#define ESA_EWORKSPACE (-3)   /* workspace missing or smaller than esa_*_workspace_bytes says */
+#define ESA_EHIP (-4)         /* a HIP call failed; see esa_last_error() */
+
+/* Library version: major*10000 + minor*100 + patch. */
+ESA_API int esa_version(void);
+
+/* Text of the calling thread's most recent error ("" if none).  Host pointer, owned by the library. */
+ESA_API const char* esa_last_error(void);
+
+/* Host-side segment arithmetic of Section 3.1 (no GPU work): writes i_end and l_start. */
+ESA_API int esa_segments(int64_t t0, int64_t l_i, int64_t l_l, int64_t* i_end, int64_t* l_start);
+
+/*
+ * Eq. 5 — compression by one linear layer on the head-concatenated vector.
+ *   x    [batch][n_tok, d_in]  row stride ldx, batch stride x_bs.  A [n_tok, heads, d] tensor is
+ *        its own head-major concatenation (Section 3.1), so d_in = heads*d and ldx = heads*d.
+ *   W    [d_in, d_c] contiguous, shared by the batch;  bias [d_c] or NULL.
+ *   out  [batch][n_tok, d_c]   row stride ldo, batch stride out_bs; rounded to `dtype`
+ *        (nearest-even).  Writing K' rows of the current tokens straight into the compressed-key
+ *        cache is done by pointing `out` at cache row t0.
+ * n_tok == 0 is a no-op.  d_c must be a multiple of 16 and at most 256.
+ */
+ESA_API int esa_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx,
+                 const void* W, const void* bias, int d_c,
+                 void* out, int64_t ldo,
+                 int dtype, int batch, int64_t x_bs, int64_t out_bs, void* stream);
+
+/*
+ * Eq. 6 inside Eq. 4 — importance of every middle token m in [m_lo, m_hi):
+ *   S[c,m] = qc[c] . kc_cache[m];  mu[c] = max_m S[c,m];  score[m-m_lo] = max_c (S[c,m] - mu[c]).
+ * Consequently score <= 0, its maximum is exactly 0, and every current token's best middle
+ * token scores exactly 0.  With eps > 0 the result is then replaced by its running maximum over
+ * [m-eps, m+eps] clamped to the middle segment (Eq. 8).
+ *   qc        [batch][l_c, d_c]  contiguous rows, batch stride q_bs
+ *   kc_cache  [batch][>= m_hi, d_c] contiguous rows, batch stride kc_bs
+ *   score     [batch][m_hi-m_lo] fp32, batch stride score_bs
+ *   workspace esa_score_workspace_bytes(l_c, m_hi-m_lo, eps, batch) bytes, 256-byte aligned
+ * m_hi == m_lo is a no-op.
+ */
+ESA_API size_t esa_score_workspace_bytes(int l_c, int64_t n_mid, int eps, int batch);
+ESA_API int esa_score(const void* qc, int l_c,
+              const void* kc_cache, int64_t m_lo, int64_t m_hi, int d_c,
+              int eps, float* score, int dtype,
+              int batch, int64_t q_bs, int64_t kc_bs, int64_t score_bs,
+              void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * Eq. 2 — indices of the k_eff = min(k, n) largest scores, written as ASCENDING absolute
+ * positions (array index + base).  Equal scores: the lower position wins.  Scores are compared
+ * as IEEE fp32 totally ordered by value (-0 < +0; NaN must not occur).
+ *   score [batch][n] fp32;  idx [batch][k_eff] int32, batch stride idx_bs
+ *   workspace esa_select_topk_workspace_bytes(n, k, batch) bytes, 256-byte aligned
+ * n == 0 or k == 0 is a no-op.
+ */
+ESA_API size_t esa_select_topk_workspace_bytes(int64_t n, int k, int batch);
+ESA_API int esa_select_topk(const float* score, int64_t n, int k, int64_t base,
+                    int32_t* idx,
+                    int batch, int64_t score_bs, int64_t idx_bs,
+                    void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * Fetch the full-size keys and values of the selected tokens into dense buffers.
+ *   k_cache, v_cache [batch][S, h_kv, d]  token stride tok_stride (>= h_kv*d), batch stride cache_bs
+ *   idx              [batch][n_sel] token positions (each in [0, S); not checked on the device)
+ *   k_sel, v_sel     [batch][n_sel, h_kv, d] contiguous, batch stride sel_bs
+ * n_sel == 0 is a no-op.
+ */
+ESA_API int esa_gather_kv(const void* k_cache, const void* v_cache, int64_t tok_stride,
+                  const int32_t* idx, int n_sel, int h_kv, int d,
+                  void* k_sel, void* v_sel,
+                  int dtype, int batch, int64_t cache_bs, int64_t idx_bs, int64_t sel_bs, void* stream);
+
+/*
+ * Eq. 1 — softmax attention of the current tokens over [I, M_k, L, C]:
+ *   out[c,h] = sum_j softmax_j( scale * q[c,h].k[j,g] ) v[j,g],   g = h / (h / h_kv),
+ *   j over cache rows [0, i_end), the n_sel gathered rows, cache rows [l_start, t0),
+ *   and cache rows [t0, t0+c] (a current token sees itself and earlier current tokens;
+ *   Algorithm 1: causal local part, non-causal global part, one normalisation).
+ * The caller has already stored the current tokens' keys/values in cache rows [t0, t0+l_c).
+ *   q    [batch][l_c, h, d] contiguous, batch stride q_bs
+ *   k_cache, v_cache as in esa_gather_kv;  k_sel, v_sel [batch][n_sel, h_kv, d] (may be NULL if n_sel == 0)
+ *   out  [batch][l_c, h, d] contiguous, batch stride out_bs
+ *   lse  [batch][l_c, h] fp32 natural-log normaliser, batch stride l_c*h; NULL to skip
+ *   workspace esa_attend_workspace_bytes(...) bytes, 256-byte aligned
+ */
+ESA_API size_t esa_attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch);
+ESA_API int esa_attend(const void* q, int l_c, int h, int h_kv, int d,
+               const void* k_cache, const void* v_cache, int64_t tok_stride,
+               int64_t t0, int64_t l_i, int64_t l_l,
+               const void* k_sel, const void* v_sel, int n_sel,
+               float scale, void* out, float* lse,
+               int dtype, int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs,
+               void* workspace, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ESA_H */

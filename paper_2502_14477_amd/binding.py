@@ -1,0 +1,227 @@
+"""ctypes binding over libesa.so: argument marshalling only.
+
+Every function has the name and meaning of its C entry point (include/esa.h).  Tensors are
+torch CUDA tensors (torch provides device memory and the current stream, nothing else); a
+leading batch dimension is optional.  Outputs and workspaces are torch allocations made here.
+Nothing in this module computes: with the library missing, import fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+ESA_F32, ESA_BF16 = 0, 1
+_PKG = os.path.dirname(os.path.abspath(__file__))
+
+
+class EsaError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("libesa error %d: %s" % (code, text))
+        self.code = code
+
+
+def lib_path() -> str:
+    return os.path.join(_PKG, "libesa.so")
+
+
+def _load() -> ctypes.CDLL:
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(
+            "%s is missing: build it with `python -m paper_2502_14477_amd.build` "
+            "(there is no fallback path)" % path)
+    L = ctypes.CDLL(path)
+    i32, i64, vp, sz, f32 = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float
+    L.esa_version.restype = i32
+    L.esa_version.argtypes = []
+    L.esa_last_error.restype = ctypes.c_char_p
+    L.esa_last_error.argtypes = []
+    L.esa_segments.restype = i32
+    L.esa_segments.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    L.esa_compress.restype = i32
+    L.esa_compress.argtypes = [vp, i64, i64, i64, vp, vp, i32, vp, i64, i32, i32, i64, i64, vp]
+    L.esa_score_workspace_bytes.restype = sz
+    L.esa_score_workspace_bytes.argtypes = [i32, i64, i32, i32]
+    L.esa_score.restype = i32
+    L.esa_score.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, i32, i32, i64, i64, i64, vp, sz, vp]
+    L.esa_select_topk_workspace_bytes.restype = sz
+    L.esa_select_topk_workspace_bytes.argtypes = [i64, i32, i32]
+    L.esa_select_topk.restype = i32
+    L.esa_select_topk.argtypes = [vp, i64, i32, i64, vp, i32, i64, i64, vp, sz, vp]
+    L.esa_gather_kv.restype = i32
+    L.esa_gather_kv.argtypes = [vp, vp, i64, vp, i32, i32, i32, vp, vp, i32, i32, i64, i64, i64, vp]
+    L.esa_attend_workspace_bytes.restype = sz
+    L.esa_attend_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
+    L.esa_attend.restype = i32
+    L.esa_attend.argtypes = [vp, i32, i32, i32, i32, vp, vp, i64, i64, i64, i64, vp, vp, i32, f32, vp, vp,
+                             i32, i32, i64, i64, i64, i64, vp, sz, vp]
+    return L
+
+
+lib = _load()
+
+EXPORTS = ("esa_version", "esa_last_error", "esa_segments", "esa_compress", "esa_score_workspace_bytes",
+           "esa_score", "esa_select_topk_workspace_bytes", "esa_select_topk", "esa_gather_kv",
+           "esa_attend_workspace_bytes", "esa_attend")
+
+
+def _check(code: int) -> None:
+    if code != 0:
+        raise EsaError(code, lib.esa_last_error().decode())
+
+
+def _dtype(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return ESA_F32
+    if t.dtype == torch.bfloat16:
+        return ESA_BF16
+    raise EsaError(-2, "unsupported torch dtype %s" % t.dtype)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+_ws_cache = {}
+
+
+def _workspace(nbytes: int, device, tag: str) -> torch.Tensor:
+    """A reusable 256-byte aligned scratch tensor per (device, call)."""
+    key = (device, tag)
+    t = _ws_cache.get(key)
+    if t is None or t.numel() < nbytes:
+        t = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        assert t.data_ptr() % 256 == 0
+        _ws_cache[key] = t
+    return t
+
+
+def _batched(t: torch.Tensor, rank: int) -> Tuple[torch.Tensor, bool]:
+    if t.dim() == rank:
+        return t.unsqueeze(0), False
+    if t.dim() == rank + 1:
+        return t, True
+    raise EsaError(-1, "expected %d or %d dimensions, got %d" % (rank, rank + 1, t.dim()))
+
+
+def esa_version() -> int:
+    return lib.esa_version()
+
+
+def esa_segments(t0: int, l_i: int, l_l: int) -> Tuple[int, int]:
+    a, b = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib.esa_segments(t0, l_i, l_l, ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
+
+
+def esa_compress(x: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor] = None,
+                 out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """x [B?, n_tok, heads, d] or [B?, n_tok, d_in] -> [B?, n_tok, d_c].  `out` may be a row-strided
+    view (e.g. rows t0.. of the compressed-key cache)."""
+    d_in, d_c = W.shape
+    if x.shape[-1] != d_in:
+        x = x.flatten(-2)
+    xb, had_batch = _batched(x, 2)
+    B, n_tok = xb.shape[0], xb.shape[1]
+    assert xb.shape[2] == d_in and xb.stride(2) == 1 and W.is_contiguous()
+    if out is None:
+        ob = torch.empty((B, n_tok, d_c), dtype=x.dtype, device=x.device)
+    else:
+        ob, _ = _batched(out, 2)
+        assert ob.shape == (B, n_tok, d_c) and ob.stride(2) == 1 and ob.dtype == x.dtype
+    _check(lib.esa_compress(_ptr(xb), n_tok, d_in, xb.stride(1), _ptr(W), _ptr(bias), d_c, _ptr(ob), ob.stride(1),
+                            _dtype(x), B, xb.stride(0), ob.stride(0), _stream()))
+    return ob if had_batch else ob[0]
+
+
+def esa_score(qc: torch.Tensor, kc_cache: torch.Tensor, m_lo: int, m_hi: int, eps: int = 0,
+              out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """qc [B?, l_c, d_c], kc_cache [B?, S, d_c] -> score [B?, m_hi-m_lo] fp32."""
+    qb, had_batch = _batched(qc, 2)
+    kb, _ = _batched(kc_cache, 2)
+    B, l_c, d_c = qb.shape
+    assert kb.shape[0] == B and kb.shape[2] == d_c and qb.stride(2) == 1 and kb.stride(2) == 1
+    assert qb.stride(1) == d_c and kb.stride(1) == d_c and kb.dtype == qb.dtype
+    n = m_hi - m_lo
+    if out is None:
+        sb = torch.empty((B, max(n, 0)), dtype=torch.float32, device=qc.device)
+    else:
+        sb, _ = _batched(out, 1)
+    nbytes = lib.esa_score_workspace_bytes(l_c, n, eps, B)
+    ws = _workspace(nbytes, qc.device, "score")
+    _check(lib.esa_score(_ptr(qb), l_c, _ptr(kb), m_lo, m_hi, d_c, eps, _ptr(sb), _dtype(qc), B, qb.stride(0),
+                         kb.stride(0), sb.stride(0) if B > 1 else max(n, 1), _ptr(ws), ws.numel(), _stream()))
+    return sb if had_batch else sb[0]
+
+
+def esa_select_topk(score: torch.Tensor, k: int, base: int = 0) -> torch.Tensor:
+    """score [B?, n] fp32 -> idx [B?, min(k, n)] int32, ascending absolute positions."""
+    sb, had_batch = _batched(score, 1)
+    B, n = sb.shape
+    assert sb.dtype == torch.float32 and (n == 0 or sb.stride(1) == 1)
+    k_eff = min(k, n)
+    idx = torch.empty((B, k_eff), dtype=torch.int32, device=score.device)
+    nbytes = lib.esa_select_topk_workspace_bytes(n, k, B)
+    ws = _workspace(nbytes, score.device, "topk")
+    _check(lib.esa_select_topk(_ptr(sb), n, k, base, _ptr(idx), B, sb.stride(0) if B > 1 else max(n, 1),
+                               max(k_eff, 1), _ptr(ws), ws.numel(), _stream()))
+    return idx if had_batch else idx[0]
+
+
+def esa_gather_kv(k_cache: torch.Tensor, v_cache: torch.Tensor, idx: torch.Tensor):
+    """caches [B?, S, h_kv, d], idx [B?, n_sel] int32 -> (k_sel, v_sel) [B?, n_sel, h_kv, d]."""
+    kb, had_batch = _batched(k_cache, 3)
+    vb, _ = _batched(v_cache, 3)
+    ib, _ = _batched(idx, 1)
+    B, S, h_kv, d = kb.shape
+    n_sel = ib.shape[1]
+    assert vb.shape == kb.shape and vb.stride() == kb.stride() and kb.stride(3) == 1 and kb.stride(2) == d
+    assert ib.dtype == torch.int32 and ib.shape[0] == B and (n_sel == 0 or ib.stride(1) == 1)
+    ks = torch.empty((B, n_sel, h_kv, d), dtype=k_cache.dtype, device=k_cache.device)
+    vs = torch.empty_like(ks)
+    _check(lib.esa_gather_kv(_ptr(kb), _ptr(vb), kb.stride(1), _ptr(ib), n_sel, h_kv, d, _ptr(ks), _ptr(vs),
+                             _dtype(k_cache), B, kb.stride(0), ib.stride(0) if B > 1 else max(n_sel, 1),
+                             n_sel * h_kv * d, _stream()))
+    return (ks, vs) if had_batch else (ks[0], vs[0])
+
+
+def esa_attend(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, t0: int, l_i: int, l_l: int,
+               k_sel: Optional[torch.Tensor], v_sel: Optional[torch.Tensor], scale: Optional[float] = None,
+               return_lse: bool = False):
+    """q [B?, l_c, h, d]; caches [B?, S, h_kv, d] holding the current tokens at rows t0..; gathered
+    buffers [B?, n_sel, h_kv, d] -> out [B?, l_c, h, d] (and lse [B?, l_c, h] fp32)."""
+    qb, had_batch = _batched(q, 3)
+    kb, _ = _batched(k_cache, 3)
+    vb, _ = _batched(v_cache, 3)
+    B, l_c, h, d = qb.shape
+    h_kv = kb.shape[2]
+    assert qb.is_contiguous() and kb.stride(3) == 1 and kb.stride(2) == d and vb.stride() == kb.stride()
+    assert kb.shape[1] >= t0 + l_c, "the cache must already hold the current tokens"
+    n_sel = 0
+    sel_bs = 0
+    ksb = vsb = None
+    if k_sel is not None and k_sel.numel() > 0:
+        ksb, _ = _batched(k_sel, 3)
+        vsb, _ = _batched(v_sel, 3)
+        assert ksb.is_contiguous() and vsb.is_contiguous() and ksb.shape == vsb.shape
+        n_sel = ksb.shape[1]
+        sel_bs = ksb.stride(0)
+    out = torch.empty_like(qb)
+    lse = torch.empty((B, l_c, h), dtype=torch.float32, device=q.device) if return_lse else None
+    scale = float(d) ** -0.5 if scale is None else float(scale)
+    nbytes = lib.esa_attend_workspace_bytes(l_c, h, h_kv, d, _dtype(q), B)
+    ws = _workspace(nbytes, q.device, "attend")
+    _check(lib.esa_attend(_ptr(qb), l_c, h, h_kv, d, _ptr(kb), _ptr(vb), kb.stride(1), t0, l_i, l_l, _ptr(ksb),
+                          _ptr(vsb), n_sel, scale, _ptr(out), _ptr(lse), _dtype(q), B, qb.stride(0), kb.stride(0),
+                          sel_bs, out.stride(0), _ptr(ws), ws.numel(), _stream()))
+    if not had_batch:
+        out = out[0]
+        lse = None if lse is None else lse[0]
+    return (out, lse) if return_lse else out

@@ -1,0 +1,147 @@
+// Selected attention (Eq. 1): softmax attention of the current tokens over the virtual key
+// sequence  [ I | M_k | L | C ]  =  cache rows [0,i_end) ++ gathered rows [0,n_sel) ++ cache rows
+// [l_start, t0+l_c).  Current token c sees virtual keys [0, n_fixed + c], n_fixed = i_end + n_sel +
+// (t0 - l_start): everything before the chunk plus the chunk up to itself (Algorithm 1).
+#include "esa_common.h"
+#include "attend_mfma.h"
+
+namespace esa {
+namespace {
+
+struct KeySpace {
+  const char* k_cache;
+  const char* v_cache;
+  const char* k_sel;
+  const char* v_sel;
+  int64_t tok_bytes;      // cache token stride in bytes
+  int64_t sel_bytes;      // gathered-row stride in bytes
+  int64_t i_end, n_sel, l_start;
+};
+
+// Byte offset of virtual key j inside (is_sel ? the gathered buffer : the cache).
+__device__ __forceinline__ const char* key_row(const KeySpace& ks, int64_t j, bool values) {
+  if (j < ks.i_end) return (values ? ks.v_cache : ks.k_cache) + j * ks.tok_bytes;
+  j -= ks.i_end;
+  if (j < ks.n_sel) return (values ? ks.v_sel : ks.k_sel) + j * ks.sel_bytes;
+  j -= ks.n_sel;
+  return (values ? ks.v_cache : ks.k_cache) + (ks.l_start + j) * ks.tok_bytes;
+}
+
+__device__ __forceinline__ float block_max(float v, float* red) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// One workgroup per (current token, query head, batch element); fp32 arithmetic with full-precision
+// expf/logf.  Serves fp32 storage and every shape the matrix-core kernel does not cover.
+template <typename T>
+__global__ __launch_bounds__(256) void attend_fma(const T* __restrict__ q, int l_c, int h, int h_kv, int d, KeySpace ks,
+                                                  int64_t n_fixed, float scale, T* __restrict__ out,
+                                                  float* __restrict__ lse, int64_t q_bs, int64_t cache_bs_bytes,
+                                                  int64_t sel_bs_bytes, int64_t out_bs) {
+  __shared__ float qs[256];
+  __shared__ float p[256];
+  __shared__ float red[4];
+  __shared__ float accs[256];
+  const int c = blockIdx.x, hh = blockIdx.y, b = blockIdx.z;
+  const int g = hh / (h / h_kv);
+  ks.k_cache += (int64_t)b * cache_bs_bytes;
+  ks.v_cache += (int64_t)b * cache_bs_bytes;
+  if (ks.n_sel > 0) {
+    ks.k_sel += (int64_t)b * sel_bs_bytes;
+    ks.v_sel += (int64_t)b * sel_bs_bytes;
+  }
+  const T* qrow = q + (int64_t)b * q_bs + ((int64_t)c * h + hh) * d;
+  if ((int)threadIdx.x < d) qs[threadIdx.x] = load_f32(qrow + threadIdx.x);
+  __syncthreads();
+  const int64_t n_keys = n_fixed + c + 1;
+  const int nsub = 256 / d, dim = threadIdx.x % d, sub = threadIdx.x / d;
+  float m_run = -INFINITY, l_run = 0.f, acc = 0.f;
+  for (int64_t j0 = 0; j0 < n_keys; j0 += 256) {
+    const int64_t j = j0 + threadIdx.x;
+    float logit = -INFINITY;
+    if (j < n_keys) {
+      const T* kr = (const T*)key_row(ks, j, false) + (int64_t)g * d;
+      float s = 0.f;
+      for (int i = 0; i < d; ++i) s = __fmaf_rn(qs[i], load_f32(kr + i), s);
+      logit = s * scale;
+    }
+    const float m_new = fmaxf(m_run, block_max(logit, red));
+    const float pj = (j < n_keys) ? expf(logit - m_new) : 0.f;
+    const float s_tile = block_sum(pj, red);
+    const float corr = (m_run == -INFINITY) ? 0.f : expf(m_run - m_new);
+    l_run = l_run * corr + s_tile;
+    acc *= corr;
+    p[threadIdx.x] = pj;
+    __syncthreads();
+    const int lim = (n_keys - j0) < 256 ? (int)(n_keys - j0) : 256;
+    for (int jj = sub; jj < lim; jj += nsub) {
+      const T* vr = (const T*)key_row(ks, j0 + jj, true) + (int64_t)g * d;
+      acc = __fmaf_rn(p[jj], load_f32(vr + dim), acc);
+    }
+    m_run = m_new;
+    __syncthreads();
+  }
+  accs[threadIdx.x] = acc;
+  __syncthreads();
+  if ((int)threadIdx.x < d) {
+    float o = 0.f;
+    for (int s = 0; s < nsub; ++s) o += accs[s * d + threadIdx.x];
+    store_f32(out + (int64_t)b * out_bs + ((int64_t)c * h + hh) * d + threadIdx.x, o / l_run);
+  }
+  if (lse && threadIdx.x == 0) lse[((int64_t)b * l_c + c) * h + hh] = m_run + logf(l_run);
+}
+
+}  // namespace
+
+size_t attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch) {
+  if (l_c <= 0 || h <= 0 || h_kv <= 0 || d <= 0 || batch <= 0) return 256;
+  if (attend_mfma_supported(l_c, h, h_kv, d, dtype)) return attend_mfma_workspace_bytes(l_c, h, h_kv, d, batch);
+  return 256;
+}
+
+int launch_attend(const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
+                  int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, const void* k_sel, const void* v_sel,
+                  int n_sel, float scale, void* out, float* lse, int dtype, int batch, int64_t q_bs,
+                  int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes, hipStream_t st) {
+  const Segments sg = segments(t0, l_i, l_l);
+  const int64_t n_fixed = sg.i_end + n_sel + (t0 - sg.l_start);
+  if (attend_mfma_supported(l_c, h, h_kv, d, dtype) &&
+      attend_mfma_aligned(q, k_cache, v_cache, k_sel, v_sel, out, tok_stride, q_bs, cache_bs, sel_bs, out_bs)) {
+    return launch_attend_mfma(q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, sg.i_end, sg.l_start, k_sel,
+                              v_sel, n_sel, scale, out, lse, batch, q_bs, cache_bs, sel_bs, out_bs, ws, ws_bytes, st);
+  }
+  const int64_t esz = (dtype == ESA_F32) ? 4 : 2;
+  KeySpace ks;
+  ks.k_cache = (const char*)k_cache;
+  ks.v_cache = (const char*)v_cache;
+  ks.k_sel = (const char*)k_sel;
+  ks.v_sel = (const char*)v_sel;
+  ks.tok_bytes = tok_stride * esz;
+  ks.sel_bytes = (int64_t)h_kv * d * esz;
+  ks.i_end = sg.i_end;
+  ks.n_sel = n_sel;
+  ks.l_start = sg.l_start;
+  const dim3 grid(l_c, h, batch);
+  if (dtype == ESA_BF16) {
+    attend_fma<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)q, l_c, h, h_kv, d, ks, n_fixed, scale, (bf16_t*)out, lse,
+                                             q_bs, cache_bs * esz, sel_bs * esz, out_bs);
+  } else {
+    attend_fma<float><<<grid, 256, 0, st>>>((const float*)q, l_c, h, h_kv, d, ks, n_fixed, scale, (float*)out, lse,
+                                            q_bs, cache_bs * esz, sel_bs * esz, out_bs);
+  }
+  ESA_LAUNCH_CHECK("attend_fma");
+  return ESA_OK;
+}
+
+}  // namespace esa

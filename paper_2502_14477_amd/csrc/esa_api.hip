@@ -1,0 +1,158 @@
+// The C ABI of libesa: argument validation and dispatch.  No kernel code here.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "esa_common.h"
+
+namespace esa {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+int hip_failed(hipError_t e, const char* what) {
+  set_error("%s: %s", what, hipGetErrorString(e));
+  return ESA_EHIP;
+}
+
+static bool dtype_ok(int dtype) { return dtype == ESA_F32 || dtype == ESA_BF16; }
+static size_t elem_size(int dtype) { return dtype == ESA_F32 ? 4 : 2; }
+static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+constexpr int kMaxBatch = 65535;
+
+}  // namespace esa
+
+using namespace esa;
+
+extern "C" {
+
+int esa_version(void) { return 100; }
+
+const char* esa_last_error(void) { return g_err; }
+
+int esa_segments(int64_t t0, int64_t l_i, int64_t l_l, int64_t* i_end, int64_t* l_start) {
+  if (!i_end || !l_start) ESA_FAIL(ESA_EINVAL, "esa_segments: null output pointer");
+  if (t0 < 0 || l_i < 0 || l_l < 0) ESA_FAIL(ESA_EINVAL, "esa_segments: negative argument");
+  const Segments s = segments(t0, l_i, l_l);
+  *i_end = s.i_end;
+  *l_start = s.l_start;
+  return ESA_OK;
+}
+
+int esa_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx, const void* W, const void* bias, int d_c,
+                 void* out, int64_t ldo, int dtype, int batch, int64_t x_bs, int64_t out_bs, void* stream) {
+  if (!dtype_ok(dtype)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_compress: dtype %d", dtype);
+  if (n_tok < 0 || d_in <= 0 || d_c <= 0 || batch <= 0 || batch > kMaxBatch)
+    ESA_FAIL(ESA_EINVAL, "esa_compress: bad size (n_tok=%lld d_in=%lld d_c=%d batch=%d)", (long long)n_tok,
+             (long long)d_in, d_c, batch);
+  if (d_c % 16 != 0 || d_c > 256) ESA_FAIL(ESA_EUNSUPPORTED, "esa_compress: d_c=%d (multiple of 16, <= 256)", d_c);
+  if (ldx < d_in || ldo < d_c) ESA_FAIL(ESA_EINVAL, "esa_compress: row stride smaller than the row");
+  if (n_tok >= (int64_t)1 << 31) ESA_FAIL(ESA_EINVAL, "esa_compress: n_tok too large");
+  if (n_tok == 0) return ESA_OK;
+  if (!x || !W || !out) ESA_FAIL(ESA_EINVAL, "esa_compress: null pointer");
+  const size_t es = elem_size(dtype);
+  if (!aligned(x, es) || !aligned(W, es) || !aligned(out, es) || !aligned(bias, es))
+    ESA_FAIL(ESA_EINVAL, "esa_compress: misaligned pointer");
+  return launch_compress(x, n_tok, d_in, ldx, W, bias, d_c, out, ldo, dtype, batch, x_bs, out_bs,
+                         (hipStream_t)stream);
+}
+
+size_t esa_score_workspace_bytes(int l_c, int64_t n_mid, int eps, int batch) {
+  return score_workspace_bytes(l_c, n_mid, eps, batch);
+}
+
+int esa_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, int64_t m_hi, int d_c, int eps,
+              float* score, int dtype, int batch, int64_t q_bs, int64_t kc_bs, int64_t score_bs, void* workspace,
+              size_t ws_bytes, void* stream) {
+  if (!dtype_ok(dtype)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_score: dtype %d", dtype);
+  if (l_c <= 0 || d_c <= 0 || batch <= 0 || batch > kMaxBatch || eps < 0 || m_lo < 0 || m_hi < m_lo)
+    ESA_FAIL(ESA_EINVAL, "esa_score: bad size (l_c=%d d_c=%d batch=%d eps=%d m=[%lld,%lld))", l_c, d_c, batch, eps,
+             (long long)m_lo, (long long)m_hi);
+  if (d_c % 16 != 0 || d_c > 256) ESA_FAIL(ESA_EUNSUPPORTED, "esa_score: d_c=%d (multiple of 16, <= 256)", d_c);
+  if (m_hi - m_lo >= (int64_t)1 << 31) ESA_FAIL(ESA_EINVAL, "esa_score: more than 2^31-1 middle tokens");
+  if (m_hi == m_lo) return ESA_OK;
+  if (!qc || !kc_cache || !score) ESA_FAIL(ESA_EINVAL, "esa_score: null pointer");
+  const size_t es = elem_size(dtype);
+  if (!aligned(qc, es) || !aligned(kc_cache, es) || !aligned(score, 4))
+    ESA_FAIL(ESA_EINVAL, "esa_score: misaligned pointer");
+  if (!workspace || !aligned(workspace, 256) || ws_bytes < score_workspace_bytes(l_c, m_hi - m_lo, eps, batch))
+    ESA_FAIL(ESA_EWORKSPACE, "esa_score: workspace needs %zu bytes, 256-byte aligned",
+             score_workspace_bytes(l_c, m_hi - m_lo, eps, batch));
+  return launch_score(qc, l_c, kc_cache, m_lo, m_hi, d_c, eps, score, dtype, batch, q_bs, kc_bs, score_bs, workspace,
+                      ws_bytes, (hipStream_t)stream);
+}
+
+size_t esa_select_topk_workspace_bytes(int64_t n, int k, int batch) { return topk_workspace_bytes(n, k, batch); }
+
+int esa_select_topk(const float* score, int64_t n, int k, int64_t base, int32_t* idx, int batch, int64_t score_bs,
+                    int64_t idx_bs, void* workspace, size_t ws_bytes, void* stream) {
+  if (n < 0 || k < 0 || batch <= 0 || batch > kMaxBatch)
+    ESA_FAIL(ESA_EINVAL, "esa_select_topk: bad size (n=%lld k=%d batch=%d)", (long long)n, k, batch);
+  if (base < 0 || base + n > (int64_t)INT32_MAX) ESA_FAIL(ESA_EINVAL, "esa_select_topk: positions exceed int32");
+  if (n == 0 || k == 0) return ESA_OK;
+  if (!score || !idx) ESA_FAIL(ESA_EINVAL, "esa_select_topk: null pointer");
+  if (!aligned(score, 4) || !aligned(idx, 4)) ESA_FAIL(ESA_EINVAL, "esa_select_topk: misaligned pointer");
+  if (!workspace || !aligned(workspace, 256) || ws_bytes < topk_workspace_bytes(n, k, batch))
+    ESA_FAIL(ESA_EWORKSPACE, "esa_select_topk: workspace needs %zu bytes, 256-byte aligned",
+             topk_workspace_bytes(n, k, batch));
+  return launch_topk(score, n, k, base, idx, batch, score_bs, idx_bs, workspace, ws_bytes, (hipStream_t)stream);
+}
+
+int esa_gather_kv(const void* k_cache, const void* v_cache, int64_t tok_stride, const int32_t* idx, int n_sel,
+                  int h_kv, int d, void* k_sel, void* v_sel, int dtype, int batch, int64_t cache_bs, int64_t idx_bs,
+                  int64_t sel_bs, void* stream) {
+  if (!dtype_ok(dtype)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_gather_kv: dtype %d", dtype);
+  if (n_sel < 0 || h_kv <= 0 || d <= 0 || batch <= 0 || batch > kMaxBatch || tok_stride < (int64_t)h_kv * d)
+    ESA_FAIL(ESA_EINVAL, "esa_gather_kv: bad size (n_sel=%d h_kv=%d d=%d batch=%d tok_stride=%lld)", n_sel, h_kv, d,
+             batch, (long long)tok_stride);
+  if (n_sel == 0) return ESA_OK;
+  if (!k_cache || !v_cache || !idx || !k_sel || !v_sel) ESA_FAIL(ESA_EINVAL, "esa_gather_kv: null pointer");
+  const size_t es = elem_size(dtype);
+  if (!aligned(k_cache, es) || !aligned(v_cache, es) || !aligned(k_sel, es) || !aligned(v_sel, es) || !aligned(idx, 4))
+    ESA_FAIL(ESA_EINVAL, "esa_gather_kv: misaligned pointer");
+  return launch_gather(k_cache, v_cache, tok_stride, idx, n_sel, h_kv, d, k_sel, v_sel, dtype, batch, cache_bs, idx_bs,
+                       sel_bs, (hipStream_t)stream);
+}
+
+size_t esa_attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch) {
+  return attend_workspace_bytes(l_c, h, h_kv, d, dtype, batch);
+}
+
+int esa_attend(const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
+               int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, const void* k_sel, const void* v_sel,
+               int n_sel, float scale, void* out, float* lse, int dtype, int batch, int64_t q_bs, int64_t cache_bs,
+               int64_t sel_bs, int64_t out_bs, void* workspace, size_t ws_bytes, void* stream) {
+  if (!dtype_ok(dtype)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend: dtype %d", dtype);
+  if (l_c <= 0 || h <= 0 || h_kv <= 0 || d <= 0 || batch <= 0 || batch > kMaxBatch || n_sel < 0 || t0 < 0 ||
+      l_i < 0 || l_l < 0 || l_c > 65535 || h > 65535)
+    ESA_FAIL(ESA_EINVAL, "esa_attend: bad size (l_c=%d h=%d h_kv=%d d=%d batch=%d n_sel=%d t0=%lld)", l_c, h, h_kv, d,
+             batch, n_sel, (long long)t0);
+  if (h % h_kv != 0) ESA_FAIL(ESA_EINVAL, "esa_attend: h=%d is not a multiple of h_kv=%d", h, h_kv);
+  if (d > 256 || 256 % d != 0) ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend: head size %d (32, 64, 128 or 256)", d);
+  if (tok_stride < (int64_t)h_kv * d) ESA_FAIL(ESA_EINVAL, "esa_attend: tok_stride smaller than a token");
+  if (!q || !k_cache || !v_cache || !out) ESA_FAIL(ESA_EINVAL, "esa_attend: null pointer");
+  if (n_sel > 0 && (!k_sel || !v_sel)) ESA_FAIL(ESA_EINVAL, "esa_attend: null gathered buffer with n_sel > 0");
+  {
+    const Segments sg = segments(t0, l_i, l_l);
+    if (n_sel > sg.l_start - sg.i_end)
+      ESA_FAIL(ESA_EINVAL, "esa_attend: n_sel=%d exceeds the %lld middle tokens", n_sel,
+               (long long)(sg.l_start - sg.i_end));
+  }
+  const size_t es = elem_size(dtype);
+  if (!aligned(q, es) || !aligned(k_cache, es) || !aligned(v_cache, es) || !aligned(k_sel, es) || !aligned(v_sel, es) ||
+      !aligned(out, es) || !aligned(lse, 4))
+    ESA_FAIL(ESA_EINVAL, "esa_attend: misaligned pointer");
+  const size_t need = attend_workspace_bytes(l_c, h, h_kv, d, dtype, batch);
+  if (need > 256 && (!workspace || !aligned(workspace, 256) || ws_bytes < need))
+    ESA_FAIL(ESA_EWORKSPACE, "esa_attend: workspace needs %zu bytes, 256-byte aligned", need);
+  return launch_attend(q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, k_sel, v_sel, n_sel, scale, out,
+                       lse, dtype, batch, q_bs, cache_bs, sel_bs, out_bs, workspace, ws_bytes, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,109 @@
+// Shared declarations of libesa's translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "esa.h"
+
+namespace esa {
+
+// ---------------------------------------------------------------- errors (host)
+void set_error(const char* fmt, ...);
+int hip_failed(hipError_t e, const char* what);   // records the text, returns ESA_EHIP
+
+#define ESA_FAIL(code, ...)          \
+  do {                               \
+    ::esa::set_error(__VA_ARGS__);   \
+    return (code);                   \
+  } while (0)
+
+#define ESA_LAUNCH_CHECK(what)                                   \
+  do {                                                           \
+    hipError_t e__ = hipGetLastError();                          \
+    if (e__ != hipSuccess) return ::esa::hip_failed(e__, what);  \
+  } while (0)
+
+// ---------------------------------------------------------------- storage types
+typedef uint16_t bf16_t;   // raw bfloat16 bit pattern
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// Round to nearest, ties to even.  Inputs are finite in every use inside the library.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float load_f32(const T* p);
+template <> __device__ __forceinline__ float load_f32<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float load_f32<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
+
+template <typename T> __device__ __forceinline__ void store_f32(T* p, float v);
+template <> __device__ __forceinline__ void store_f32<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_f32<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// ---------------------------------------------------------------- order-preserving keys
+// fp32 -> uint32 such that a < b (as floats, -0 < +0) <=> key(a) < key(b) (as unsigned).
+__device__ __forceinline__ uint32_t ordered_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  return u ^ ((u & 0x80000000u) ? 0xFFFFFFFFu : 0x80000000u);
+}
+__device__ __forceinline__ float ordered_key_to_f32(uint32_t k) {
+  uint32_t u = k ^ ((k & 0x80000000u) ? 0x80000000u : 0xFFFFFFFFu);
+  return __uint_as_float(u);
+}
+constexpr uint32_t kOrderedKeyOfMinusInf = 0x007FFFFFu;   // ordered_key(-inf)
+
+// ---------------------------------------------------------------- wave helpers (64 lanes)
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---------------------------------------------------------------- segment arithmetic (Section 3.1)
+struct Segments {
+  int64_t i_end, l_start;
+};
+static inline Segments segments(int64_t t0, int64_t l_i, int64_t l_l) {
+  Segments s;
+  s.i_end = l_i < t0 ? l_i : t0;
+  s.l_start = (t0 - l_l) > s.i_end ? (t0 - l_l) : s.i_end;
+  return s;
+}
+
+// ---------------------------------------------------------------- launchers (one per .hip file)
+int launch_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx, const void* W, const void* bias,
+                    int d_c, void* out, int64_t ldo, int dtype, int batch, int64_t x_bs, int64_t out_bs,
+                    hipStream_t st);
+
+size_t score_workspace_bytes(int l_c, int64_t n_mid, int eps, int batch);
+int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, int64_t m_hi, int d_c, int eps,
+                 float* score, int dtype, int batch, int64_t q_bs, int64_t kc_bs, int64_t score_bs,
+                 void* ws, size_t ws_bytes, hipStream_t st);
+
+size_t topk_workspace_bytes(int64_t n, int k, int batch);
+int launch_topk(const float* score, int64_t n, int k, int64_t base, int32_t* idx, int batch, int64_t score_bs,
+                int64_t idx_bs, void* ws, size_t ws_bytes, hipStream_t st);
+
+int launch_gather(const void* k_cache, const void* v_cache, int64_t tok_stride, const int32_t* idx, int n_sel,
+                  int h_kv, int d, void* k_sel, void* v_sel, int dtype, int batch, int64_t cache_bs,
+                  int64_t idx_bs, int64_t sel_bs, hipStream_t st);
+
+size_t attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch);
+int launch_attend(const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
+                  int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, const void* k_sel, const void* v_sel,
+                  int n_sel, float scale, void* out, float* lse, int dtype, int batch, int64_t q_bs,
+                  int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes, hipStream_t st);
+
+}  // namespace esa

@@ -1,0 +1,73 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad arguments
+before touching the GPU (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import paper_2502_14477_amd as esa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "esa.h")).read()
+    return sorted(set(re.findall(r"ESA_API\s+[\w\s\*]+?\b(esa_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    names = _declared()
+    assert len(names) == 11 and "esa_attend" in names and "esa_select_topk" in names
+    raw = ctypes.CDLL(esa.lib_path())
+    for n in names:
+        assert hasattr(raw, n), n
+    assert sorted(esa.EXPORTS) == names
+    for n in ("esa_compress", "esa_score", "esa_select_topk", "esa_gather_kv", "esa_attend", "esa_segments"):
+        assert callable(getattr(esa, n))
+    assert esa.esa_version() >= 100
+
+
+def test_segments_host_logic():
+    assert esa.esa_segments(0, 128, 2048) == (0, 0)
+    assert esa.esa_segments(100, 128, 2048) == (100, 100)
+    assert esa.esa_segments(1000, 128, 2048) == (128, 128)
+    assert esa.esa_segments(4608, 128, 2048) == (128, 2560)
+    assert esa.esa_segments(130560, 128, 2048) == (128, 128512)
+    L = esa.lib
+    assert L.esa_segments(-1, 0, 0, ctypes.byref(ctypes.c_int64()), ctypes.byref(ctypes.c_int64())) == -1
+    assert L.esa_segments(5, 1, 1, None, None) == -1
+
+
+def test_argument_validation_returns_codes_without_a_gpu():
+    L = esa.lib
+    fake = ctypes.c_void_p(4096)          # never dereferenced: every call below fails validation first
+    odd = ctypes.c_void_p(4097)
+    # unsupported dtype / sizes
+    assert L.esa_compress(fake, 4, 64, 64, fake, None, 32, fake, 32, 7, 1, 0, 0, None) == -2
+    assert L.esa_compress(fake, 4, 64, 64, fake, None, 24, fake, 24, 0, 1, 0, 0, None) == -2
+    assert L.esa_compress(fake, 4, 64, 32, fake, None, 32, fake, 32, 0, 1, 0, 0, None) == -1     # ldx < d_in
+    assert L.esa_compress(None, 4, 64, 64, fake, None, 32, fake, 32, 0, 1, 0, 0, None) == -1     # null x
+    assert L.esa_compress(odd, 4, 64, 64, fake, None, 32, fake, 32, 0, 1, 0, 0, None) == -1      # misaligned
+    assert L.esa_compress(None, 0, 64, 64, None, None, 32, None, 32, 0, 1, 0, 0, None) == 0      # empty: no-op
+    assert b"esa_compress" in L.esa_last_error()
+    # score: bad range, missing workspace
+    assert L.esa_score(fake, 4, fake, 10, 5, 32, 0, fake, 0, 1, 0, 0, 0, fake, 1 << 20, None) == -1
+    assert L.esa_score(fake, 4, fake, 0, 100, 32, 0, fake, 0, 1, 0, 0, 0, None, 0, None) == -3
+    assert L.esa_score(fake, 4, fake, 0, 100, 32, 0, fake, 0, 1, 0, 0, 0, fake, 8, None) == -3
+    assert L.esa_score(fake, 4, fake, 7, 7, 32, 0, fake, 0, 1, 0, 0, 0, None, 0, None) == 0       # empty middle
+    # top-k
+    assert L.esa_select_topk(fake, -1, 4, 0, fake, 1, 0, 0, fake, 1 << 20, None) == -1
+    assert L.esa_select_topk(fake, 100, 4, 2**31 - 50, fake, 1, 0, 0, fake, 1 << 20, None) == -1  # positions overflow int32
+    assert L.esa_select_topk(fake, 100000, 4, 0, fake, 1, 0, 0, fake, 16, None) == -3
+    assert L.esa_select_topk(fake, 0, 4, 0, fake, 1, 0, 0, None, 0, None) == 0
+    assert L.esa_select_topk_workspace_bytes(128384, 2048, 1) >= 3 * 2048 * 4
+    # gather
+    assert L.esa_gather_kv(fake, fake, 10, fake, 4, 2, 64, fake, fake, 0, 1, 0, 0, 0, None) == -1  # tok_stride < row
+    assert L.esa_gather_kv(fake, fake, 128, None, 4, 2, 64, fake, fake, 0, 1, 0, 0, 0, None) == -1
+    assert L.esa_gather_kv(fake, fake, 128, fake, 0, 2, 64, fake, fake, 0, 1, 0, 0, 0, None) == 0
+    # attend: H not a multiple of H_kv, unsupported head size, more selected than middle tokens
+    args = lambda h, h_kv, d, n_sel, t0: (fake, 8, h, h_kv, d, fake, fake, h_kv * d, t0, 4, 8, fake, fake, n_sel,
+                                           ctypes.c_float(0.1), fake, None, 0, 1, 0, 0, 0, 0, fake, 1 << 20, None)
+    assert L.esa_attend(*args(6, 4, 64, 0, 100)) == -1
+    assert L.esa_attend(*args(4, 2, 48, 0, 100)) == -2
+    assert L.esa_attend(*args(4, 2, 64, 200, 100)) == -1
+    assert b"middle tokens" in L.esa_last_error()
