@@ -13,8 +13,9 @@ Recipe (per batch element):
     the key alpha_i * (u P_k), where P = pinv(W) is the least-norm pre-image map of
     the stored weights, i.e. (u P) W = u.  The compressed needle keys are
     therefore aligned with the chunk's mean compressed query.
-  * cold keys: 0.25 * N(0,1) rows used by test harnesses to clear a band of
-    near-tied scores (they decide which rows to replace; this module only draws).
+  * push_keys_down: adds a small multiple of the pre-image of -u to chosen key rows; test
+    harnesses use it to clear a band of near-tied scores below a selection boundary (they
+    decide which rows; this module only edits the data).
 Values are produced in fp32 and stored as fp32 or as bf16 bit patterns (uint16,
 round-to-nearest-even).
 """
@@ -31,7 +32,7 @@ from .configs import EsaConfig, segment_bounds, chunk_starts
 
 ROW_BLOCK = 1024
 
-_T_Q, _T_K, _T_V, _T_WQ, _T_WK, _T_DIR, _T_POS, _T_AMP, _T_COLD = range(1, 10)
+_T_Q, _T_K, _T_V, _T_WQ, _T_WK, _T_DIR, _T_POS, _T_AMP = range(1, 9)
 
 
 # ----------------------------------------------------------------------------- storage
@@ -144,14 +145,35 @@ def needle_plan(cfg: EsaConfig, batch: int = 0) -> NeedlePlan:
     return plan
 
 
-def cold_key_rows(cfg: EsaConfig, batch: int, positions, generation: int = 0) -> np.ndarray:
-    """Replacement key rows (storage form, [n, H_kv, d]) far below any selection boundary."""
-    positions = np.asarray(positions, dtype=np.int64)
-    out = np.empty((positions.shape[0], cfg.d_K), dtype=np.float32)
-    for i, p in enumerate(positions):
-        out[i] = 0.25 * _stream(cfg.seed, _T_COLD, batch, int(p), generation).standard_normal(
-            cfg.d_K, dtype=np.float32)
-    return to_storage(out, cfg.dtype).reshape(-1, cfg.H_kv, cfg.d)
+_PINV_CACHE: Dict[tuple, np.ndarray] = {}
+
+
+def _pinv_wk(cfg: EsaConfig) -> np.ndarray:
+    key = (cfg.seed, cfg.dtype, cfg.d_K, cfg.d_c)
+    if key not in _PINV_CACHE:
+        _PINV_CACHE[key] = np.linalg.pinv(storage_to_f64(make_weights(cfg)[1], cfg.dtype))
+    return _PINV_CACHE[key]
+
+
+def push_keys_down(cfg: EsaConfig, batch: int, key_rows: np.ndarray, away_from, plan: NeedlePlan,
+                   delta: float) -> np.ndarray:
+    """Stored key rows [n, H_kv, d] with a small planted component added, re-rounded to storage.
+
+    Row i gets the pre-image of -delta * u for every chunk start t0 in away_from[i] that owns a
+    planted direction u.  All queries of that chunk share the component +beta * u in compressed
+    space, so the row's compressed score drops for every one of them (by delta * (beta + noise)),
+    while for other chunks the change is a small random perturbation.  Test harnesses use this to
+    open a gap below a selection boundary; which rows to push is their decision.
+    """
+    rows = storage_to_f64(key_rows, cfg.dtype).reshape(-1, cfg.d_K)
+    p_k = _pinv_wk(cfg)
+    for i in range(rows.shape[0]):
+        push = np.zeros(cfg.d_c)
+        for t0 in away_from[i]:
+            if t0 in plan.direction:
+                push -= delta * plan.direction[t0]
+        rows[i] += push @ p_k
+    return to_storage(rows.astype(np.float32), cfg.dtype).reshape(-1, cfg.H_kv, cfg.d)
 
 
 # ----------------------------------------------------------------------------- the layer

@@ -3,48 +3,55 @@
 Adjacent order statistics of the importance score near rank k are closer together than
 the rounding differences between an fp32-accumulating GPU kernel and float64, so the
 selected *set* is only well defined if rank k and rank k+1 are separated.  For every
-step under test, tokens ranked below k whose score lies within `tau` of the k-th score are
-replaced by cold keys (drawn by the input generator), which land far below every boundary.
-A replaced token may have been selected by another step, which moves that step's boundary
-by one rank, so the procedure repeats until no step has a token inside its band.
+step under test, tokens ranked below k whose score lies within `tau` of the k-th score get
+their key pushed (by the input generator) against the direction that step's queries share:
+their score for that step drops, while other steps see only a small random change.  A push can
+still move a token across another step's boundary, so the procedure repeats, with a growing
+push, until no step has a token inside its band.
 """
 from __future__ import annotations
 
 import numpy as np
 
-from esa_inputs import cold_key_rows, segment_bounds
+from esa_inputs import push_keys_down, segment_bounds
 from . import esa_oracle as orc
 
 
-def plant_gap(layer, steps, tau: float, max_rounds: int = 20):
+def plant_gap(layer, steps, tau: float, max_rounds: int = 30):
     """Modify layer.K in place.  `steps` = chunk start positions to protect.
 
-    Returns (sorted array of replaced positions, compressed keys K' as float64 [S, d_c]).
+    Returns (sorted array of modified positions, compressed keys K' as float64 [S, d_c]).
+    Steps without a planted direction cannot be protected this way and raise.
     """
     cfg = layer.cfg
     W_q = orc.widen(layer.W_q, cfg.dtype)
     W_k = orc.widen(layer.W_k, cfg.dtype)
     kc = orc.compress(orc.widen(layer.K, cfg.dtype), W_k, None, cfg.dtype)
     q_lo = getattr(layer, "q_row0", 0)
-    replaced = set()
+    touched = set()
     for rnd in range(max_rounds):
-        bad = set()
+        bad = {}
         for t0 in steps:
             i_end, l_start = segment_bounds(t0, cfg.l_I, cfg.l_L)
             n_mid = l_start - i_end
             if n_mid <= cfg.k:
                 continue
+            if t0 not in layer.plan.direction:
+                raise ValueError("step %d has no planted direction to push against" % t0)
             t1 = min(t0 + cfg.l_C, cfg.S)
             qc = orc.compress(orc.widen(layer.Q[t0 - q_lo:t1 - q_lo], cfg.dtype), W_q, None, cfg.dtype)
             F = orc.importance(qc, kc[i_end:l_start])
             order = np.argsort(-F, kind="stable")
             f_k = F[order[cfg.k - 1]]
             below = order[cfg.k:]
-            bad.update((below[F[below] > f_k - tau] + i_end).tolist())
+            for p in (below[F[below] > f_k - tau] + i_end).tolist():
+                bad.setdefault(p, []).append(t0)
         if not bad:
-            return np.array(sorted(replaced), dtype=np.int64), kc
+            return np.array(sorted(touched), dtype=np.int64), kc
         pos = np.array(sorted(bad), dtype=np.int64)
-        layer.K[pos] = cold_key_rows(cfg, layer.batch, pos, generation=rnd)
+        delta = (2.0 * tau / layer.plan.beta) * 2.0 ** min(rnd, 12)
+        layer.K[pos] = push_keys_down(cfg, layer.batch, layer.K[pos], [bad[p] for p in pos.tolist()],
+                                      layer.plan, delta)
         kc[pos] = orc.compress(orc.widen(layer.K[pos], cfg.dtype), W_k, None, cfg.dtype)
-        replaced.update(pos.tolist())
+        touched.update(pos.tolist())
     raise RuntimeError("planted gap did not converge")

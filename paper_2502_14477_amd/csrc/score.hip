@@ -74,6 +74,208 @@ __global__ __launch_bounds__(256) void score_fma(const T* __restrict__ qc, int l
   }
 }
 
+
+// ------------------------------------------------------------------------------------------ MFMA (bf16, d_c = 128)
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+// v_mfma_f32_32x32x16_bf16 computes D[32x32] += A[32x16] B[16x32].  Lane l supplies eight
+// consecutive reduction elements of A row l%32 and of B column l%32 (which eight depends only on
+// l/32, identically for A and B), and owns D[8*(v/4) + 4*(l/32) + v%4][l%32] in register v.
+//
+// Here A rows are current tokens (queries), B columns are middle tokens.  A workgroup of four
+// waves keeps up to 512 compressed queries in registers (128 per wave, as A fragments for the whole
+// d_c = 128) and streams its share of K' past them in tiles of 32 tokens, so K' is read from
+// memory once per sweep and Q' once per workgroup.  With a token per lane, the column maximum of
+// Eq. 4 is an in-lane reduction over the accumulator registers plus one exchange between the two
+// half-waves; the row maximum is kept per register across all tiles and reduced across lanes once.
+constexpr int kDc = 128;
+constexpr int kKSteps = kDc / 16;        // MFMA reduction steps per tile
+constexpr int kMT = 4;                   // 32-query tiles per wave
+constexpr int kQPerWave = 32 * kMT;
+constexpr int kQPerBlock = 4 * kQPerWave;
+constexpr int kMaxTilesPerBlock = 64;    // 2048 tokens: bounds the LDS column-maximum buffer
+
+__device__ __forceinline__ void load_tok_frags(bf16x8 (&b)[kKSteps], const bf16_t* __restrict__ kmid, int64_t n,
+                                               int64_t tile, int r, int hi) {
+  int64_t tok = tile * 32 + r;
+  tok = tok < n ? tok : n - 1;           // a repeated token changes no maximum and is never stored
+  const bf16_t* p = kmid + tok * kDc + hi * 8;
+#pragma unroll
+  for (int ks = 0; ks < kKSteps; ++ks) b[ks] = *(const bf16x8*)(p + ks * 16);
+}
+
+// PASS 0: row maxima into mu_keys.  PASS 1: F into score.
+template <int PASS>
+__global__ __launch_bounds__(256) void score_mfma_bf16(const bf16_t* __restrict__ qc, int l_c,
+                                                       const bf16_t* __restrict__ kc, int64_t m_lo, int64_t n,
+                                                       uint32_t* __restrict__ mu_keys, float* __restrict__ score,
+                                                       int64_t q_bs, int64_t kc_bs, int64_t score_bs,
+                                                       int tiles_per_block) {
+  extern __shared__ float fpart[];       // PASS 1: [4 waves][tiles_per_block*32] column maxima
+  const int b = blockIdx.y;
+  const bf16_t* q = qc + (int64_t)b * q_bs;
+  const bf16_t* kmid = kc + (int64_t)b * kc_bs + m_lo * (int64_t)kDc;
+  uint32_t* mu = mu_keys + (int64_t)b * l_c;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 31, hi = lane >> 5;
+  const int64_t n_tiles = (n + 31) / 32;
+  const int64_t tile0 = (int64_t)blockIdx.x * tiles_per_block;
+  const int64_t tile1 = (tile0 + tiles_per_block) < n_tiles ? (tile0 + tiles_per_block) : n_tiles;
+  const int span = tiles_per_block * 32;
+
+  for (int qb = 0; qb * kQPerBlock < l_c; ++qb) {
+    const int q0 = qb * kQPerBlock + wave * kQPerWave;
+    int n_mt = (l_c - q0 + 31) / 32;     // 32-query tiles of this wave that hold at least one query
+    n_mt = n_mt < 0 ? 0 : (n_mt > kMT ? kMT : n_mt);
+
+    bf16x8 a[kMT][kKSteps];
+    float aux[kMT][16];                  // PASS 0: running row maxima.  PASS 1: mu of the lane's rows.
+#pragma unroll
+    for (int mt = 0; mt < kMT; ++mt) {
+      const int row = q0 + 32 * mt + r;
+      const bool ok = row < l_c;
+      const bf16_t* p = q + (int64_t)(ok ? row : 0) * kDc + hi * 8;
+#pragma unroll
+      for (int ks = 0; ks < kKSteps; ++ks) {
+        bf16x8 v = *(const bf16x8*)(p + ks * 16);
+        if (!ok) v = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+        a[mt][ks] = v;
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        if (PASS == 0) {
+          aux[mt][v] = -INFINITY;
+        } else {
+          const int qrow = q0 + 32 * mt + 8 * (v / 4) + 4 * hi + (v % 4);
+          aux[mt][v] = (qrow < l_c) ? ordered_key_to_f32(mu[qrow]) : INFINITY;
+        }
+      }
+    }
+
+    bf16x8 bcur[kKSteps], bnext[kKSteps];
+    if (tile0 < tile1) load_tok_frags(bcur, kmid, n, tile0, r, hi);
+    for (int64_t t = tile0; t < tile1; ++t) {
+      if (t + 1 < tile1) load_tok_frags(bnext, kmid, n, t + 1, r, hi);
+      f32x16 acc[kMT];
+#pragma unroll
+      for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < kKSteps; ++ks)
+#pragma unroll
+        for (int mt = 0; mt < kMT; ++mt)
+          if (mt < n_mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][ks], bcur[ks], acc[mt], 0, 0, 0);
+      if (PASS == 0) {
+#pragma unroll
+        for (int mt = 0; mt < kMT; ++mt)
+          if (mt < n_mt) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) aux[mt][v] = fmaxf(aux[mt][v], acc[mt][v]);
+          }
+      } else {
+        float best = -INFINITY;
+#pragma unroll
+        for (int mt = 0; mt < kMT; ++mt)
+          if (mt < n_mt) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) best = fmaxf(best, acc[mt][v] - aux[mt][v]);
+          }
+        best = fmaxf(best, __shfl_xor(best, 32, 64));
+        if (hi == 0) {
+          float* slot = &fpart[wave * span + (int)(t - tile0) * 32 + r];
+          *slot = (qb == 0) ? best : fmaxf(*slot, best);
+        }
+      }
+#pragma unroll
+      for (int ks = 0; ks < kKSteps; ++ks) bcur[ks] = bnext[ks];
+    }
+
+    if (PASS == 0) {
+#pragma unroll
+      for (int mt = 0; mt < kMT; ++mt)
+        if (mt < n_mt) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            float m = aux[mt][v];
+#pragma unroll
+            for (int off = 16; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+            const int qrow = q0 + 32 * mt + 8 * (v / 4) + 4 * hi + (v % 4);
+            if (r == 0 && qrow < l_c && tile0 < tile1) atomicMax(&mu[qrow], ordered_key(m));
+          }
+        }
+    }
+  }
+
+  if (PASS == 1) {
+    __syncthreads();
+    for (int i = threadIdx.x; i < span; i += 256) {
+      const int64_t m = tile0 * 32 + i;
+      if (m < n && m < tile1 * 32) {
+        const float f = fmaxf(fmaxf(fpart[i], fpart[span + i]), fmaxf(fpart[2 * span + i], fpart[3 * span + i]));
+        score[(int64_t)b * score_bs + m] = f;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------ decode (l_c = 1)
+// One current token: S is a matrix-vector product over the whole compressed-key cache, pure HBM
+// streaming.  LPR lanes share a K' row (16 bytes each), so a wave reads 64*16 contiguous bytes per
+// step.  Writes S and folds its maximum into mu; score_sub_mu then forms F = S - mu.
+template <int LPR>
+__global__ __launch_bounds__(256) void score_gemv_bf16(const bf16_t* __restrict__ qc, const bf16_t* __restrict__ kc,
+                                                       int64_t m_lo, int64_t n, uint32_t* __restrict__ mu_keys,
+                                                       float* __restrict__ raw, int64_t q_bs, int64_t kc_bs,
+                                                       int64_t raw_bs) {
+  constexpr int kDcv = LPR * 8;
+  constexpr int kRowsPerStep = 256 / LPR;
+  constexpr int kSteps = 16;
+  __shared__ float red[4];
+  const int b = blockIdx.y;
+  const bf16_t* kmid = kc + (int64_t)b * kc_bs + m_lo * (int64_t)kDcv;
+  const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+  float qv[8];
+  {
+    const uint4 u = *(const uint4*)(qc + (int64_t)b * q_bs + sub * 8);
+    const bf16_t* pq = (const bf16_t*)&u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) qv[i] = bf16_to_f32(pq[i]);
+  }
+  float best = -INFINITY;
+  const int64_t row0 = (int64_t)blockIdx.x * (kRowsPerStep * kSteps);
+#pragma unroll 4
+  for (int it = 0; it < kSteps; ++it) {
+    const int64_t row = row0 + it * kRowsPerStep + grp;
+    float s = 0.f;
+    if (row < n) {
+      const uint4 u = *(const uint4*)(kmid + row * kDcv + sub * 8);
+      const bf16_t* pk = (const bf16_t*)&u;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s = __fmaf_rn(qv[i], bf16_to_f32(pk[i]), s);
+    }
+#pragma unroll
+    for (int off = LPR / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (row < n) {
+      if (sub == 0) raw[(int64_t)b * raw_bs + row] = s;
+      best = fmaxf(best, s);
+    }
+  }
+  best = wave_max(best);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = best;
+  __syncthreads();
+  if (threadIdx.x == 0)
+    atomicMax(&mu_keys[b], ordered_key(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]))));
+}
+
+__global__ void score_sub_mu(float* __restrict__ raw, int64_t n, const uint32_t* __restrict__ mu_keys, int64_t raw_bs) {
+  const float mu = ordered_key_to_f32(mu_keys[blockIdx.y]);
+  float* p = raw + (int64_t)blockIdx.y * raw_bs;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+    p[i] = p[i] - mu;
+}
+
 // Eq. 8: out[j] = max(in[max(j-eps,0) .. min(j+eps,n-1)]).
 __global__ void proximity_maxpool(const float* __restrict__ in, float* __restrict__ out, int64_t n, int eps,
                                   int64_t in_bs, int64_t out_bs) {
@@ -108,26 +310,51 @@ int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, in
     raw_bs = (int64_t)(align_up((size_t)n * 4, 256) / 4);
   }
   fill_u32<<<(l_c * batch + 255) / 256, 256, 0, st>>>(mu, (int64_t)l_c * batch, kOrderedKeyOfMinusInf);
-  const dim3 grid((unsigned)((n + kGTok - 1) / kGTok), batch);
-  const size_t smem = (size_t)(kGTok * (d_c + 1) + 4 * kGTok) * sizeof(float);
-  if (smem > 65536) {   // d_c > 240: raise the dynamic LDS limit of the four instantiations
-    const void* fns[] = {(const void*)score_fma<bf16_t, 0>, (const void*)score_fma<bf16_t, 1>,
-                         (const void*)score_fma<float, 0>, (const void*)score_fma<float, 1>};
-    for (const void* f : fns) {
-      hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-      if (e != hipSuccess) return hip_failed(e, "hipFuncSetAttribute(score_fma)");
-    }
-  }
-  if (dtype == ESA_BF16) {
-    score_fma<bf16_t, 0><<<grid, 256, smem, st>>>((const bf16_t*)qc, l_c, (const bf16_t*)kc_cache, m_lo, n, d_c, mu,
-                                                  raw, q_bs, kc_bs, raw_bs);
-    score_fma<bf16_t, 1><<<grid, 256, smem, st>>>((const bf16_t*)qc, l_c, (const bf16_t*)kc_cache, m_lo, n, d_c, mu,
-                                                  raw, q_bs, kc_bs, raw_bs);
+  const bool vec_ok = dtype == ESA_BF16 && (((uintptr_t)qc | (uintptr_t)kc_cache) % 16 == 0) && q_bs % 8 == 0 &&
+                      kc_bs % 8 == 0;
+  if (vec_ok && l_c == 1 && (d_c == 64 || d_c == 128 || d_c == 256)) {
+    const int lpr = d_c / 8;
+    const int rows_per_block = (256 / lpr) * 16;
+    const dim3 grid((unsigned)((n + rows_per_block - 1) / rows_per_block), batch);
+    const bf16_t* q = (const bf16_t*)qc;
+    const bf16_t* k = (const bf16_t*)kc_cache;
+    if (lpr == 8) score_gemv_bf16<8><<<grid, 256, 0, st>>>(q, k, m_lo, n, mu, raw, q_bs, kc_bs, raw_bs);
+    else if (lpr == 16) score_gemv_bf16<16><<<grid, 256, 0, st>>>(q, k, m_lo, n, mu, raw, q_bs, kc_bs, raw_bs);
+    else score_gemv_bf16<32><<<grid, 256, 0, st>>>(q, k, m_lo, n, mu, raw, q_bs, kc_bs, raw_bs);
+    const int blocks = (int)((n + 1023) / 1024 < 2048 ? (n + 1023) / 1024 : 2048);
+    score_sub_mu<<<dim3(blocks, batch), 256, 0, st>>>(raw, n, mu, raw_bs);
+  } else if (vec_ok && d_c == kDc) {
+    const int64_t n_tiles = (n + 31) / 32;
+    int64_t per = (n_tiles + 255) / 256;                       // about one workgroup per compute unit
+    per = per < 1 ? 1 : (per > kMaxTilesPerBlock ? kMaxTilesPerBlock : per);
+    const dim3 grid((unsigned)((n_tiles + per - 1) / per), batch);
+    const size_t lds = (size_t)4 * per * 32 * sizeof(float);
+    score_mfma_bf16<0><<<grid, 256, 0, st>>>((const bf16_t*)qc, l_c, (const bf16_t*)kc_cache, m_lo, n, mu, raw, q_bs,
+                                             kc_bs, raw_bs, (int)per);
+    score_mfma_bf16<1><<<grid, 256, lds, st>>>((const bf16_t*)qc, l_c, (const bf16_t*)kc_cache, m_lo, n, mu, raw, q_bs,
+                                               kc_bs, raw_bs, (int)per);
   } else {
-    score_fma<float, 0><<<grid, 256, smem, st>>>((const float*)qc, l_c, (const float*)kc_cache, m_lo, n, d_c, mu,
-                                                 raw, q_bs, kc_bs, raw_bs);
-    score_fma<float, 1><<<grid, 256, smem, st>>>((const float*)qc, l_c, (const float*)kc_cache, m_lo, n, d_c, mu,
-                                                 raw, q_bs, kc_bs, raw_bs);
+    const dim3 grid((unsigned)((n + kGTok - 1) / kGTok), batch);
+    const size_t smem = (size_t)(kGTok * (d_c + 1) + 4 * kGTok) * sizeof(float);
+    if (smem > 65536) {   // d_c > 240: raise the dynamic LDS limit of the four instantiations
+      const void* fns[] = {(const void*)score_fma<bf16_t, 0>, (const void*)score_fma<bf16_t, 1>,
+                           (const void*)score_fma<float, 0>, (const void*)score_fma<float, 1>};
+      for (const void* f : fns) {
+        hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return hip_failed(e, "hipFuncSetAttribute(score_fma)");
+      }
+    }
+    if (dtype == ESA_BF16) {
+      score_fma<bf16_t, 0><<<grid, 256, smem, st>>>((const bf16_t*)qc, l_c, (const bf16_t*)kc_cache, m_lo, n, d_c, mu,
+                                                    raw, q_bs, kc_bs, raw_bs);
+      score_fma<bf16_t, 1><<<grid, 256, smem, st>>>((const bf16_t*)qc, l_c, (const bf16_t*)kc_cache, m_lo, n, d_c, mu,
+                                                    raw, q_bs, kc_bs, raw_bs);
+    } else {
+      score_fma<float, 0><<<grid, 256, smem, st>>>((const float*)qc, l_c, (const float*)kc_cache, m_lo, n, d_c, mu,
+                                                   raw, q_bs, kc_bs, raw_bs);
+      score_fma<float, 1><<<grid, 256, smem, st>>>((const float*)qc, l_c, (const float*)kc_cache, m_lo, n, d_c, mu,
+                                                   raw, q_bs, kc_bs, raw_bs);
+    }
   }
   if (eps > 0) {
     const int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);

@@ -125,9 +125,10 @@ def _assert_compressed_close(got, want, x, W, b, dtype):
         return
     exact = x.reshape(x.shape[0], -1) @ W + (0.0 if b is None else b[None, :])
     diff = got != want
-    # a mismatch is a rounding-boundary flip: still within one bf16 step of the float64 value, and rare
-    assert np.all(np.abs(got - exact)[diff] <= bf16_ulp(exact)[diff] * 0.5000001 + 1e-4 * np.abs(exact)[diff])
-    assert np.all(np.abs(got - want)[diff] <= bf16_ulp(want)[diff] * 1.0000001)
+    # a mismatch is a rounding-boundary flip: the fp32-accumulated sum (absolute error ~ sqrt(d_in) * 2^-24 for
+    # unit-scale terms) fell on the other side of a bf16 midpoint; still half a step from the float64 value, and rare
+    assert np.all(np.abs(got - exact)[diff] <= bf16_ulp(exact)[diff] * 0.5 + 4e-6)
+    assert np.all(np.abs(got - want)[diff] <= bf16_ulp(want)[diff] + 4e-6)
     assert diff.mean() < 5e-3, diff.mean()
 
 
