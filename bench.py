@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the ESA hot path on one MI355X.
+
+A "step" is one pass of the whole hot path for one chunk of current tokens: compress the
+chunk's queries and keys, score every middle token, pick the top-k, gather their keys/values
+and attend over [I, M_k, L, C].  The default workload is the metric's: the Llama-3-8B-shaped
+layer at 128k context (configuration 3), steady-state last chunk (t0 = 130560, 128384 middle
+tokens).  Inputs (Q, K, V, the compressed-key cache of the preceding tokens, weights) are
+resident in HBM before the timed region.
+
+Prints ONE JSON line: the contract fields plus `roofline` (dominant call, from HIP events
+recorded live on the launch stream) and `cpu_baseline` (the float64 oracle timed on the host
+cores on the same step).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def algorithmic_work(cfg, t0, n_mid, k_eff, l_c):
+    """Per-step algorithmic FLOPs / bytes of each call (Appendix A of the paper; causal part at half)."""
+    d_Hq, d_K, d_c, esz = cfg.H * cfg.d, cfg.H_kv * cfg.d, cfg.d_c, 2 if cfg.dtype == "bf16" else 4
+    i_end = min(cfg.l_I, t0)
+    n_local = t0 - max(t0 - cfg.l_L, i_end)
+    keys_eff = i_end + k_eff + n_local + (l_c + 1) / 2.0
+    return {
+        "compress": {"flops": 2.0 * l_c * (d_Hq + d_K) * d_c,
+                     "bytes": (l_c * (d_Hq + d_K) + (d_Hq + d_K) * d_c + 2 * l_c * d_c) * esz},
+        "score": {"flops": 2.0 * l_c * n_mid * d_c, "bytes": n_mid * d_c * esz + 4 * n_mid},
+        "select": {"flops": 0.0, "bytes": 4.0 * n_mid + 4.0 * k_eff},
+        "gather": {"flops": 0.0, "bytes": 4.0 * k_eff * d_K * esz},
+        "attend": {"flops": 4.0 * d_Hq * l_c * keys_eff,
+                   "bytes": (2 * l_c * d_Hq + 2 * (i_end + k_eff + n_local + l_c) * d_K) * esz},
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="C3", help="C2, C3 or C5 (prefill), C4 (decode)")
+    ap.add_argument("--seq", type=int, default=0, help="override the sequence length (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_2502_14477_amd as esa
+    from esa_inputs import get_config, make_layer, segment_bounds, chunk_starts
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = get_config(args.config)
+    if args.seq:
+        cfg = cfg.scaled(S=args.seq)
+    t0 = chunk_starts(cfg)[-1]
+    l_c = min(cfg.l_C, cfg.S - t0)
+    i_end, l_start = segment_bounds(t0, cfg.l_I, cfg.l_L)
+    n_mid = l_start - i_end
+    k_eff = min(cfg.k, n_mid)
+
+    t_gen = time.time()
+    layer = make_layer(cfg, q_rows=(t0, t0 + l_c))
+    layer.q_row0 = t0
+
+    def dev(a):
+        if cfg.dtype == "f32":
+            return torch.from_numpy(a).cuda()
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+
+    Q, K, V, W_q, W_k = dev(layer.Q), dev(layer.K), dev(layer.V), dev(layer.W_q), dev(layer.W_k)
+    # state left by the preceding steps: compressed keys of every earlier token
+    kc = torch.zeros((cfg.S, cfg.d_c), dtype=K.dtype, device="cuda")
+    for r0 in range(0, t0, 16384):
+        esa.esa_compress(K[r0:min(r0 + 16384, t0)], W_k, out=kc[r0:min(r0 + 16384, t0)])
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+
+    calls = ("compress", "score", "select", "gather", "attend")
+
+    def step(events=None):
+        def mark(i):
+            if events is not None:
+                events[i].record()
+        mark(0)
+        qc = esa.esa_compress(Q, W_q)
+        esa.esa_compress(K[t0:t0 + l_c], W_k, out=kc[t0:t0 + l_c])
+        mark(1)
+        if n_mid > cfg.k:
+            score = esa.esa_score(qc, kc, i_end, l_start)
+        else:
+            score = torch.zeros(max(n_mid, 1), dtype=torch.float32, device="cuda")[:n_mid]
+        mark(2)
+        idx = esa.esa_select_topk(score, cfg.k, base=i_end)
+        mark(3)
+        ks, vs = esa.esa_gather_kv(K, V, idx)
+        mark(4)
+        out = esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks, vs)
+        mark(5)
+        return out
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = 1e3 * elapsed / args.steps
+
+    # per-call durations from HIP events on the launch stream (torch's current stream)
+    per_call = {c: [] for c in calls}
+    for _ in range(max(5, min(args.steps, 30))):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+        step(ev)
+        torch.cuda.synchronize()
+        for i, c in enumerate(calls):
+            per_call[c].append(ev[i].elapsed_time(ev[i + 1]))
+    call_ms = {c: float(np.mean(v)) for c, v in per_call.items()}
+
+    work = algorithmic_work(cfg, t0, n_mid, k_eff, l_c)
+    per_call_report = {}
+    for c in calls:
+        us = 1e3 * call_ms[c]
+        rep = {"us": round(us, 2)}
+        if work[c]["flops"]:
+            rep["tflops"] = round(work[c]["flops"] / (us * 1e-6) / 1e12, 2)
+        rep["gbs"] = round(work[c]["bytes"] / (us * 1e-6) / 1e9, 1)
+        per_call_report[c] = rep
+    dominant = max(calls, key=lambda c: call_ms[c])
+    if work[dominant]["flops"]:
+        achieved = work[dominant]["flops"] / (call_ms[dominant] * 1e-3) / 1e12
+        roofline = {"kernel": "esa_" + dominant, "bound": "mfma", "achieved": round(achieved, 2),
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                    "traffic": None}
+    else:
+        achieved = work[dominant]["bytes"] / (call_ms[dominant] * 1e-3) / 1e9
+        roofline = {"kernel": "esa_" + dominant, "bound": "hbm", "achieved": round(achieved, 1),
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4),
+                    "traffic": None}
+    roofline["per_call"] = per_call_report
+    step_flops = sum(w["flops"] for w in work.values())
+    roofline["step_tflops"] = round(step_flops / (ms_per_step * 1e-3) / 1e12, 2)
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        cpu_baseline = cpu_oracle_baseline(layer, cfg, t0, l_c)
+
+    unit = "tokens/s"
+    value = l_c / (ms_per_step * 1e-3)
+    result = {
+        "metric": "ESA prefill tokens/s per layer at 128k ctx" if not cfg.decode else "ESA decode step",
+        "value": round(value, 1), "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": "%s: H=%d H_kv=%d d=%d, S=%d, chunk l_C=%d at t0=%d, l_I=%d l_L=%d k=%d d_c=%d, "
+                               "%d middle tokens; one step = compress+score+select+gather+attend for one chunk"
+                               % (cfg.name, cfg.H, cfg.H_kv, cfg.d, cfg.S, l_c, t0, cfg.l_I, cfg.l_L, cfg.k,
+                                  cfg.d_c, n_mid),
+                   "global_batch": 1, "seq_len": cfg.S, "parallelism": "single GPU"},
+        "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "setup_s": round(t_gen, 1),
+    }
+    print(json.dumps(result))
+
+
+def cpu_oracle_baseline(layer, cfg, t0, l_c):
+    """The float64 oracle, as it stands, on the same step; K' of the preceding tokens is state, not timed."""
+    import numpy as np
+    from oracle import esa_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    W_q, W_k = orc.widen(layer.W_q, cfg.dtype), orc.widen(layer.W_k, cfg.dtype)
+    K = orc.widen(layer.K, cfg.dtype)
+    V = orc.widen(layer.V, cfg.dtype)
+    q = orc.widen(layer.Q, cfg.dtype)
+    kc = np.zeros((cfg.S, cfg.d_c))
+    for r0 in range(0, t0, 16384):
+        kc[r0:min(r0 + 16384, t0)] = orc.compress(K[r0:min(r0 + 16384, t0)], W_k, None, cfg.dtype)
+    times = []
+    t_all = time.perf_counter()
+    while True:
+        ts = time.perf_counter()
+        qc = orc.compress(q, W_q, None, cfg.dtype)
+        kc[t0:t0 + l_c] = orc.compress(K[t0:t0 + l_c], W_k, None, cfg.dtype)
+        orc.esa_step(q, K[:t0 + l_c], V[:t0 + l_c], kc, qc, t0, cfg.l_I, cfg.l_L, cfg.k, 1.0 / np.sqrt(cfg.d))
+        times.append(time.perf_counter() - ts)
+        if time.perf_counter() - t_all > 12.0 or len(times) >= 5:
+            break
+    best = min(times)
+    return {"value": round(l_c / best, 1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": "the same step (one chunk of %d tokens at t0=%d), float64 numpy, best of %d runs, %.2f s each"
+                      % (l_c, t0, len(times), best)}
+
+
+if __name__ == "__main__":
+    main()

@@ -4,28 +4,10 @@
 // (t0 - l_start): everything before the chunk plus the chunk up to itself (Algorithm 1).
 #include "esa_common.h"
 #include "attend_mfma.h"
+#include "keyspace.h"
 
 namespace esa {
 namespace {
-
-struct KeySpace {
-  const char* k_cache;
-  const char* v_cache;
-  const char* k_sel;
-  const char* v_sel;
-  int64_t tok_bytes;      // cache token stride in bytes
-  int64_t sel_bytes;      // gathered-row stride in bytes
-  int64_t i_end, n_sel, l_start;
-};
-
-// Byte offset of virtual key j inside (is_sel ? the gathered buffer : the cache).
-__device__ __forceinline__ const char* key_row(const KeySpace& ks, int64_t j, bool values) {
-  if (j < ks.i_end) return (values ? ks.v_cache : ks.k_cache) + j * ks.tok_bytes;
-  j -= ks.i_end;
-  if (j < ks.n_sel) return (values ? ks.v_sel : ks.k_sel) + j * ks.sel_bytes;
-  j -= ks.n_sel;
-  return (values ? ks.v_cache : ks.k_cache) + (ks.l_start + j) * ks.tok_bytes;
-}
 
 __device__ __forceinline__ float block_max(float v, float* red) {
   v = wave_max(v);
