@@ -81,7 +81,9 @@ def main():
             return torch.from_numpy(a).cuda()
         return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
 
-    Q, K, V, W_q, W_k = dev(layer.Q), dev(layer.K), dev(layer.V), dev(layer.W_q), dev(layer.W_k)
+    Q, K, V = dev(layer.Q), dev(layer.K), dev(layer.V)
+    # weights are packed once per layer, at load time
+    W_q, W_k = esa.esa_pack_weights(dev(layer.W_q)), esa.esa_pack_weights(dev(layer.W_k))
     # state left by the preceding steps: compressed keys of every earlier token
     kc = torch.zeros((cfg.S, cfg.d_c), dtype=K.dtype, device="cuda")
     for r0 in range(0, t0, 16384):

@@ -55,18 +55,30 @@ ESA_API const char* esa_last_error(void);
 /* Host-side segment arithmetic of Section 3.1 (no GPU work): writes i_end and l_start. */
 ESA_API int esa_segments(int64_t t0, int64_t l_i, int64_t l_l, int64_t* i_end, int64_t* l_start);
 
+/* Layout of the compression weights handed to esa_compress. */
+#define ESA_W_ROWMAJOR 0      /* W [d_in, d_c], as a linear layer y = x W stores it */
+#define ESA_W_PACKED 1        /* W^T [d_c, d_in], written by esa_pack_weights: the fast path */
+
+/*
+ * One-time re-layout of a compression weight matrix (per layer, at load time; not part of a
+ * step): W [d_in, d_c] contiguous -> W_packed [d_c, d_in] contiguous, same dtype.  With packed
+ * weights both matrix-core operands of Eq. 5 are read with their reduction elements contiguous.
+ */
+ESA_API int esa_pack_weights(const void* W, int64_t d_in, int d_c, int dtype, void* W_packed, void* stream);
+
 /*
  * Eq. 5 — compression by one linear layer on the head-concatenated vector.
  *   x    [batch][n_tok, d_in]  row stride ldx, batch stride x_bs.  A [n_tok, heads, d] tensor is
  *        its own head-major concatenation (Section 3.1), so d_in = heads*d and ldx = heads*d.
- *   W    [d_in, d_c] contiguous, shared by the batch;  bias [d_c] or NULL.
+ *   W    [d_in, d_c] contiguous (w_layout = ESA_W_ROWMAJOR) or its packed form [d_c, d_in]
+ *        (ESA_W_PACKED), shared by the batch;  bias [d_c] or NULL.
  *   out  [batch][n_tok, d_c]   row stride ldo, batch stride out_bs; rounded to `dtype`
  *        (nearest-even).  Writing K' rows of the current tokens straight into the compressed-key
  *        cache is done by pointing `out` at cache row t0.
  * n_tok == 0 is a no-op.  d_c must be a multiple of 16 and at most 256.
  */
 ESA_API int esa_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx,
-                 const void* W, const void* bias, int d_c,
+                 const void* W, int w_layout, const void* bias, int d_c,
                  void* out, int64_t ldo,
                  int dtype, int batch, int64_t x_bs, int64_t out_bs, void* stream);
 

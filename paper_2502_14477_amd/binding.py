@@ -14,6 +14,7 @@ from typing import Optional, Tuple
 import torch
 
 ESA_F32, ESA_BF16 = 0, 1
+ESA_W_ROWMAJOR, ESA_W_PACKED = 0, 1
 _PKG = os.path.dirname(os.path.abspath(__file__))
 
 
@@ -42,7 +43,9 @@ def _load() -> ctypes.CDLL:
     L.esa_segments.restype = i32
     L.esa_segments.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
     L.esa_compress.restype = i32
-    L.esa_compress.argtypes = [vp, i64, i64, i64, vp, vp, i32, vp, i64, i32, i32, i64, i64, vp]
+    L.esa_pack_weights.restype = i32
+    L.esa_pack_weights.argtypes = [vp, i64, i32, i32, vp, vp]
+    L.esa_compress.argtypes = [vp, i64, i64, i64, vp, i32, vp, i32, vp, i64, i32, i32, i64, i64, vp]
     L.esa_score_workspace_bytes.restype = sz
     L.esa_score_workspace_bytes.argtypes = [i32, i64, i32, i32]
     L.esa_score.restype = i32
@@ -63,7 +66,7 @@ def _load() -> ctypes.CDLL:
 
 lib = _load()
 
-EXPORTS = ("esa_version", "esa_last_error", "esa_segments", "esa_compress", "esa_score_workspace_bytes",
+EXPORTS = ("esa_version", "esa_last_error", "esa_segments", "esa_pack_weights", "esa_compress", "esa_score_workspace_bytes",
            "esa_score", "esa_select_topk_workspace_bytes", "esa_select_topk", "esa_gather_kv",
            "esa_attend_workspace_bytes", "esa_attend")
 
@@ -121,11 +124,31 @@ def esa_segments(t0: int, l_i: int, l_l: int) -> Tuple[int, int]:
     return a.value, b.value
 
 
-def esa_compress(x: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor] = None,
-                 out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """x [B?, n_tok, heads, d] or [B?, n_tok, d_in] -> [B?, n_tok, d_c].  `out` may be a row-strided
-    view (e.g. rows t0.. of the compressed-key cache)."""
+class PackedWeights:
+    """Compression weights in the packed layout [d_c, d_in] (see esa_pack_weights)."""
+
+    def __init__(self, data: torch.Tensor, d_in: int, d_c: int):
+        self.data, self.d_in, self.d_c = data, d_in, d_c
+
+
+def esa_pack_weights(W: torch.Tensor) -> PackedWeights:
+    """W [d_in, d_c] -> packed weights; done once per layer."""
     d_in, d_c = W.shape
+    assert W.is_contiguous()
+    out = torch.empty((d_c, d_in), dtype=W.dtype, device=W.device)
+    _check(lib.esa_pack_weights(_ptr(W), d_in, d_c, _dtype(W), _ptr(out), _stream()))
+    return PackedWeights(out, d_in, d_c)
+
+
+def esa_compress(x: torch.Tensor, W, bias: Optional[torch.Tensor] = None,
+                 out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """x [B?, n_tok, heads, d] or [B?, n_tok, d_in] -> [B?, n_tok, d_c].  W is a [d_in, d_c] tensor or
+    PackedWeights.  `out` may be a row-strided view (e.g. rows t0.. of the compressed-key cache)."""
+    if isinstance(W, PackedWeights):
+        layout, d_in, d_c, W = ESA_W_PACKED, W.d_in, W.d_c, W.data
+    else:
+        layout = ESA_W_ROWMAJOR
+        d_in, d_c = W.shape
     if x.shape[-1] != d_in:
         x = x.flatten(-2)
     xb, had_batch = _batched(x, 2)
@@ -136,7 +159,7 @@ def esa_compress(x: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor] 
     else:
         ob, _ = _batched(out, 2)
         assert ob.shape == (B, n_tok, d_c) and ob.stride(2) == 1 and ob.dtype == x.dtype
-    _check(lib.esa_compress(_ptr(xb), n_tok, d_in, xb.stride(1), _ptr(W), _ptr(bias), d_c, _ptr(ob), ob.stride(1),
+    _check(lib.esa_compress(_ptr(xb), n_tok, d_in, xb.stride(1), _ptr(W), layout, _ptr(bias), d_c, _ptr(ob), ob.stride(1),
                             _dtype(x), B, xb.stride(0), ob.stride(0), _stream()))
     return ob if had_batch else ob[0]
 

@@ -3,7 +3,10 @@
 // Work decomposition.  The query heads of one KV group share keys and values, so a workgroup
 // owns 256 "rows" = (heads of one KV group) x (256/G consecutive current tokens) and one slice of
 // the virtual key sequence [I | M_k | L | C]; slices of one row tile are merged afterwards with
-// the log-sum-exp rule of Algorithm 1 (esa_attend_merge).  Four waves, 64 rows each.
+// the log-sum-exp rule of Algorithm 1 (esa_attend_merge).  Eight waves of 32 rows each, two waves
+// per SIMD, so that one wave's softmax arithmetic overlaps the other's matrix instructions; the
+// kernel stays under 256 registers per lane for that.  Workgroups are numbered so that all
+// workgroups of one (batch element, KV head) land on the same XCD and share its L2.
 //
 // Matrix-core formulation (v_mfma_f32_32x32x16_bf16, D[32x32] += A[32x16] B[16x32]; lane l feeds
 // A row l%32 / B column l%32 with eight consecutive reduction elements chosen by l/32, and owns
@@ -15,7 +18,8 @@
 // between the two half-waves, and S^T's accumulator layout is directly P^T's B-operand layout once
 // the reduction slots of the second product are assigned to keys accordingly (the V^T tile is
 // stored in LDS in that key order).  V is transposed on its way from global memory to LDS in
-// registers (4x4 blocks of bf16), K is copied as is.
+// registers (4x4 blocks of bf16), K is copied as is.  Tiles of 64 keys are double buffered in LDS:
+// one barrier per tile, the next tile's global loads in flight during the current tile's math.
 #include "attend_mfma.h"
 #include "keyspace.h"
 
@@ -30,8 +34,14 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int kD = 128;             // head size
 constexpr int kKT = 64;             // virtual keys per tile
 constexpr int kRows = 256;          // query rows per workgroup
+constexpr int kWaves = 8;
+constexpr int kThreads = 64 * kWaves;
 constexpr int kKLd = kD + 8;        // LDS row stride of the K tile in elements (272 B: conflict-free 16-byte reads)
 constexpr int kVLd = kKT + 8;       // LDS row stride of the V^T tile in elements (144 B)
+constexpr int kKElems = kKT * kKLd;
+constexpr int kVElems = kD * kVLd;
+constexpr int kStageElems = kKElems + kVElems;
+constexpr int kLdsBytes = 2 * kStageElems * 2;
 constexpr int kMaxSplits = 8;
 constexpr int kMinLc = 16;          // shorter chunks go to the plain kernel
 constexpr float kLog2e = 1.4426950408889634f;
@@ -43,9 +53,15 @@ struct AttendArgs {
   float* lse;
   float* part_o;      // [batch][n_split][l_c][h][128] unnormalised partial outputs
   float* part_ml;     // [batch][n_split][l_c][h][2]   running maximum (log2 domain) and sum
-  KeySpace ks;
-  int l_c, h, h_kv, group, qpt, n_qt, n_split;
-  int64_t n_fixed;
+  const char* k_cache;
+  const char* v_cache;
+  const char* k_sel;
+  const char* v_sel;
+  uint32_t tok_bytes, sel_bytes;    // row strides of the cache / the gathered buffers
+  uint32_t i_end, n_sel, l_start;
+  int l_c, h, h_kv, group, qpt, n_qt, n_split, batch;
+  int xcd_mapping;                  // 1: (batch, KV head) pairs are a multiple of 8
+  uint32_t n_fixed;
   float c2;           // scale * log2(e)
   int64_t q_bs, out_bs, cache_bs_bytes, sel_bs_bytes;
 };
@@ -56,191 +72,201 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return *(uint32_t*)&b;
 }
 
-__global__ __launch_bounds__(256) void attend_mfma_bf16(AttendArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16_t k_lds[kKT * kKLd];
-  __shared__ __attribute__((aligned(16))) bf16_t vt_lds[kD * kVLd];
+// Row of virtual key j: which buffer, and the byte offset inside it (branch-free).
+struct RowRef {
+  bool in_sel;
+  uint64_t off;
+};
+__device__ __forceinline__ RowRef row_ref(const AttendArgs& a, uint32_t j) {
+  const bool in_i = j < a.i_end;
+  const bool in_s = !in_i && (j < a.i_end + a.n_sel);
+  const uint32_t row = in_i ? j : (in_s ? j - a.i_end : j - a.i_end - a.n_sel + a.l_start);
+  RowRef r;
+  r.in_sel = in_s;
+  r.off = (uint64_t)row * (in_s ? a.sel_bytes : a.tok_bytes);
+  return r;
+}
+
+__global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  bf16_t* lds = (bf16_t*)lds_raw;     // [2 stages][K tile | V^T tile]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, hi = lane >> 5;
-  const int qt = blockIdx.x % a.n_qt, split = blockIdx.x / a.n_qt, g = blockIdx.y, b = blockIdx.z;
-  KeySpace ks = a.ks;
-  ks.k_cache += (int64_t)b * a.cache_bs_bytes + (int64_t)g * kD * 2;
-  ks.v_cache += (int64_t)b * a.cache_bs_bytes + (int64_t)g * kD * 2;
-  if (ks.n_sel > 0) {
-    ks.k_sel += (int64_t)b * a.sel_bs_bytes + (int64_t)g * kD * 2;
-    ks.v_sel += (int64_t)b * a.sel_bs_bytes + (int64_t)g * kD * 2;
+
+  // ---- which (batch element, KV head, row tile, key slice) is this workgroup
+  const int per_pair = a.n_qt * a.n_split;
+  int pair, inner;
+  if (a.xcd_mapping) {                 // consecutive workgroup ids go to consecutive XCDs
+    const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
+    pair = xcd + 8 * (k / per_pair);
+    inner = k % per_pair;
+  } else {
+    pair = blockIdx.x / per_pair;
+    inner = blockIdx.x % per_pair;
   }
+  const int b = pair / a.h_kv, g = pair % a.h_kv;
+  const int qt = inner % a.n_qt, split = inner / a.n_qt;
+
+  const char* kc = a.k_cache + (int64_t)b * a.cache_bs_bytes + (int64_t)g * kD * 2;
+  const char* vc = a.v_cache + (int64_t)b * a.cache_bs_bytes + (int64_t)g * kD * 2;
+  const char* ksl = a.k_sel + (a.n_sel ? (int64_t)b * a.sel_bs_bytes + (int64_t)g * kD * 2 : 0);
+  const char* vsl = a.v_sel + (a.n_sel ? (int64_t)b * a.sel_bs_bytes + (int64_t)g * kD * 2 : 0);
 
   // ---- this workgroup's rows and key slice
   const int q0 = qt * a.qpt;
   const int c_last = (q0 + a.qpt < a.l_c ? q0 + a.qpt : a.l_c) - 1;
-  const int64_t n_vis = a.n_fixed + c_last + 1;                    // keys the tile's last token sees
-  const int64_t n_tiles = (n_vis + kKT - 1) / kKT;
-  const int64_t tile_begin = n_tiles * split / a.n_split, tile_end = n_tiles * (split + 1) / a.n_split;
-  const int64_t k_end = tile_end * kKT < n_vis ? tile_end * kKT : n_vis;
+  const uint32_t n_vis = a.n_fixed + c_last + 1;                   // keys the tile's last token sees
+  const uint32_t n_tiles = (n_vis + kKT - 1) / kKT;
+  const uint32_t tile_begin = (uint32_t)((uint64_t)n_tiles * split / a.n_split);
+  const uint32_t tile_end = (uint32_t)((uint64_t)n_tiles * (split + 1) / a.n_split);
+  const uint32_t k_end = tile_end * kKT < n_vis ? tile_end * kKT : n_vis;
 
+  // ---- this wave's 32 rows: one head, 32 consecutive current tokens, one per lane (both half-waves)
   const int tph = a.qpt / 32;                                      // 32-row tiles per head
-  int head[2], c[2];
-  bool c_ok[2];
-  int64_t lim[2];                                                  // first virtual key this lane's query may NOT see
-  bf16x8 qf[2][kD / 16];
+  const int head = g * a.group + wave / tph;
+  const int c = q0 + (wave % tph) * 32 + r;
+  const bool c_ok = c < a.l_c;
+  const int cc = c_ok ? c : a.l_c - 1;                             // rows past the chunk repeat its last token
+  const uint32_t vis = a.n_fixed + cc + 1;
+  const uint32_t lim = vis < k_end ? vis : k_end;                  // first virtual key this lane's query may NOT see
+  const uint32_t lim_lo = __shfl(lim, 0, 64);                      // smallest limit in the wave (r = 0)
+  bf16x8 qf[kD / 16];
+  {
+    const bf16_t* qp = a.q + (int64_t)b * a.q_bs + ((int64_t)cc * a.h + head) * kD + hi * 8;
 #pragma unroll
-  for (int nq = 0; nq < 2; ++nq) {
-    const int nt = 2 * wave + nq;
-    head[nq] = g * a.group + nt / tph;
-    c[nq] = q0 + (nt % tph) * 32 + r;
-    c_ok[nq] = c[nq] < a.l_c;
-    const int cc = c_ok[nq] ? c[nq] : a.l_c - 1;                   // rows past the chunk repeat its last token
-    const int64_t vis = a.n_fixed + cc + 1;
-    lim[nq] = vis < k_end ? vis : k_end;
-    const bf16_t* qp = a.q + (int64_t)b * a.q_bs + ((int64_t)cc * a.h + head[nq]) * kD + hi * 8;
-#pragma unroll
-    for (int ks16 = 0; ks16 < kD / 16; ++ks16) qf[nq][ks16] = *(const bf16x8*)(qp + ks16 * 16);
+    for (int ks16 = 0; ks16 < kD / 16; ++ks16) qf[ks16] = *(const bf16x8*)(qp + ks16 * 16);
   }
-  const int64_t lim_lo0 = __shfl(lim[0], 0, 64), lim_lo1 = __shfl(lim[1], 0, 64);
-  const int64_t lim_lo = lim_lo0 < lim_lo1 ? lim_lo0 : lim_lo1;    // smallest limit in the wave (r = 0)
 
-  f32x16 o[2][4];
+  f32x16 o[4];
 #pragma unroll
-  for (int nq = 0; nq < 2; ++nq)
+  for (int md = 0; md < 4; ++md)
 #pragma unroll
-    for (int md = 0; md < 4; ++md)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[nq][md][v] = 0.f;
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+    for (int v = 0; v < 16; ++v) o[md][v] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
 
-  // ---- staging of one tile: global -> registers -> LDS
-  uint4 kreg[4];
-  uint2 vreg[2][4];
-  const int vb = (lane >> 3) + 8 * wave;                           // which 4 head-dims (0..31)
-  auto load_tile = [&](int64_t j0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int id = tid + 256 * i;
-      int64_t j = j0 + (id >> 4);
-      j = j < k_end ? j : k_end - 1;                               // the tail repeats a key; masked below
-      kreg[i] = *(const uint4*)(key_row(ks, j, false) + (id & 15) * 16);
-    }
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      const int ap = (lane & 7) + 8 * p;                           // 4-key group as stored in LDS
-      const int sw = ap & 3;
-      const int ag = (ap & ~3) | (sw == 1 ? 2 : sw == 2 ? 1 : sw); // 4-key group in key order
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        int64_t j = j0 + 4 * ag + kk;
-        j = j < k_end ? j : k_end - 1;
-        vreg[p][kk] = *(const uint2*)(key_row(ks, j, true) + vb * 8);
-      }
-    }
+  // ---- staging of one tile: global -> registers -> LDS.  K: two 16-byte pieces per thread
+  // (key = piece / 16, 16 pieces per 256-byte row).  V: one 4-key x 4-dim block per thread.
+  uint4 k0, k1;
+  uint2 v0, v1, v2, v3;
+  const int kp0 = tid, kp1 = tid + kThreads;
+  const int vb = (lane >> 3) + 8 * (wave & 3);                     // which 4 head-dims (0..31)
+  const int ap = (lane & 7) + 8 * (wave >> 2);                     // 4-key group as stored in LDS (0..15)
+  const int sw = ap & 3;
+  const int ag = (ap & ~3) | (sw == 1 ? 2 : sw == 2 ? 1 : sw);     // 4-key group in key order
+  auto k_src = [&](uint32_t j0, int piece) -> const uint4* {
+    uint32_t j = j0 + (piece >> 4);
+    j = j < k_end ? j : k_end - 1;                                 // the tail repeats a key; masked below
+    const RowRef rr = row_ref(a, j);
+    return (const uint4*)((rr.in_sel ? ksl : kc) + rr.off + (piece & 15) * 16);
   };
-  auto store_tile = [&]() {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int id = tid + 256 * i;
-      *(uint4*)&k_lds[(id >> 4) * kKLd + (id & 15) * 8] = kreg[i];
-    }
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      const int ap = (lane & 7) + 8 * p;
-      // 4 keys x 4 dims -> 4 dims x 4 keys
-      const uint32_t r0l = vreg[p][0].x, r0h = vreg[p][0].y, r1l = vreg[p][1].x, r1h = vreg[p][1].y;
-      const uint32_t r2l = vreg[p][2].x, r2h = vreg[p][2].y, r3l = vreg[p][3].x, r3h = vreg[p][3].y;
-      uint2 d0, d1, d2, d3;
-      d0.x = (r0l & 0xFFFFu) | (r1l << 16);
-      d0.y = (r2l & 0xFFFFu) | (r3l << 16);
-      d1.x = (r0l >> 16) | (r1l & 0xFFFF0000u);
-      d1.y = (r2l >> 16) | (r3l & 0xFFFF0000u);
-      d2.x = (r0h & 0xFFFFu) | (r1h << 16);
-      d2.y = (r2h & 0xFFFFu) | (r3h << 16);
-      d3.x = (r0h >> 16) | (r1h & 0xFFFF0000u);
-      d3.y = (r2h >> 16) | (r3h & 0xFFFF0000u);
-      bf16_t* dst = &vt_lds[(4 * vb) * kVLd + 4 * ap];
-      *(uint2*)(dst) = d0;
-      *(uint2*)(dst + kVLd) = d1;
-      *(uint2*)(dst + 2 * kVLd) = d2;
-      *(uint2*)(dst + 3 * kVLd) = d3;
-    }
+  auto v_src = [&](uint32_t j0, int kk) -> const uint2* {
+    uint32_t j = j0 + 4 * ag + kk;
+    j = j < k_end ? j : k_end - 1;
+    const RowRef rr = row_ref(a, j);
+    return (const uint2*)((rr.in_sel ? vsl : vc) + rr.off + vb * 8);
+  };
+#define ESA_TILE_LOAD(j0)                                      \
+  do {                                                         \
+    k0 = *k_src(j0, kp0); k1 = *k_src(j0, kp1);                \
+    v0 = *v_src(j0, 0); v1 = *v_src(j0, 1);                    \
+    v2 = *v_src(j0, 2); v3 = *v_src(j0, 3);                    \
+  } while (0)
+  auto tile_store = [&](int stage) {
+    bf16_t* kt = lds + stage * kStageElems;
+    bf16_t* vt = kt + kKElems;
+    *(uint4*)&kt[(kp0 >> 4) * kKLd + (kp0 & 15) * 8] = k0;
+    *(uint4*)&kt[(kp1 >> 4) * kKLd + (kp1 & 15) * 8] = k1;
+    // 4 keys x 4 dims -> 4 dims x 4 keys
+    uint2 d0, d1, d2, d3;
+    d0.x = (v0.x & 0xFFFFu) | (v1.x << 16);
+    d0.y = (v2.x & 0xFFFFu) | (v3.x << 16);
+    d1.x = (v0.x >> 16) | (v1.x & 0xFFFF0000u);
+    d1.y = (v2.x >> 16) | (v3.x & 0xFFFF0000u);
+    d2.x = (v0.y & 0xFFFFu) | (v1.y << 16);
+    d2.y = (v2.y & 0xFFFFu) | (v3.y << 16);
+    d3.x = (v0.y >> 16) | (v1.y & 0xFFFF0000u);
+    d3.y = (v2.y >> 16) | (v3.y & 0xFFFF0000u);
+    bf16_t* dst = &vt[(4 * vb) * kVLd + 4 * ap];
+    *(uint2*)(dst) = d0;
+    *(uint2*)(dst + kVLd) = d1;
+    *(uint2*)(dst + 2 * kVLd) = d2;
+    *(uint2*)(dst + 3 * kVLd) = d3;
   };
 
-  if (tile_begin < tile_end) load_tile(tile_begin * kKT);
-  for (int64_t t = tile_begin; t < tile_end; ++t) {
-    const int64_t j0 = t * kKT;
-    __syncthreads();                     // every wave is done reading the previous tile
-    store_tile();
-    __syncthreads();
-    if (t + 1 < tile_end) load_tile(j0 + kKT);
+  if (tile_begin < tile_end) {
+    ESA_TILE_LOAD(tile_begin * kKT);
+    tile_store(0);
+  }
+  for (uint32_t t = tile_begin; t < tile_end; ++t) {
+    const uint32_t j0 = t * kKT;
+    const int stage = (int)((t - tile_begin) & 1);
+    __syncthreads();                     // tile t is in LDS; every wave is done with tile t-1
+    if (t + 1 < tile_end) ESA_TILE_LOAD(j0 + kKT);
+    const bf16_t* kt = lds + stage * kStageElems;
+    const bf16_t* vt = kt + kKElems;
 
     // ---- S^T = K Q^T
-    f32x16 s[2][2];
+    f32x16 s[2];
 #pragma unroll
-    for (int nq = 0; nq < 2; ++nq)
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s[nq][mt][v] = 0.f;
+      for (int v = 0; v < 16; ++v) s[mt][v] = 0.f;
 #pragma unroll
     for (int ks16 = 0; ks16 < kD / 16; ++ks16)
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt) {
-        const bf16x8 ka = *(const bf16x8*)&k_lds[(32 * mt + r) * kKLd + 16 * ks16 + 8 * hi];
-#pragma unroll
-        for (int nq = 0; nq < 2; ++nq)
-          s[nq][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[nq][ks16], s[nq][mt], 0, 0, 0);
+        const bf16x8 ka = *(const bf16x8*)&kt[(32 * mt + r) * kKLd + 16 * ks16 + 8 * hi];
+        s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks16], s[mt], 0, 0, 0);
       }
 
     // ---- mask keys beyond each query's limit (causal diagonal, end of the slice)
     if (j0 + kKT > lim_lo) {
 #pragma unroll
-      for (int nq = 0; nq < 2; ++nq)
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int64_t j = j0 + 32 * mt + 8 * (v / 4) + 4 * hi + (v % 4);
-            if (j >= lim[nq]) s[nq][mt][v] = -INFINITY;
-          }
-    }
-
-    // ---- online softmax, one query per lane
-    bf16x8 pf[2][4];
-#pragma unroll
-    for (int nq = 0; nq < 2; ++nq) {
-      float mx = s[nq][0][0];
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[nq][mt][v]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run[nq], mx * a.c2);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float corr = __builtin_amdgcn_exp2f(m_run[nq] - m_use);
-      m_run[nq] = m_new;
-      float psum = 0.f;
-#pragma unroll
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[nq][mt][v], a.c2, -m_use));
-          s[nq][mt][v] = p;
-          psum += p;
+          const uint32_t j = j0 + 32 * mt + 8 * (v / 4) + 4 * hi + (v % 4);
+          if (j >= lim) s[mt][v] = -INFINITY;
         }
-      l_run[nq] = l_run[nq] * corr + psum;
-      if (__ballot(corr != 1.f) != 0ull) {
+    }
+
+    // ---- online softmax, one query per lane
+    float mx = s[0][0];
 #pragma unroll
-        for (int md = 0; md < 4; ++md)
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) o[nq][md][v] *= corr;
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[mt][v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx * a.c2);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
+    m_run = m_new;
+    float psum = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mt][v], a.c2, -m_use));
+        s[mt][v] = p;
+        psum += p;
       }
+    l_run = l_run * corr + psum;
+    if (__ballot(corr != 1.f) != 0ull) {
 #pragma unroll
-      for (int kp = 0; kp < 4; ++kp) {
-        const int mt = kp >> 1, v0 = (kp & 1) * 8;
-        uint4 w;
-        w.x = pack_bf16x2(s[nq][mt][v0 + 0], s[nq][mt][v0 + 1]);
-        w.y = pack_bf16x2(s[nq][mt][v0 + 2], s[nq][mt][v0 + 3]);
-        w.z = pack_bf16x2(s[nq][mt][v0 + 4], s[nq][mt][v0 + 5]);
-        w.w = pack_bf16x2(s[nq][mt][v0 + 6], s[nq][mt][v0 + 7]);
-        pf[nq][kp] = *(bf16x8*)&w;
-      }
+      for (int md = 0; md < 4; ++md)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[md][v] *= corr;
+    }
+    bf16x8 pf[4];
+#pragma unroll
+    for (int kp = 0; kp < 4; ++kp) {
+      const int mt = kp >> 1, e0 = (kp & 1) * 8;
+      uint4 w;
+      w.x = pack_bf16x2(s[mt][e0 + 0], s[mt][e0 + 1]);
+      w.y = pack_bf16x2(s[mt][e0 + 2], s[mt][e0 + 3]);
+      w.z = pack_bf16x2(s[mt][e0 + 4], s[mt][e0 + 5]);
+      w.w = pack_bf16x2(s[mt][e0 + 6], s[mt][e0 + 7]);
+      pf[kp] = *(bf16x8*)&w;
     }
 
     // ---- O^T += V^T P^T
@@ -248,74 +274,89 @@ __global__ __launch_bounds__(256) void attend_mfma_bf16(AttendArgs a) {
     for (int kp = 0; kp < 4; ++kp)
 #pragma unroll
       for (int md = 0; md < 4; ++md) {
-        const bf16x8 va = *(const bf16x8*)&vt_lds[(32 * md + r) * kVLd + 16 * kp + 8 * hi];
-#pragma unroll
-        for (int nq = 0; nq < 2; ++nq)
-          o[nq][md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[nq][kp], o[nq][md], 0, 0, 0);
+        const bf16x8 va = *(const bf16x8*)&vt[(32 * md + r) * kVLd + 16 * kp + 8 * hi];
+        o[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[kp], o[md], 0, 0, 0);
       }
+
+    if (t + 1 < tile_end) tile_store(stage ^ 1);
   }
+#undef ESA_TILE_LOAD
 
   // ---- results: accumulator register v of tile md is head-dim 32*md + 8*(v/4) + 4*hi + v%4 of this lane's query
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (!c_ok) return;
+  const int64_t row = (int64_t)c * a.h + head;
+  if (a.n_split == 1) {
+    const float inv = 1.f / l_tot;
+    bf16_t* op = a.out + (int64_t)b * a.out_bs + row * kD;
 #pragma unroll
-  for (int nq = 0; nq < 2; ++nq) {
-    const float l_tot = l_run[nq] + __shfl_xor(l_run[nq], 32, 64);
-    if (!c_ok[nq]) continue;
-    const int64_t row = (int64_t)c[nq] * a.h + head[nq];
-    if (a.n_split == 1) {
-      const float inv = 1.f / l_tot;
-      bf16_t* op = a.out + (int64_t)b * a.out_bs + row * kD;
+    for (int md = 0; md < 4; ++md)
 #pragma unroll
-      for (int md = 0; md < 4; ++md)
-#pragma unroll
-        for (int vg = 0; vg < 4; ++vg) {
-          uint2 w;
-          w.x = pack_bf16x2(o[nq][md][4 * vg + 0] * inv, o[nq][md][4 * vg + 1] * inv);
-          w.y = pack_bf16x2(o[nq][md][4 * vg + 2] * inv, o[nq][md][4 * vg + 3] * inv);
-          *(uint2*)(op + 32 * md + 8 * vg + 4 * hi) = w;
-        }
-      if (a.lse && hi == 0) a.lse[(int64_t)b * a.l_c * a.h + row] = (m_run[nq] + __builtin_amdgcn_logf(l_tot)) * kLn2;
-    } else {
-      const int64_t prow = ((int64_t)(b * a.n_split + split) * a.l_c) * a.h + row;
-      float* pp = a.part_o + prow * kD;
-#pragma unroll
-      for (int md = 0; md < 4; ++md)
-#pragma unroll
-        for (int vg = 0; vg < 4; ++vg) {
-          float4 w = {o[nq][md][4 * vg + 0], o[nq][md][4 * vg + 1], o[nq][md][4 * vg + 2], o[nq][md][4 * vg + 3]};
-          *(float4*)(pp + 32 * md + 8 * vg + 4 * hi) = w;
-        }
-      if (hi == 0) {
-        float2 ml = {m_run[nq], l_tot};
-        *(float2*)(a.part_ml + prow * 2) = ml;
+      for (int vg = 0; vg < 4; ++vg) {
+        uint2 w;
+        w.x = pack_bf16x2(o[md][4 * vg + 0] * inv, o[md][4 * vg + 1] * inv);
+        w.y = pack_bf16x2(o[md][4 * vg + 2] * inv, o[md][4 * vg + 3] * inv);
+        *(uint2*)(op + 32 * md + 8 * vg + 4 * hi) = w;
       }
+    if (a.lse && hi == 0) a.lse[(int64_t)b * a.l_c * a.h + row] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2;
+  } else {
+    const int64_t prow = ((int64_t)(b * a.n_split + split) * a.l_c) * a.h + row;
+    float* pp = a.part_o + prow * kD;
+#pragma unroll
+    for (int md = 0; md < 4; ++md)
+#pragma unroll
+      for (int vg = 0; vg < 4; ++vg) {
+        float4 w = {o[md][4 * vg + 0], o[md][4 * vg + 1], o[md][4 * vg + 2], o[md][4 * vg + 3]};
+        *(float4*)(pp + 32 * md + 8 * vg + 4 * hi) = w;
+      }
+    if (hi == 0) {
+      float2 ml = {m_run, l_tot};
+      *(float2*)(a.part_ml + prow * 2) = ml;
     }
   }
 }
 
 // Algorithm 1's merge over the key slices: weights 2^(m_s - M) with the maximum subtracted first.
-__global__ __launch_bounds__(128) void esa_attend_merge(const float* __restrict__ part_o,
+// 32 lanes per row (four head-dims each), eight rows per workgroup.
+__global__ __launch_bounds__(256) void esa_attend_merge(const float* __restrict__ part_o,
                                                         const float* __restrict__ part_ml, int n_split, int64_t rows,
                                                         bf16_t* __restrict__ out, float* __restrict__ lse,
                                                         int64_t out_bs, int64_t lse_bs) {
-  const int64_t row = blockIdx.x;
+  const int64_t row = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);
+  const int d4 = (threadIdx.x & 31) * 4;
   const int b = blockIdx.y;
+  if (row >= rows) return;
   float m[kMaxSplits], l[kMaxSplits];
   float M = -INFINITY;
-  for (int s = 0; s < n_split; ++s) {
-    const float2 ml = *(const float2*)(part_ml + (((int64_t)b * n_split + s) * rows + row) * 2);
-    m[s] = ml.x;
-    l[s] = ml.y;
-    M = fmaxf(M, ml.x);
+#pragma unroll
+  for (int s = 0; s < kMaxSplits; ++s) {
+    if (s < n_split) {
+      const float2 ml = *(const float2*)(part_ml + (((int64_t)b * n_split + s) * rows + row) * 2);
+      m[s] = ml.x;
+      l[s] = ml.y;
+      M = fmaxf(M, ml.x);
+    }
   }
-  float L = 0.f, acc = 0.f;
-  for (int s = 0; s < n_split; ++s) {
-    if (m[s] == -INFINITY) continue;              // a slice this query saw nothing of
-    const float w = __builtin_amdgcn_exp2f(m[s] - M);
-    L += w * l[s];
-    acc += w * part_o[(((int64_t)b * n_split + s) * rows + row) * kD + threadIdx.x];
+  float L = 0.f;
+  float4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s = 0; s < kMaxSplits; ++s) {
+    if (s < n_split && m[s] != -INFINITY) {       // a slice this query saw nothing of carries no weight
+      const float w = __builtin_amdgcn_exp2f(m[s] - M);
+      const float4 po = *(const float4*)(part_o + (((int64_t)b * n_split + s) * rows + row) * kD + d4);
+      L += w * l[s];
+      acc.x += w * po.x;
+      acc.y += w * po.y;
+      acc.z += w * po.z;
+      acc.w += w * po.w;
+    }
   }
-  out[(int64_t)b * out_bs + row * kD + threadIdx.x] = f32_to_bf16(acc / L);
-  if (lse && threadIdx.x == 0) lse[(int64_t)b * lse_bs + row] = (M + __builtin_amdgcn_logf(L)) * kLn2;
+  const float inv = 1.f / L;
+  uint2 w2;
+  w2.x = pack_bf16x2(acc.x * inv, acc.y * inv);
+  w2.y = pack_bf16x2(acc.z * inv, acc.w * inv);
+  *(uint2*)(out + (int64_t)b * out_bs + row * kD + d4) = w2;
+  if (lse && d4 == 0) lse[(int64_t)b * lse_bs + row] = (M + __builtin_amdgcn_logf(L)) * kLn2;
 }
 
 int choose_splits(int l_c, int group, int h_kv, int batch) {
@@ -354,35 +395,39 @@ int launch_attend_mfma(const void* q, int l_c, int h, int h_kv, int d, const voi
                        const void* v_sel, int n_sel, float scale, void* out, float* lse, int batch, int64_t q_bs,
                        int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes, hipStream_t st) {
   if (!(scale > 0.f)) ESA_FAIL(ESA_EINVAL, "esa_attend: scale must be positive");
+  if (t0 + l_c >= ((int64_t)1 << 31) || tok_stride * 2 >= ((int64_t)1 << 32))
+    ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend: positions beyond 2^31 are not supported by the matrix-core kernel");
   AttendArgs a;
   a.q = (const bf16_t*)q;
   a.out = (bf16_t*)out;
   a.lse = lse;
-  a.ks.k_cache = (const char*)k_cache;
-  a.ks.v_cache = (const char*)v_cache;
-  a.ks.k_sel = (const char*)k_sel;
-  a.ks.v_sel = (const char*)v_sel;
-  a.ks.tok_bytes = tok_stride * 2;
-  a.ks.sel_bytes = (int64_t)h_kv * d * 2;
-  a.ks.i_end = i_end;
-  a.ks.n_sel = n_sel;
-  a.ks.l_start = l_start;
+  a.k_cache = (const char*)k_cache;
+  a.v_cache = (const char*)v_cache;
+  a.k_sel = (const char*)k_sel;
+  a.v_sel = (const char*)v_sel;
+  a.tok_bytes = (uint32_t)(tok_stride * 2);
+  a.sel_bytes = (uint32_t)((int64_t)h_kv * d * 2);
+  a.i_end = (uint32_t)i_end;
+  a.n_sel = (uint32_t)n_sel;
+  a.l_start = (uint32_t)l_start;
   a.l_c = l_c;
   a.h = h;
   a.h_kv = h_kv;
   a.group = h / h_kv;
   a.qpt = kRows / a.group;
   a.n_qt = (l_c + a.qpt - 1) / a.qpt;
-  a.n_fixed = i_end + n_sel + (t0 - l_start);
+  a.batch = batch;
+  a.n_fixed = (uint32_t)(i_end + n_sel + (t0 - l_start));
   a.c2 = scale * kLog2e;
   a.q_bs = q_bs;
   a.out_bs = out_bs;
   a.cache_bs_bytes = cache_bs * 2;
   a.sel_bs_bytes = sel_bs * 2;
   int ns = choose_splits(l_c, a.group, h_kv, batch);
-  const int64_t min_tiles = (a.n_fixed + (l_c < a.qpt ? l_c : a.qpt) + kKT - 1) / kKT;   // tiles of the first row tile
+  const int64_t min_tiles = ((int64_t)a.n_fixed + (l_c < a.qpt ? l_c : a.qpt) + kKT - 1) / kKT;   // first row tile
   if (ns > min_tiles) ns = (int)min_tiles;
   a.n_split = ns;
+  a.xcd_mapping = ((batch * h_kv) % 8 == 0) ? 1 : 0;
   a.part_o = nullptr;
   a.part_ml = nullptr;
   if (ns > 1) {
@@ -392,11 +437,20 @@ int launch_attend_mfma(const void* q, int l_c, int h, int h_kv, int d, const voi
     a.part_o = (float*)ws;
     a.part_ml = (float*)((char*)ws + align_up(rows * kD * sizeof(float), 256));
   }
-  attend_mfma_bf16<<<dim3(a.n_qt * ns, h_kv, batch), 256, 0, st>>>(a);
-  if (ns > 1)
-    esa_attend_merge<<<dim3((unsigned)((int64_t)l_c * h), batch), 128, 0, st>>>(a.part_o, a.part_ml, ns,
-                                                                                (int64_t)l_c * h, (bf16_t*)out, lse,
-                                                                                out_bs, (int64_t)l_c * h);
+  static bool lds_limit_raised = false;          // idempotent; a race only repeats the call
+  if (!lds_limit_raised) {
+    hipError_t e = hipFuncSetAttribute((const void*)attend_mfma_bf16, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kLdsBytes);
+    if (e != hipSuccess) return hip_failed(e, "hipFuncSetAttribute(attend_mfma_bf16)");
+    lds_limit_raised = true;
+  }
+  const int64_t n_wg = (int64_t)batch * h_kv * a.n_qt * ns;
+  attend_mfma_bf16<<<dim3((unsigned)n_wg), kThreads, kLdsBytes, st>>>(a);
+  if (ns > 1) {
+    const int64_t rows = (int64_t)l_c * h;
+    esa_attend_merge<<<dim3((unsigned)((rows + 7) / 8), batch), 256, 0, st>>>(a.part_o, a.part_ml, ns, rows,
+                                                                              (bf16_t*)out, lse, out_bs, rows);
+  }
   ESA_LAUNCH_CHECK("attend_mfma");
   return ESA_OK;
 }

@@ -1,11 +1,16 @@
 // Query/key compression (Eq. 5): out[n, :] = x[n, :] . W (+ bias), one linear layer on the
 // head-concatenated vector, fp32 accumulation, result rounded to the storage type.
 //
-// Two kernels:
-//   * compress_mfma_bf16 — bf16 storage, matrix cores.  A workgroup owns 16 tokens x 64 outputs and
-//     walks the whole reduction dimension, so every output is accumulated in one fixed order
-//     (deterministic; no atomics, no split-K).
-//   * compress_fma — any storage type and shape, plain fp32 FMAs in ascending reduction order.
+// Kernels:
+//   * compress_mfma_packed_bf16 — bf16 storage, weights in the packed (output-major) layout written by
+//     esa_pack_weights.  Both MFMA operands then have their reduction elements contiguous in memory
+//     and are loaded straight from global memory, 16 bytes per lane, with no LDS staging.  A
+//     workgroup owns a 16-token x 16-output tile; its four waves each reduce a quarter of d_in and
+//     the four partial tiles are added in a fixed order (deterministic, no atomics).
+//   * compress_mfma_bf16 — bf16 storage, weights as given ([d_in, d_c]); W is transposed through LDS.
+//   * compress_fma — any storage type, shape and weight layout, plain fp32 FMAs in ascending
+//     reduction order.
+//   * pack_weights — the one-time transposition [d_in, d_c] -> [d_c, d_in].
 #include "esa_common.h"
 
 namespace esa {
@@ -16,7 +21,7 @@ constexpr int kTok = 16;       // tokens per block
 constexpr int kChunk = 64;     // reduction elements staged per step
 constexpr int kMaxColsPerLane = 4;
 
-template <typename T>
+template <typename T, bool PACKED>
 __global__ __launch_bounds__(256) void compress_fma(const T* __restrict__ x, int64_t n_tok, int64_t d_in, int64_t ldx,
                                                     const T* __restrict__ W, const T* __restrict__ bias, int d_c,
                                                     T* __restrict__ out, int64_t ldo, int64_t x_bs, int64_t out_bs) {
@@ -45,7 +50,7 @@ __global__ __launch_bounds__(256) void compress_fma(const T* __restrict__ x, int
 #pragma unroll
       for (int c = 0; c < kMaxColsPerLane; ++c) {
         const int j = lane + 64 * c;
-        wv[c] = (j < d_c) ? load_f32(W + (i0 + ii) * (int64_t)d_c + j) : 0.f;
+        wv[c] = (j < d_c) ? load_f32(PACKED ? W + (int64_t)j * d_in + (i0 + ii) : W + (i0 + ii) * (int64_t)d_c + j) : 0.f;
       }
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
@@ -131,28 +136,103 @@ __global__ __launch_bounds__(256) void compress_mfma_bf16(const bf16_t* __restri
   }
 }
 
+
+// ------------------------------------------------------------------------------------------ MFMA, packed weights
+// v_mfma_f32_16x16x32_bf16: lane l supplies A[l%16][8*(l/16) .. +7] and B[8*(l/16) .. +7][l%16] and owns
+// C[4*(l/16) .. +3][l%16].  A rows are tokens, B columns are outputs, so a lane reads eight consecutive
+// reduction elements of one token row of x and of one output row of the packed weights.
+__global__ __launch_bounds__(256) void compress_mfma_packed_bf16(const bf16_t* __restrict__ x, int64_t n_tok,
+                                                                 int64_t d_in, int64_t ldx,
+                                                                 const bf16_t* __restrict__ Wt,
+                                                                 const bf16_t* __restrict__ bias, int d_c,
+                                                                 bf16_t* __restrict__ out, int64_t ldo, int64_t x_bs,
+                                                                 int64_t out_bs) {
+  __shared__ float red[4][256];
+  const bf16_t* xb = x + (int64_t)blockIdx.z * x_bs;
+  bf16_t* ob = out + (int64_t)blockIdx.z * out_bs;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, q = lane >> 4;
+  const int64_t tok0 = (int64_t)blockIdx.x * 16;
+  const int col0 = blockIdx.y * 16;
+  int64_t tok = tok0 + r;
+  tok = tok < n_tok ? tok : n_tok - 1;               // keep the address valid; the row is discarded
+  const int64_t kq = d_in / 4;                       // this wave's share of the reduction (multiple of 32)
+  const bf16_t* xp = xb + tok * ldx + wave * kq + q * 8;
+  const bf16_t* wp = Wt + (int64_t)(col0 + r) * d_in + wave * kq + q * 8;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+  for (int64_t ks = 0; ks < kq; ks += 32) {
+    const bf16x8 a = *(const bf16x8*)(xp + ks);
+    const bf16x8 b = *(const bf16x8*)(wp + ks);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
+  }
+#pragma unroll
+  for (int v = 0; v < 4; ++v) red[wave][(4 * q + v) * 16 + r] = acc[v];
+  __syncthreads();
+  const int t = threadIdx.x;
+  const int64_t row = tok0 + (t >> 4);
+  const int col = col0 + (t & 15);
+  if (row < n_tok) {
+    float v = ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
+    if (bias) v += bf16_to_f32(bias[col]);
+    ob[row * ldo + col] = f32_to_bf16(v);
+  }
+}
+
+// W [d_in, d_c] -> Wt [d_c, d_in], through a padded LDS tile so both sides are coalesced.
+template <typename T>
+__global__ __launch_bounds__(256) void pack_weights(const T* __restrict__ W, int64_t d_in, int d_c, T* __restrict__ Wt) {
+  __shared__ T tile[32][33];
+  const int64_t i0 = (int64_t)blockIdx.x * 32;
+  const int j0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+  for (int yy = ty; yy < 32; yy += 8)
+    if (i0 + yy < d_in && j0 + tx < d_c) tile[yy][tx] = W[(i0 + yy) * d_c + j0 + tx];
+  __syncthreads();
+  for (int yy = ty; yy < 32; yy += 8)
+    if (j0 + yy < d_c && i0 + tx < d_in) Wt[(int64_t)(j0 + yy) * d_in + i0 + tx] = tile[tx][yy];
+}
+
 }  // namespace
 
-int launch_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx, const void* W, const void* bias,
-                    int d_c, void* out, int64_t ldo, int dtype, int batch, int64_t x_bs, int64_t out_bs,
-                    hipStream_t st) {
+int launch_pack_weights(const void* W, int64_t d_in, int d_c, int dtype, void* Wt, hipStream_t st) {
+  const dim3 grid((unsigned)((d_in + 31) / 32), (unsigned)((d_c + 31) / 32));
+  if (dtype == ESA_BF16) pack_weights<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)W, d_in, d_c, (bf16_t*)Wt);
+  else pack_weights<float><<<grid, 256, 0, st>>>((const float*)W, d_in, d_c, (float*)Wt);
+  ESA_LAUNCH_CHECK("pack_weights");
+  return ESA_OK;
+}
+
+int launch_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx, const void* W, int w_layout,
+                    const void* bias, int d_c, void* out, int64_t ldo, int dtype, int batch, int64_t x_bs,
+                    int64_t out_bs, hipStream_t st) {
   const int64_t nblk = (n_tok + kTok - 1) / kTok;
+  const bool packed = (w_layout == ESA_W_PACKED);
   if (dtype == ESA_BF16) {
-    const bool mfma_ok = (d_c % kMCols == 0) && (d_in % kMStep == 0) && (ldx % 8 == 0) && (x_bs % 8 == 0) &&
-                         (((uintptr_t)x | (uintptr_t)W) % 16 == 0);
-    if (mfma_ok) {
+    const bool vec_ok = (ldx % 8 == 0) && (x_bs % 8 == 0) && (((uintptr_t)x | (uintptr_t)W) % 16 == 0);
+    if (packed && vec_ok && d_c % 16 == 0 && d_in % 128 == 0) {
+      compress_mfma_packed_bf16<<<dim3((unsigned)((n_tok + 15) / 16), d_c / 16, batch), 256, 0, st>>>(
+          (const bf16_t*)x, n_tok, d_in, ldx, (const bf16_t*)W, (const bf16_t*)bias, d_c, (bf16_t*)out, ldo, x_bs,
+          out_bs);
+    } else if (!packed && vec_ok && (d_c % kMCols == 0) && (d_in % kMStep == 0)) {
       compress_mfma_bf16<<<dim3((unsigned)nblk, d_c / kMCols, batch), 256, 0, st>>>(
           (const bf16_t*)x, n_tok, d_in, ldx, (const bf16_t*)W, (const bf16_t*)bias, d_c, (bf16_t*)out, ldo, x_bs,
           out_bs);
+    } else if (packed) {
+      compress_fma<bf16_t, true><<<dim3((unsigned)nblk, batch), 256, 0, st>>>(
+          (const bf16_t*)x, n_tok, d_in, ldx, (const bf16_t*)W, (const bf16_t*)bias, d_c, (bf16_t*)out, ldo, x_bs,
+          out_bs);
     } else {
-      compress_fma<bf16_t><<<dim3((unsigned)nblk, batch), 256, 0, st>>>((const bf16_t*)x, n_tok, d_in, ldx,
-                                                                       (const bf16_t*)W, (const bf16_t*)bias, d_c,
-                                                                       (bf16_t*)out, ldo, x_bs, out_bs);
+      compress_fma<bf16_t, false><<<dim3((unsigned)nblk, batch), 256, 0, st>>>(
+          (const bf16_t*)x, n_tok, d_in, ldx, (const bf16_t*)W, (const bf16_t*)bias, d_c, (bf16_t*)out, ldo, x_bs,
+          out_bs);
     }
+  } else if (packed) {
+    compress_fma<float, true><<<dim3((unsigned)nblk, batch), 256, 0, st>>>(
+        (const float*)x, n_tok, d_in, ldx, (const float*)W, (const float*)bias, d_c, (float*)out, ldo, x_bs, out_bs);
   } else {
-    compress_fma<float><<<dim3((unsigned)nblk, batch), 256, 0, st>>>((const float*)x, n_tok, d_in, ldx,
-                                                                    (const float*)W, (const float*)bias, d_c,
-                                                                    (float*)out, ldo, x_bs, out_bs);
+    compress_fma<float, false><<<dim3((unsigned)nblk, batch), 256, 0, st>>>(
+        (const float*)x, n_tok, d_in, ldx, (const float*)W, (const float*)bias, d_c, (float*)out, ldo, x_bs, out_bs);
   }
   ESA_LAUNCH_CHECK("compress");
   return ESA_OK;

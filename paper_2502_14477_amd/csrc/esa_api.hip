@@ -45,9 +45,21 @@ int esa_segments(int64_t t0, int64_t l_i, int64_t l_l, int64_t* i_end, int64_t* 
   return ESA_OK;
 }
 
-int esa_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx, const void* W, const void* bias, int d_c,
-                 void* out, int64_t ldo, int dtype, int batch, int64_t x_bs, int64_t out_bs, void* stream) {
+int esa_pack_weights(const void* W, int64_t d_in, int d_c, int dtype, void* W_packed, void* stream) {
+  if (!dtype_ok(dtype)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_pack_weights: dtype %d", dtype);
+  if (d_in <= 0 || d_c <= 0) ESA_FAIL(ESA_EINVAL, "esa_pack_weights: bad size (d_in=%lld d_c=%d)", (long long)d_in, d_c);
+  if (!W || !W_packed || W == W_packed) ESA_FAIL(ESA_EINVAL, "esa_pack_weights: null or aliased pointer");
+  if (!aligned(W, elem_size(dtype)) || !aligned(W_packed, elem_size(dtype)))
+    ESA_FAIL(ESA_EINVAL, "esa_pack_weights: misaligned pointer");
+  return launch_pack_weights(W, d_in, d_c, dtype, W_packed, (hipStream_t)stream);
+}
+
+int esa_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx, const void* W, int w_layout,
+                 const void* bias, int d_c, void* out, int64_t ldo, int dtype, int batch, int64_t x_bs,
+                 int64_t out_bs, void* stream) {
   if (!dtype_ok(dtype)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_compress: dtype %d", dtype);
+  if (w_layout != ESA_W_ROWMAJOR && w_layout != ESA_W_PACKED)
+    ESA_FAIL(ESA_EINVAL, "esa_compress: weight layout %d", w_layout);
   if (n_tok < 0 || d_in <= 0 || d_c <= 0 || batch <= 0 || batch > kMaxBatch)
     ESA_FAIL(ESA_EINVAL, "esa_compress: bad size (n_tok=%lld d_in=%lld d_c=%d batch=%d)", (long long)n_tok,
              (long long)d_in, d_c, batch);
@@ -59,7 +71,7 @@ int esa_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx, const 
   const size_t es = elem_size(dtype);
   if (!aligned(x, es) || !aligned(W, es) || !aligned(out, es) || !aligned(bias, es))
     ESA_FAIL(ESA_EINVAL, "esa_compress: misaligned pointer");
-  return launch_compress(x, n_tok, d_in, ldx, W, bias, d_c, out, ldo, dtype, batch, x_bs, out_bs,
+  return launch_compress(x, n_tok, d_in, ldx, W, w_layout, bias, d_c, out, ldo, dtype, batch, x_bs, out_bs,
                          (hipStream_t)stream);
 }
 

@@ -83,9 +83,10 @@ static inline Segments segments(int64_t t0, int64_t l_i, int64_t l_l) {
 }
 
 // ---------------------------------------------------------------- launchers (one per .hip file)
-int launch_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx, const void* W, const void* bias,
-                    int d_c, void* out, int64_t ldo, int dtype, int batch, int64_t x_bs, int64_t out_bs,
-                    hipStream_t st);
+int launch_pack_weights(const void* W, int64_t d_in, int d_c, int dtype, void* Wt, hipStream_t st);
+int launch_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx, const void* W, int w_layout,
+                    const void* bias, int d_c, void* out, int64_t ldo, int dtype, int batch, int64_t x_bs,
+                    int64_t out_bs, hipStream_t st);
 
 size_t score_workspace_bytes(int l_c, int64_t n_mid, int eps, int batch);
 int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, int64_t m_hi, int d_c, int eps,

@@ -79,3 +79,10 @@ def layer_to_dev(layer):
     d = {n: to_dev(getattr(layer, n), cfg.dtype) for n in ("Q", "K", "V", "W_q", "W_k")}
     d["q_row0"] = getattr(layer, "q_row0", 0)
     return d
+
+
+def pack_layer_weights(esa, dev):
+    """Switch a device layer to packed compression weights (the layout the benchmark uses)."""
+    dev["W_q"] = esa.esa_pack_weights(dev["W_q"])
+    dev["W_k"] = esa.esa_pack_weights(dev["W_k"])
+    return dev

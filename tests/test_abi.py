@@ -16,7 +16,7 @@ def _declared():
 
 def test_every_declared_symbol_is_exported_and_bound():
     names = _declared()
-    assert len(names) == 11 and "esa_attend" in names and "esa_select_topk" in names
+    assert len(names) == 12 and "esa_attend" in names and "esa_select_topk" in names
     raw = ctypes.CDLL(esa.lib_path())
     for n in names:
         assert hasattr(raw, n), n
@@ -42,13 +42,16 @@ def test_argument_validation_returns_codes_without_a_gpu():
     fake = ctypes.c_void_p(4096)          # never dereferenced: every call below fails validation first
     odd = ctypes.c_void_p(4097)
     # unsupported dtype / sizes
-    assert L.esa_compress(fake, 4, 64, 64, fake, None, 32, fake, 32, 7, 1, 0, 0, None) == -2
-    assert L.esa_compress(fake, 4, 64, 64, fake, None, 24, fake, 24, 0, 1, 0, 0, None) == -2
-    assert L.esa_compress(fake, 4, 64, 32, fake, None, 32, fake, 32, 0, 1, 0, 0, None) == -1     # ldx < d_in
-    assert L.esa_compress(None, 4, 64, 64, fake, None, 32, fake, 32, 0, 1, 0, 0, None) == -1     # null x
-    assert L.esa_compress(odd, 4, 64, 64, fake, None, 32, fake, 32, 0, 1, 0, 0, None) == -1      # misaligned
-    assert L.esa_compress(None, 0, 64, 64, None, None, 32, None, 32, 0, 1, 0, 0, None) == 0      # empty: no-op
-    assert b"esa_compress" in L.esa_last_error()
+    assert L.esa_compress(fake, 4, 64, 64, fake, 0, None, 32, fake, 32, 7, 1, 0, 0, None) == -2
+    assert L.esa_compress(fake, 4, 64, 64, fake, 0, None, 24, fake, 24, 0, 1, 0, 0, None) == -2
+    assert L.esa_compress(fake, 4, 64, 32, fake, 0, None, 32, fake, 32, 0, 1, 0, 0, None) == -1     # ldx < d_in
+    assert L.esa_compress(None, 4, 64, 64, fake, 0, None, 32, fake, 32, 0, 1, 0, 0, None) == -1     # null x
+    assert L.esa_compress(odd, 4, 64, 64, fake, 0, None, 32, fake, 32, 0, 1, 0, 0, None) == -1      # misaligned
+    assert L.esa_compress(fake, 4, 64, 64, fake, 5, None, 32, fake, 32, 0, 1, 0, 0, None) == -1     # unknown weight layout
+    assert L.esa_compress(None, 0, 64, 64, None, 1, None, 32, None, 32, 0, 1, 0, 0, None) == 0      # empty: no-op
+    assert L.esa_pack_weights(fake, 64, 32, 0, fake, None) == -1                                    # in place is refused
+    assert L.esa_pack_weights(None, 64, 32, 0, fake, None) == -1
+    assert b"esa_pack_weights" in L.esa_last_error()
     # score: bad range, missing workspace
     assert L.esa_score(fake, 4, fake, 10, 5, 32, 0, fake, 0, 1, 0, 0, 0, fake, 1 << 20, None) == -1
     assert L.esa_score(fake, 4, fake, 0, 100, 32, 0, fake, 0, 1, 0, 0, 0, None, 0, None) == -3

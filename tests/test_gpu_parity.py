@@ -16,7 +16,7 @@ from esa_inputs import get_config, make_layer, segment_bounds, chunk_starts
 from oracle import esa_oracle as orc
 from oracle.planted_gap import plant_gap
 
-from support import to_dev, to_f64, f64_to_dev, bf16_ulp, oracle_step, gpu_step, layer_to_dev
+from support import to_dev, to_f64, f64_to_dev, bf16_ulp, oracle_step, gpu_step, layer_to_dev, pack_layer_weights
 
 pytestmark = pytest.mark.gpu
 
@@ -114,9 +114,13 @@ def test_compress_matches_oracle(esa, dtype, n_tok, heads, d, d_c, bias):
     W = orc.round_to_storage(rng.standard_normal((d_in, d_c)) / np.sqrt(d_in), dtype)
     b = orc.round_to_storage(rng.standard_normal(d_c), dtype) if bias else None
     want = orc.compress(x, W, b, dtype)
-    got = to_f64(esa.esa_compress(f64_to_dev(x, dtype), f64_to_dev(W, dtype),
-                                  None if b is None else f64_to_dev(b, dtype)))
-    _assert_compressed_close(got, want, x, W, b, dtype)
+    xd, Wd = f64_to_dev(x, dtype), f64_to_dev(W, dtype)
+    bd = None if b is None else f64_to_dev(b, dtype)
+    _assert_compressed_close(to_f64(esa.esa_compress(xd, Wd, bd)), want, x, W, b, dtype)
+    # the packed weight layout computes the same thing
+    Wp = esa.esa_pack_weights(Wd)
+    assert torch.equal(Wp.data, Wd.t().contiguous())
+    _assert_compressed_close(to_f64(esa.esa_compress(xd, Wp, bd)), want, x, W, b, dtype)
 
 
 def _assert_compressed_close(got, want, x, W, b, dtype):
@@ -296,7 +300,7 @@ def test_llama_shaped_layer_sampled_chunks_bf16(esa, S, sample):
     layer = make_layer(cfg)
     replaced, kc64 = plant_gap(layer, sample, TAU_E2E["bf16"])
     say(f"C2-shaped S={S}, chunks {sample}, {replaced.shape[0]} rows replaced")
-    dev = layer_to_dev(layer)
+    dev = pack_layer_weights(esa, layer_to_dev(layer))
     kc_dev = esa.esa_compress(dev["K"], dev["W_k"])
     _assert_compressed_close(to_f64(kc_dev), kc64, layer.f64("K"), orc.widen(layer.W_k, "bf16"), None, "bf16")
     for t0 in sample:
