@@ -135,6 +135,10 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     const bf16_t* qp = a.q + (int64_t)b * a.q_bs + ((int64_t)cc * a.h + head) * kD + hi * 8;
 #pragma unroll
     for (int ks16 = 0; ks16 < kD / 16; ++ks16) qf[ks16] = *(const bf16x8*)(qp + ks16 * 16);
+    // Pin the fragments as arrived values here: otherwise every use inside the tile loop carries a
+    // wait on the vector-memory counter, which would also wait for the tile loads just issued.
+#pragma unroll
+    for (int ks16 = 0; ks16 < kD / 16; ++ks16) asm volatile("" : "+v"(qf[ks16]));
   }
 
   f32x16 o[4];
@@ -153,6 +157,12 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   const int ap = (lane & 7) + 8 * (wave >> 2);                     // 4-key group as stored in LDS (0..15)
   const int sw = ap & 3;
   const int ag = (ap & ~3) | (sw == 1 ? 2 : sw == 2 ? 1 : sw);     // 4-key group in key order
+  // Per-thread row numbers inside a tile.  A tile whose 64 keys lie inside one segment of the
+  // virtual sequence (the usual case) is addressed as uniform base + row * stride + column, the base
+  // and stride chosen on the scalar unit; tiles that straddle a segment boundary or the end of
+  // the slice take the general per-row path.
+  const uint32_t kr0 = kp0 >> 4, kr1 = kp1 >> 4, kcol0 = (kp0 & 15) * 16, kcol1 = (kp1 & 15) * 16;
+  const uint32_t vr = 4 * ag, vcol = vb * 8;
   auto k_src = [&](uint32_t j0, int piece) -> const uint4* {
     uint32_t j = j0 + (piece >> 4);
     j = j < k_end ? j : k_end - 1;                                 // the tail repeats a key; masked below
@@ -165,12 +175,40 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     const RowRef rr = row_ref(a, j);
     return (const uint2*)((rr.in_sel ? vsl : vc) + rr.off + vb * 8);
   };
-#define ESA_TILE_LOAD(j0)                                      \
-  do {                                                         \
-    k0 = *k_src(j0, kp0); k1 = *k_src(j0, kp1);                \
-    v0 = *v_src(j0, 0); v1 = *v_src(j0, 1);                    \
-    v2 = *v_src(j0, 2); v3 = *v_src(j0, 3);                    \
-  } while (0)
+  auto tile_load = [&](uint32_t j0) {
+    const uint32_t sel_end = a.i_end + a.n_sel;
+    int seg = -1;                                                  // 0: cache rows, 1: gathered rows
+    uint32_t row0 = 0;
+    if (j0 + kKT <= a.i_end) {
+      seg = 0;
+      row0 = j0;
+    } else if (j0 >= a.i_end && j0 + kKT <= sel_end) {
+      seg = 1;
+      row0 = j0 - a.i_end;
+    } else if (j0 >= sel_end && j0 + kKT <= k_end) {
+      seg = 0;
+      row0 = j0 - sel_end + a.l_start;
+    }
+    if (seg >= 0) {
+      const uint32_t stride = seg ? a.sel_bytes : a.tok_bytes;
+      const char* kb = (seg ? ksl : kc) + (uint64_t)row0 * stride;
+      const char* vbase = (seg ? vsl : vc) + (uint64_t)row0 * stride;
+      k0 = *(const uint4*)(kb + (kr0 * stride + kcol0));
+      k1 = *(const uint4*)(kb + (kr1 * stride + kcol1));
+      v0 = *(const uint2*)(vbase + (vr * stride + vcol));
+      v1 = *(const uint2*)(vbase + ((vr + 1) * stride + vcol));
+      v2 = *(const uint2*)(vbase + ((vr + 2) * stride + vcol));
+      v3 = *(const uint2*)(vbase + ((vr + 3) * stride + vcol));
+    } else {
+      k0 = *k_src(j0, kp0);
+      k1 = *k_src(j0, kp1);
+      v0 = *v_src(j0, 0);
+      v1 = *v_src(j0, 1);
+      v2 = *v_src(j0, 2);
+      v3 = *v_src(j0, 3);
+    }
+  };
+#define ESA_TILE_LOAD(j0) tile_load(j0)
   auto tile_store = [&](int stage) {
     bf16_t* kt = lds + stage * kStageElems;
     bf16_t* vt = kt + kKElems;

@@ -181,6 +181,10 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
         if (!ok) v = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
         a[mt][ks] = v;
       }
+      // Pin the fragments as arrived values: otherwise every use inside the stage loop carries a wait on
+      // the vector-memory counter, which would also wait for the stage loads just issued.
+#pragma unroll
+      for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(a[mt][ks]));
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         if (PASS == 0) {
@@ -189,6 +193,10 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
           const int qrow = q0 + 32 * mt + 8 * (v / 4) + 4 * hi + (v % 4);
           aux[mt][v] = (qrow < l_c) ? mu[qrow] : INFINITY;
         }
+      }
+      if (PASS == 1) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(aux[mt][v]));
       }
     }
 
