@@ -53,6 +53,8 @@ def main():
     ap.add_argument("--config", default="C3", help="C2, C3 or C5 (prefill), C4 (decode)")
     ap.add_argument("--seq", type=int, default=0, help="override the sequence length (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eager", action="store_true",
+                    help="time eager launches instead of replaying the step as a captured HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -114,15 +116,35 @@ def main():
         mark(5)
         return out
 
-    for _ in range(args.warmup):
+    def timed(fn, n):
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return 1e3 * (time.perf_counter() - t_start) / n
+
+    for _ in range(max(args.warmup, 1)):
         step()
-    torch.cuda.synchronize()
-    t_start = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_start
-    ms_per_step = 1e3 * elapsed / args.steps
+    eager_ms = timed(step, args.steps)
+    ms_per_step, mode = eager_ms, "eager launches"
+    if not args.eager:
+        # The step is launch-bound on the host (about twenty small kernels), so it is captured once
+        # as a HIP graph and replayed; every kernel of the step runs in every replay.
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            graph_out = step()
+        for _ in range(max(args.warmup, 1)):
+            graph.replay()
+        ms_per_step, mode = timed(graph.replay, args.steps), "HIP graph replay"
+        ref = step()
+        torch.cuda.synchronize()
+        assert torch.equal(ref, graph_out), "graph replay and eager step disagree"
 
     # per-call durations from HIP events on the launch stream (torch's current stream)
     per_call = {c: [] for c in calls}
@@ -175,7 +197,7 @@ def main():
                                   cfg.d_c, n_mid),
                    "global_batch": 1, "seq_len": cfg.S, "parallelism": "single GPU"},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
-        "setup_s": round(t_gen, 1),
+        "launch_mode": mode, "eager_ms_per_step": round(eager_ms, 4), "setup_s": round(t_gen, 1),
     }
     print(json.dumps(result))
 

@@ -321,3 +321,36 @@ def test_decode_step_equals_one_token_chunk_bf16(esa):
         g = _check_step(esa, layer, dev, kc64, kc_dev, t0)
         needles = np.setdiff1d(layer.plan.positions[t0], replaced)
         assert set(needles.tolist()) <= set(g["idx"].cpu().numpy().tolist())
+
+
+def test_step_captured_as_a_graph_replays_identically(esa):
+    """The five calls captured once and replayed, with eager work and synchronisations between the
+    replays: every replay must reproduce the eager result bit for bit (nothing in the library
+    records a memset node, and no call keeps state between launches)."""
+    cfg = get_config("C2").scaled(S=8192)
+    layer = make_layer(cfg)
+    say("graph capture of one step, C2-shaped S=8192")
+    dev = pack_layer_weights(esa, layer_to_dev(layer))
+    t0 = 7680
+    kc_dev = esa.esa_compress(dev["K"], dev["W_k"])
+    eager = gpu_step(esa, dev, cfg, t0, kc_dev)
+    torch.cuda.synchronize()
+    want_O, want_idx = eager["O"].clone(), eager["idx"].clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        gpu_step(esa, dev, cfg, t0, kc_dev)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        g = gpu_step(esa, dev, cfg, t0, kc_dev)
+    for rep in range(4):
+        g["O"].zero_()
+        g["idx"].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(g["O"], want_O) and torch.equal(g["idx"], want_idx), rep
+        other = gpu_step(esa, dev, cfg, 4608, kc_dev)          # eager work between replays
+        torch.cuda.synchronize()
+        assert other["O"].shape == want_O.shape
