@@ -86,14 +86,17 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 //
 // Here A rows are current tokens (queries), B columns are middle tokens.  A workgroup of eight
 // waves (two per SIMD, so one wave's maximum/subtract work overlaps the other's matrix
-// instructions) keeps up to 512 compressed queries in registers (64 per wave, as A fragments for
-// the whole d_c = 128) and streams its contiguous share of K' past them: 128-token stages are
-// copied global -> registers -> LDS with full 256-byte rows per 16 lanes (double buffered, one
-// barrier per stage), and every wave reads its B fragments from LDS.  K' is thus read from memory
-// once per sweep and Q' once per workgroup.  With a token per lane, the column maximum of Eq. 4 is
-// an in-lane reduction over the accumulator registers plus one exchange between the two
-// half-waves; the row maximum is kept per register across all tiles and reduced across lanes
-// once, then written as this workgroup's partial row maxima (no atomics) for score_rowmax_reduce.
+// instructions) owns up to 512 consecutive middle tokens.  Its whole share of K' (at most 128 KB)
+// is brought into LDS in ONE round trip — sixteen 16-byte loads per thread issued back to back,
+// full 256-byte rows per 16 lanes — and stays there; after a single barrier the kernel runs
+// without further global loads or barriers.  Queries are the register-resident operand (64 per
+// wave as A fragments for the whole d_c = 128; chunks longer than 512 loop over query blocks
+// against the same LDS tile), so K' is read from memory once per sweep.  With a token per lane,
+// the column maximum of Eq. 4 is an in-lane reduction over the accumulator registers plus one
+// exchange between the two half-waves, folded across waves with an LDS integer maximum on
+// order-preserving keys; the row maximum is kept per register across all tiles and reduced
+// across lanes once, then written as this workgroup's partial row maxima (no atomics across
+// workgroups) for score_rowmax_reduce.
 constexpr int kDc = 128;
 constexpr int kKSteps = kDc / 16;        // MFMA reduction steps per tile
 constexpr int kWaves = 8;
@@ -101,23 +104,24 @@ constexpr int kThreads = 64 * kWaves;
 constexpr int kMT = 2;                   // 32-query tiles per wave
 constexpr int kQPerWave = 32 * kMT;
 constexpr int kQPerBlock = kWaves * kQPerWave;
-constexpr int kStageTok = 128;           // tokens per LDS stage
-constexpr int kStageLd = kDc + 8;        // LDS row stride in elements (272 B: conflict-free 16-byte reads)
-constexpr int kStageElems = kStageTok * kStageLd;
-constexpr int kMaxTilesPerBlock = 32;    // 1024 tokens: bounds the LDS column-maximum buffer
+constexpr int kTileLd = kDc + 8;         // LDS row stride in elements (272 B: conflict-free 16-byte reads)
+constexpr int kMaxTilesPerBlock = 16;    // 512 tokens: 136 KB of LDS
+constexpr int kPieces = kMaxTilesPerBlock * 32 * 16 / kThreads;   // 16-byte pieces per thread (16)
 
 __host__ __device__ inline int64_t mfma_tiles_per_block(int64_t n) {
   const int64_t n_tiles = (n + 31) / 32;
-  int64_t per = (n_tiles + 255) / 256;   // about one workgroup per compute unit
-  per = (per + 3) / 4 * 4;               // whole stages
-  return per < 4 ? 4 : (per > kMaxTilesPerBlock ? kMaxTilesPerBlock : per);
+  const int64_t per = (n_tiles + 255) / 256;   // about one workgroup per compute unit
+  return per < 1 ? 1 : (per > kMaxTilesPerBlock ? kMaxTilesPerBlock : per);
 }
 __host__ __device__ inline int64_t mfma_blocks(int64_t n) {
   const int64_t per = mfma_tiles_per_block(n);
   return ((n + 31) / 32 + per - 1) / per;
 }
+__host__ __device__ inline size_t mfma_lds_bytes(int64_t per) {
+  return (size_t)per * 32 * kTileLd * sizeof(bf16_t) + (size_t)per * 32 * sizeof(uint32_t);
+}
 
-// PASS 0: partial row maxima into part_max[block][l_c].  PASS 1: F into score, using mu[l_c].
+// PASS 0: partial row maxima into part_max[l_c][blocks].  PASS 1: F into score, using mu[l_c].
 template <int PASS>
 __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __restrict__ qc, int l_c,
                                                             const bf16_t* __restrict__ kc, int64_t m_lo, int64_t n,
@@ -126,50 +130,35 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
                                                             float* __restrict__ score, int64_t q_bs, int64_t kc_bs,
                                                             int64_t score_bs, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  bf16_t* stage = (bf16_t*)lds_raw;                                   // [2][kStageTok][kStageLd]
-  float* fpart = (float*)(lds_raw + 2 * kStageElems * sizeof(bf16_t)); // PASS 1: [kWaves][span] column maxima
+  const int span = tiles_per_block * 32;                               // tokens of this workgroup
+  bf16_t* ktile = (bf16_t*)lds_raw;                                    // [span][kTileLd]
+  uint32_t* colmax = (uint32_t*)(lds_raw + (size_t)span * kTileLd * sizeof(bf16_t));   // PASS 1: [span] keys
   const int b = blockIdx.y;
   const bf16_t* q = qc + (int64_t)b * q_bs;
   const bf16_t* kmid = kc + (int64_t)b * kc_bs + m_lo * (int64_t)kDc;
   const float* mu = mu_all + (int64_t)b * l_c;
+  const bool mu_vec = (((int64_t)b * l_c) & 3) == 0;     // 16-byte aligned groups of four row maxima
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, hi = lane >> 5;
-  const int64_t n_tiles = (n + 31) / 32;
-  const int64_t tile0 = (int64_t)blockIdx.x * tiles_per_block;
-  const int64_t tile1 = (tile0 + tiles_per_block) < n_tiles ? (tile0 + tiles_per_block) : n_tiles;
-  const int span = tiles_per_block * 32;
-  const int n_stages = (int)((tile1 - tile0 + 3) / 4);
-  const int64_t tok_base = tile0 * 32;
+  const int64_t tok_base = (int64_t)blockIdx.x * span;
+  const int n_tiles_here = (int)(((n - tok_base < span ? n - tok_base : span) + 31) / 32);
 
-  // One stage in flight between global memory and LDS: four 16-byte pieces per thread, kept in
-  // named registers.
-  uint4 s0, s1, s2, s3;
-  auto piece_src = [&](int s, int i) -> const uint4* {
-    const int id = tid + kThreads * i;
-    int64_t tok = tok_base + (int64_t)s * kStageTok + (id >> 4);
-    tok = tok < n ? tok : n - 1;           // a repeated token changes no maximum and is never stored
-    return (const uint4*)(kmid + tok * kDc + (id & 15) * 8);
-  };
-  auto piece_dst = [&](int s, int i) -> uint4* {
-    const int id = tid + kThreads * i;
-    return (uint4*)&stage[(s & 1) * kStageElems + (id >> 4) * kStageLd + (id & 15) * 8];
-  };
-#define ESA_STAGE_LOAD(s)                                                                       \
-  do {                                                                                          \
-    s0 = *piece_src(s, 0); s1 = *piece_src(s, 1); s2 = *piece_src(s, 2); s3 = *piece_src(s, 3); \
-  } while (0)
-#define ESA_STAGE_STORE(s)                                                                      \
-  do {                                                                                          \
-    *piece_dst(s, 0) = s0; *piece_dst(s, 1) = s1; *piece_dst(s, 2) = s2; *piece_dst(s, 3) = s3; \
-  } while (0)
+  // ---- this workgroup's K' rows: global -> registers, all in flight at once
+  uint4 piece[kPieces];
+#pragma unroll
+  for (int i = 0; i < kPieces; ++i) {
+    const int id = tid + kThreads * i;                   // row = id / 16, 16-byte column = id % 16
+    int row = id >> 4;
+    row = row < span ? row : span - 1;                   // short shares: surplus threads repeat the last row
+    int64_t tok = tok_base + row;
+    tok = tok < n ? tok : n - 1;                         // a repeated token changes no maximum and is never stored
+    piece[i] = *(const uint4*)(kmid + tok * kDc + (id & 15) * 8);
+  }
 
-  for (int qb = 0; qb * kQPerBlock < l_c; ++qb) {
+  bf16x8 a[kMT][kKSteps];
+  float aux[kMT][16];                    // PASS 0: running row maxima.  PASS 1: mu of the lane's rows.
+  auto load_query_block = [&](int qb) {
     const int q0 = qb * kQPerBlock + wave * kQPerWave;
-    int n_mt = (l_c - q0 + 31) / 32;     // 32-query tiles of this wave that hold at least one query
-    n_mt = n_mt < 0 ? 0 : (n_mt > kMT ? kMT : n_mt);
-
-    bf16x8 a[kMT][kKSteps];
-    float aux[kMT][16];                  // PASS 0: running row maxima.  PASS 1: mu of the lane's rows.
 #pragma unroll
     for (int mt = 0; mt < kMT; ++mt) {
       const int row = q0 + 32 * mt + r;
@@ -181,131 +170,121 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
         if (!ok) v = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
         a[mt][ks] = v;
       }
-      // Pin the fragments as arrived values: otherwise every use inside the stage loop carries a wait on
-      // the vector-memory counter, which would also wait for the stage loads just issued.
 #pragma unroll
-      for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(a[mt][ks]));
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int qrow = q0 + 32 * mt + 8 * g4 + 4 * hi;    // rows qrow .. qrow+3 live in registers 4*g4 .. 4*g4+3
         if (PASS == 0) {
-          aux[mt][v] = -INFINITY;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) aux[mt][4 * g4 + e] = -INFINITY;
+        } else if (mu_vec && qrow + 4 <= l_c) {
+          const float4 m4 = *(const float4*)(mu + qrow);
+          aux[mt][4 * g4 + 0] = m4.x;
+          aux[mt][4 * g4 + 1] = m4.y;
+          aux[mt][4 * g4 + 2] = m4.z;
+          aux[mt][4 * g4 + 3] = m4.w;
         } else {
-          const int qrow = q0 + 32 * mt + 8 * (v / 4) + 4 * hi + (v % 4);
-          aux[mt][v] = (qrow < l_c) ? mu[qrow] : INFINITY;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) aux[mt][4 * g4 + e] = (qrow + e < l_c) ? mu[qrow + e] : INFINITY;
         }
       }
-      if (PASS == 1) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(aux[mt][v]));
-      }
     }
+  };
 
-    __syncthreads();                     // the previous query block is done with both stage buffers
-    if (n_stages > 0) {
-      ESA_STAGE_LOAD(0);
-      ESA_STAGE_STORE(0);
-    }
-    for (int s = 0; s < n_stages; ++s) {
-      __syncthreads();
-      if (s + 1 < n_stages) ESA_STAGE_LOAD(s + 1);
-      const bf16_t* buf = stage + (s & 1) * kStageElems;
-      int nt_lim = (int)(tile1 - tile0) - 4 * s;
-      nt_lim = nt_lim > 4 ? 4 : nt_lim;
-      if (n_mt > 0) {
-        for (int nt = 0; nt < nt_lim; ++nt) {
-          bf16x8 bfr[kKSteps];
+  // The K' pieces were issued first, so they overlap the loads of the first query block.
+  load_query_block(0);
 #pragma unroll
-          for (int ks = 0; ks < kKSteps; ++ks)
-            bfr[ks] = *(const bf16x8*)&buf[(32 * nt + r) * kStageLd + 16 * ks + 8 * hi];
-          f32x16 acc[kMT];
+  for (int i = 0; i < kPieces; ++i) {
+    const int id = tid + kThreads * i;
+    int row = id >> 4;
+    row = row < span ? row : span - 1;                   // identical data to an identical place
+    *(uint4*)&ktile[row * kTileLd + (id & 15) * 8] = piece[i];
+  }
+  if (PASS == 1)
+    for (int i = tid; i < span; i += kThreads) colmax[i] = kOrderedKeyOfMinusInf;
+  __syncthreads();
+
+  for (int qb = 0; qb * kQPerBlock < l_c; ++qb) {
+    const int q0 = qb * kQPerBlock + wave * kQPerWave;
+    int n_mt = (l_c - q0 + 31) / 32;     // 32-query tiles of this wave that hold at least one query
+    n_mt = n_mt < 0 ? 0 : (n_mt > kMT ? kMT : n_mt);
+    if (qb > 0) load_query_block(qb);
+
+    if (n_mt > 0) {
+      for (int nt = 0; nt < n_tiles_here; ++nt) {
+        bf16x8 bfr[kKSteps];
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks)
+          bfr[ks] = *(const bf16x8*)&ktile[(32 * nt + r) * kTileLd + 16 * ks + 8 * hi];
+        f32x16 acc[kMT];
+#pragma unroll
+        for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks)
+#pragma unroll
+          for (int mt = 0; mt < kMT; ++mt)
+            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][ks], bfr[ks], acc[mt], 0, 0, 0);
+        if (PASS == 0) {
 #pragma unroll
           for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
+            for (int v = 0; v < 16; ++v) aux[mt][v] = fmaxf(aux[mt][v], acc[mt][v]);
+        } else {
+          float best = -INFINITY;
 #pragma unroll
-          for (int ks = 0; ks < kKSteps; ++ks)
+          for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
-            for (int mt = 0; mt < kMT; ++mt)
-              acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][ks], bfr[ks], acc[mt], 0, 0, 0);
-          if (PASS == 0) {
-#pragma unroll
-            for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-              for (int v = 0; v < 16; ++v) aux[mt][v] = fmaxf(aux[mt][v], acc[mt][v]);
-          } else {
-            float best = -INFINITY;
-#pragma unroll
-            for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-              for (int v = 0; v < 16; ++v) best = fmaxf(best, acc[mt][v] - aux[mt][v]);
-            best = fmaxf(best, __shfl_xor(best, 32, 64));
-            if (hi == 0) {
-              float* slot = &fpart[wave * span + (4 * s + nt) * 32 + r];
-              *slot = (qb == 0) ? best : fmaxf(*slot, best);
-            }
-          }
+            for (int v = 0; v < 16; ++v) best = fmaxf(best, acc[mt][v] - aux[mt][v]);
+          best = fmaxf(best, __shfl_xor(best, 32, 64));
+          if (hi == 0) atomicMax(&colmax[32 * nt + r], ordered_key(best));   // LDS, exact, order-free
         }
-      } else if (PASS == 1 && qb == 0) {
-        // a wave without queries still owns a column-maximum row: neutral element
-        for (int nt = 0; nt < nt_lim; ++nt)
-          if (hi == 0) fpart[wave * span + (4 * s + nt) * 32 + r] = -INFINITY;
       }
-      if (s + 1 < n_stages) ESA_STAGE_STORE(s + 1);
     }
 
-    if (PASS == 0) {
+    if (PASS == 0 && n_mt > 0) {
+      // 32 running maxima per lane, each to be reduced over the 32 lanes of a half-wave: a butterfly that
+      // halves the number of values per step (31 exchanges instead of 160); lane r ends up with value r.
+      float red[32];
 #pragma unroll
-      for (int mt = 0; mt < kMT; ++mt)
-        if (mt < n_mt) {
+      for (int i = 0; i < 32; ++i) red[i] = aux[i / 16][i % 16];
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            float m = aux[mt][v];
+      for (int off = 16, cnt = 32; off > 0; off >>= 1, cnt >>= 1) {
+        const bool upper = (r & off) != 0;
 #pragma unroll
-            for (int off = 16; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
-            const int qrow = q0 + 32 * mt + 8 * (v / 4) + 4 * hi + (v % 4);
-            if (r == 0 && qrow < l_c)
-              part_max[((int64_t)b * gridDim.x + blockIdx.x) * l_c + qrow] = m;
-          }
+        for (int i = 0; i < cnt / 2; ++i) {
+          const float lo_v = red[i], hi_v = red[i + cnt / 2];
+          const float keep = upper ? hi_v : lo_v, send = upper ? lo_v : hi_v;
+          red[i] = fmaxf(keep, __shfl_xor(send, off, 64));
         }
+      }
+      const int mt = r / 16, v = r % 16;
+      const int qrow = q0 + 32 * mt + 8 * (v / 4) + 4 * hi + (v % 4);
+      if (qrow < l_c) part_max[((int64_t)b * l_c + qrow) * gridDim.x + blockIdx.x] = red[0];
     }
   }
 
   if (PASS == 1) {
     __syncthreads();
     for (int i = tid; i < span; i += kThreads) {
-      const int64_t m = tile0 * 32 + i;
-      if (m < n && m < tile1 * 32) {
-        float f = fpart[i];
-#pragma unroll
-        for (int w = 1; w < kWaves; ++w) f = fmaxf(f, fpart[w * span + i]);
-        score[(int64_t)b * score_bs + m] = f;
-      }
+      const int64_t m = tok_base + i;
+      if (m < n) score[(int64_t)b * score_bs + m] = ordered_key_to_f32(colmax[i]);
     }
   }
 }
 
-#undef ESA_STAGE_LOAD
-#undef ESA_STAGE_STORE
-
-// mu[c] = max over workgroups of their partial row maxima.  16 queries per block, 16 slices of the
-// workgroup list per query, combined through LDS.
+// mu[c] = max over workgroups of their partial row maxima ([l_c][blocks] layout): one wave per query.
 __global__ __launch_bounds__(256) void score_rowmax_reduce(const float* __restrict__ part_max, int nblk, int l_c,
                                                            float* __restrict__ mu) {
-  __shared__ float red[16][17];
-  const int cl = threadIdx.x & 15, slice = threadIdx.x >> 4;
-  const int c = blockIdx.x * 16 + cl;
+  const int lane = threadIdx.x & 63;
+  const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int b = blockIdx.y;
+  if (c >= l_c) return;
+  const float* p = part_max + ((int64_t)b * l_c + c) * nblk;
   float m = -INFINITY;
-  if (c < l_c)
-    for (int i = slice; i < nblk; i += 16) m = fmaxf(m, part_max[((int64_t)b * nblk + i) * l_c + c]);
-  red[slice][cl] = m;
-  __syncthreads();
-  if (threadIdx.x < 16 && c < l_c) {
-    float t = red[0][cl];
-#pragma unroll
-    for (int i = 1; i < 16; ++i) t = fmaxf(t, red[i][cl]);
-    mu[(int64_t)b * l_c + c] = t;
-  }
+  for (int i = lane; i < nblk; i += 64) m = fmaxf(m, p[i]);
+  m = wave_max(m);
+  if (lane == 0) mu[(int64_t)b * l_c + c] = m;
 }
 
 // ------------------------------------------------------------------------------------------ decode (l_c = 1)
@@ -421,21 +400,20 @@ int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, in
     const dim3 grid(nblk, batch);
     float* part = (float*)((char*)ws + mu_bytes(l_c, batch));
     float* muf = (float*)ws;
-    const size_t lds0 = (size_t)2 * kStageElems * sizeof(bf16_t);
-    const size_t lds1 = lds0 + (size_t)kWaves * per * 32 * sizeof(float);
+    const size_t lds0 = mfma_lds_bytes(per), lds1 = lds0;
     static bool lds_limit_raised = false;      // idempotent; a race only repeats the call
     if (!lds_limit_raised) {
+      const int most = (int)mfma_lds_bytes(kMaxTilesPerBlock);
       hipError_t e = hipFuncSetAttribute((const void*)score_mfma_bf16<0>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)lds0);
+                                         most);
       if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)score_mfma_bf16<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)(lds0 + (size_t)kWaves * kMaxTilesPerBlock * 32 * sizeof(float)));
+        e = hipFuncSetAttribute((const void*)score_mfma_bf16<1>, hipFuncAttributeMaxDynamicSharedMemorySize, most);
       if (e != hipSuccess) return hip_failed(e, "hipFuncSetAttribute(score_mfma_bf16)");
       lds_limit_raised = true;
     }
     score_mfma_bf16<0><<<grid, kThreads, lds0, st>>>((const bf16_t*)qc, l_c, (const bf16_t*)kc_cache, m_lo, n, part, muf,
                                                 raw, q_bs, kc_bs, raw_bs, per);
-    score_rowmax_reduce<<<dim3((l_c + 15) / 16, batch), 256, 0, st>>>(part, nblk, l_c, muf);
+    score_rowmax_reduce<<<dim3((l_c + 3) / 4, batch), 256, 0, st>>>(part, nblk, l_c, muf);
     score_mfma_bf16<1><<<grid, kThreads, lds1, st>>>((const bf16_t*)qc, l_c, (const bf16_t*)kc_cache, m_lo, n, part, muf,
                                                 raw, q_bs, kc_bs, raw_bs, per);
   } else {

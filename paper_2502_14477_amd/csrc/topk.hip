@@ -5,9 +5,11 @@
 // k-th largest score and how many scores equal to T are still needed; a counting pass and a
 // writing pass then emit the positions of every score above T plus the first `need` scores
 // equal to T, in ascending position order (equal scores: the lower position wins).
-// All cross-block traffic is integer atomics, so the result is deterministic.  The block that
-// finishes a pass last (ticket counter) does that pass's serial step; no block ever waits for
-// another, so no co-residency is assumed.
+// All cross-block traffic is integer atomics and plain stores, so the result is deterministic.
+// No workgroup ever waits for another: what one pass leaves in global memory (a 2048-bin
+// histogram, or the per-block counts) is re-read and scanned by EVERY workgroup of the next
+// launch, redundantly, instead of being finished by a last-arriving workgroup — a launch is then
+// one round trip to memory plus a little LDS work, which is what bounds this latency-bound call.
 #include "esa_common.h"
 
 namespace esa {
@@ -21,17 +23,10 @@ constexpr int kBins = 2048;
 // Workspace of one batch row, in uint32 words.
 struct TopkLayout {
   static constexpr int hist = 0;                         // [3][kBins]
-  static constexpr int prefix = 3 * kBins;               // key bits fixed so far
-  static constexpr int k_rem = prefix + 1;               // scores still to take at/below the prefix
-  static constexpr int done = prefix + 2;                // [4] ticket counters: three histogram passes, count
-  static constexpr int blk = prefix + 8;                 // [2][nblk]: above-T and equal-T counts / offsets
+  static constexpr int blk = 3 * kBins;                  // [2][nblk]: above-T and equal-T counts per block
 };
 
 __host__ __device__ inline int64_t topk_row_words(int64_t nblk) { return TopkLayout::blk + 2 * nblk; }
-
-__device__ __forceinline__ uint32_t coherent_load(const uint32_t* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 // Exclusive prefix sum of one value per thread over the block; *total gets the block sum.
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* total, uint32_t* wave_sums) {
@@ -66,90 +61,145 @@ __device__ __forceinline__ void load_keys(const float* row, int64_t n, int64_t f
   }
 }
 
-__global__ void topk_init(uint32_t* ws, int64_t row_words, int k_eff) {
-  uint32_t* w = ws + (int64_t)blockIdx.x * row_words;
-  for (int i = threadIdx.x; i < TopkLayout::blk; i += blockDim.x) w[i] = 0u;
+// One thread's share of a finished 2048-bin histogram; thread 0 owns the highest bins.
+constexpr int kBinsPerThread = kBins / kThreads;
+struct BinSlice {
+  uint32_t c[kBinsPerThread];
+};
+__device__ __forceinline__ BinSlice load_slice(const uint32_t* __restrict__ gh) {
+  BinSlice s;
+  const int top = kBins - 1 - threadIdx.x * kBinsPerThread;
+#pragma unroll
+  for (int e = 0; e < kBinsPerThread; ++e) s.c[e] = gh[top - e];
+  return s;
+}
+
+// Where rank k_rem falls in a histogram, walking from the top bin down: the bin, and the rank
+// inside that bin.  Every thread of the block gets the result.
+struct BinPick {
+  uint32_t bin, k_rem;
+};
+__device__ __forceinline__ BinPick pick_bin(const BinSlice& sl, uint32_t k_rem, uint32_t* wave_sums,
+                                            uint32_t* result) {
+  const int top = kBins - 1 - threadIdx.x * kBinsPerThread;
+  uint32_t mine = 0;
+#pragma unroll
+  for (int e = 0; e < kBinsPerThread; ++e) mine += sl.c[e];
+  uint32_t total;
+  const uint32_t above = block_excl_scan(mine, &total, wave_sums);
+  if (above < k_rem && k_rem <= above + mine) {          // exactly one thread
+    uint32_t cum = above;
+    bool done = false;
+#pragma unroll
+    for (int e = 0; e < kBinsPerThread; ++e) {
+      if (!done && cum + sl.c[e] >= k_rem) {
+        result[0] = (uint32_t)(top - e);
+        result[1] = k_rem - cum;
+        done = true;
+      }
+      cum += sl.c[e];
+    }
+  }
   __syncthreads();
-  if (threadIdx.x == 0) w[TopkLayout::k_rem] = (uint32_t)k_eff;
+  BinPick r;
+  r.bin = result[0];
+  r.k_rem = result[1];
+  __syncthreads();                       // result[] is free for the next pick
+  return r;
+}
+
+// Key bits fixed by the passes before PASS, and the rank still to find below them.  All
+// histogram loads are issued before the first scan, so they cost one round trip together.
+template <int PASS>
+__device__ __forceinline__ void resolve_prefix(const uint32_t* __restrict__ w, uint32_t k, uint32_t* wave_sums,
+                                               uint32_t* result, uint32_t* prefix, uint32_t* k_rem) {
+  BinSlice s0, s1, s2;
+  if (PASS >= 1) s0 = load_slice(w + TopkLayout::hist);
+  if (PASS >= 2) s1 = load_slice(w + TopkLayout::hist + kBins);
+  if (PASS >= 3) s2 = load_slice(w + TopkLayout::hist + 2 * kBins);
+  uint32_t p = 0, kr = k;
+  if (PASS >= 1) {
+    const BinPick b0 = pick_bin(s0, kr, wave_sums, result);
+    p = b0.bin << 21;
+    kr = b0.k_rem;
+  }
+  if (PASS >= 2) {
+    const BinPick b1 = pick_bin(s1, kr, wave_sums, result);
+    p |= b1.bin << 10;
+    kr = b1.k_rem;
+  }
+  if (PASS >= 3) {
+    const BinPick b2 = pick_bin(s2, kr, wave_sums, result);
+    p |= b2.bin;
+    kr = b2.k_rem;
+  }
+  *prefix = p;
+  *k_rem = kr;
+}
+
+__global__ void topk_init(uint32_t* ws, int64_t row_words) {
+  uint32_t* w = ws + (int64_t)blockIdx.y * row_words;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < 3 * kBins; i += gridDim.x * blockDim.x) w[i] = 0u;
+}
+
+// One LDS-histogram increment per lane, with the lanes of a wave that hit the leader's bin
+// folded into a single atomic (scores of one row share their exponent, so in the first pass
+// almost every lane hits the same bin).
+__device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t bin) {
+  const uint64_t act = __ballot(active);
+  if (act == 0ull) return;
+  const int leader = __ffsll((long long)act) - 1;
+  const uint32_t lead_bin = __shfl(bin, leader, 64);
+  const uint64_t same = __ballot(active && bin == lead_bin);
+  if ((int)(threadIdx.x & 63) == leader) atomicAdd(&h[lead_bin], (uint32_t)__popcll(same));
+  if (active && bin != lead_bin) atomicAdd(&h[bin], 1u);
 }
 
 // PASS 0: bits 31..21, PASS 1: bits 20..10, PASS 2: bits 9..0.
 template <int PASS>
 __global__ __launch_bounds__(kThreads) void topk_hist(const float* __restrict__ score, int64_t n, int64_t score_bs,
-                                                      uint32_t* __restrict__ ws, int64_t row_words, int nblk) {
+                                                      uint32_t* __restrict__ ws, int64_t row_words, uint32_t k) {
   __shared__ uint32_t h[kBins];
   __shared__ uint32_t wave_sums[kThreads / 64];
-  __shared__ int is_last;
+  __shared__ uint32_t result[2];
   const float* row = score + (int64_t)blockIdx.y * score_bs;
   uint32_t* w = ws + (int64_t)blockIdx.y * row_words;
-  for (int i = threadIdx.x; i < kBins; i += kThreads) h[i] = 0u;
-  const uint32_t prefix = (PASS == 0) ? 0u : w[TopkLayout::prefix];
-  __syncthreads();
-
   uint32_t key[kItems];
   bool ok[kItems];
   load_keys(row, n, (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems, key, ok);
+  for (int i = threadIdx.x; i < kBins; i += kThreads) h[i] = 0u;
+  uint32_t prefix, k_rem;
+  resolve_prefix<PASS>(w, k, wave_sums, result, &prefix, &k_rem);
+  __syncthreads();
 #pragma unroll
   for (int e = 0; e < kItems; ++e) {
-    if (!ok[e]) continue;
     if (PASS == 0) {
-      atomicAdd(&h[key[e] >> 21], 1u);
+      hist_add(h, ok[e], key[e] >> 21);
     } else if (PASS == 1) {
-      if ((key[e] >> 21) == (prefix >> 21)) atomicAdd(&h[(key[e] >> 10) & 2047u], 1u);
+      hist_add(h, ok[e] && (key[e] >> 21) == (prefix >> 21), (key[e] >> 10) & 2047u);
     } else {
-      if ((key[e] >> 10) == (prefix >> 10)) atomicAdd(&h[key[e] & 1023u], 1u);
+      hist_add(h, ok[e] && (key[e] >> 10) == (prefix >> 10), key[e] & 1023u);
     }
   }
   __syncthreads();
   uint32_t* gh = w + TopkLayout::hist + PASS * kBins;
   for (int i = threadIdx.x; i < kBins; i += kThreads)
     if (h[i]) atomicAdd(&gh[i], h[i]);
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) is_last = (atomicAdd(&w[TopkLayout::done + PASS], 1u) == (uint32_t)(nblk - 1));
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-
-  // Serial step: walk the finished histogram from the top bin down to the bin holding rank k_rem.
-  for (int i = threadIdx.x; i < kBins; i += kThreads) h[i] = coherent_load(&gh[i]);
-  const uint32_t k_rem = coherent_load(&w[TopkLayout::k_rem]);
-  __syncthreads();
-  constexpr int per = kBins / kThreads;                  // bins per thread, thread 0 owns the highest
-  const int top = kBins - 1 - threadIdx.x * per;
-  uint32_t mine = 0;
-#pragma unroll
-  for (int e = 0; e < per; ++e) mine += h[top - e];
-  uint32_t total;
-  const uint32_t above = block_excl_scan(mine, &total, wave_sums);
-  if (above < k_rem && k_rem <= above + mine) {          // exactly one thread
-    uint32_t cum = above;
-    for (int e = 0; e < per; ++e) {
-      const uint32_t c = h[top - e];
-      if (cum + c >= k_rem) {
-        const uint32_t bin = (uint32_t)(top - e);
-        const uint32_t shift = (PASS == 0) ? 21u : (PASS == 1) ? 10u : 0u;
-        w[TopkLayout::prefix] = prefix | (bin << shift);
-        w[TopkLayout::k_rem] = k_rem - cum;
-        break;
-      }
-      cum += c;
-    }
-  }
 }
 
-// Per block: how many scores lie above T and how many equal T; the last block turns both
-// arrays into exclusive offsets.
+// Per block: how many scores lie above T and how many equal T.
 __global__ __launch_bounds__(kThreads) void topk_count(const float* __restrict__ score, int64_t n, int64_t score_bs,
-                                                       uint32_t* __restrict__ ws, int64_t row_words, int nblk) {
+                                                       uint32_t* __restrict__ ws, int64_t row_words, int nblk,
+                                                       uint32_t k) {
   __shared__ uint32_t wave_sums[kThreads / 64];
-  __shared__ int is_last;
+  __shared__ uint32_t result[2];
   const float* row = score + (int64_t)blockIdx.y * score_bs;
   uint32_t* w = ws + (int64_t)blockIdx.y * row_words;
-  const uint32_t T = w[TopkLayout::prefix];
   uint32_t key[kItems];
   bool ok[kItems];
   load_keys(row, n, (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems, key, ok);
+  uint32_t T, need;
+  resolve_prefix<3>(w, k, wave_sums, result, &T, &need);
   uint32_t gt = 0, eq = 0;
 #pragma unroll
   for (int e = 0; e < kItems; ++e) {
@@ -159,50 +209,36 @@ __global__ __launch_bounds__(kThreads) void topk_count(const float* __restrict__
   uint32_t tot_gt, tot_eq;
   block_excl_scan(gt, &tot_gt, wave_sums);
   block_excl_scan(eq, &tot_eq, wave_sums);
-  uint32_t* bg = w + TopkLayout::blk;
-  uint32_t* be = bg + nblk;
   if (threadIdx.x == 0) {
-    __hip_atomic_store(&bg[blockIdx.x], tot_gt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(&be[blockIdx.x], tot_eq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __threadfence();
-    is_last = (atomicAdd(&w[TopkLayout::done + 3], 1u) == (uint32_t)(nblk - 1));
-  }
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-  uint32_t carry_gt = 0, carry_eq = 0;
-  for (int base = 0; base < nblk; base += kThreads) {
-    const int i = base + threadIdx.x;
-    const uint32_t g = (i < nblk) ? coherent_load(&bg[i]) : 0u;
-    const uint32_t q = (i < nblk) ? coherent_load(&be[i]) : 0u;
-    uint32_t tg, tq;
-    const uint32_t xg = block_excl_scan(g, &tg, wave_sums);
-    const uint32_t xq = block_excl_scan(q, &tq, wave_sums);
-    if (i < nblk) {
-      bg[i] = carry_gt + xg;
-      be[i] = carry_eq + xq;
-    }
-    carry_gt += tg;
-    carry_eq += tq;
+    w[TopkLayout::blk + blockIdx.x] = tot_gt;
+    w[TopkLayout::blk + nblk + blockIdx.x] = tot_eq;
   }
 }
 
 __global__ __launch_bounds__(kThreads) void topk_write(const float* __restrict__ score, int64_t n, int64_t score_bs,
                                                        const uint32_t* __restrict__ ws, int64_t row_words, int nblk,
                                                        int64_t base, int32_t* __restrict__ idx, int64_t idx_bs,
-                                                       int k_eff) {
+                                                       uint32_t k) {
   __shared__ uint32_t wave_sums[kThreads / 64];
+  __shared__ uint32_t result[2];
   const float* row = score + (int64_t)blockIdx.y * score_bs;
   const uint32_t* w = ws + (int64_t)blockIdx.y * row_words;
   int32_t* out = idx + (int64_t)blockIdx.y * idx_bs;
-  const uint32_t T = w[TopkLayout::prefix];
-  const uint32_t need = w[TopkLayout::k_rem];            // equal-to-T scores to take, lowest positions first
-  const uint32_t off_gt = w[TopkLayout::blk + blockIdx.x];
-  const uint32_t off_eq = w[TopkLayout::blk + nblk + blockIdx.x];
   const int64_t first = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems;
   uint32_t key[kItems];
   bool ok[kItems];
   load_keys(row, n, first, key, ok);
+  // scores above / equal to T in the blocks before this one
+  uint32_t my_gt = 0, my_eq = 0;
+  for (int i = threadIdx.x; i < (int)blockIdx.x; i += kThreads) {
+    my_gt += w[TopkLayout::blk + i];
+    my_eq += w[TopkLayout::blk + nblk + i];
+  }
+  uint32_t off_gt, off_eq;
+  block_excl_scan(my_gt, &off_gt, wave_sums);
+  block_excl_scan(my_eq, &off_eq, wave_sums);
+  uint32_t T, need;                                      // need: equal-to-T scores to take, lowest positions first
+  resolve_prefix<3>(w, k, wave_sums, result, &T, &need);
   uint32_t gt = 0, eq = 0;
 #pragma unroll
   for (int e = 0; e < kItems; ++e) {
@@ -218,7 +254,7 @@ __global__ __launch_bounds__(kThreads) void topk_write(const float* __restrict__
     const bool is_gt = key[e] > T, is_eq = key[e] == T;
     if (is_gt || (is_eq && e_before < need)) {
       const uint32_t slot = g_before + (e_before < need ? e_before : need);
-      if (slot < (uint32_t)k_eff) out[slot] = (int32_t)(base + first + e);
+      if (slot < k) out[slot] = (int32_t)(base + first + e);
     }
     g_before += is_gt ? 1u : 0u;
     e_before += is_eq ? 1u : 0u;
@@ -253,12 +289,12 @@ int launch_topk(const float* score, int64_t n, int k, int64_t base, int32_t* idx
   const int64_t row_words = (int64_t)(align_up((size_t)topk_row_words(nblk) * sizeof(uint32_t), 256) / sizeof(uint32_t));
   uint32_t* w = (uint32_t*)ws;
   const dim3 grid(nblk, batch);
-  topk_init<<<batch, 256, 0, st>>>(w, row_words, k);
-  topk_hist<0><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk);
-  topk_hist<1><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk);
-  topk_hist<2><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk);
-  topk_count<<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk);
-  topk_write<<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, base, idx, idx_bs, k);
+  topk_init<<<dim3(3, batch), 1024, 0, st>>>(w, row_words);
+  topk_hist<0><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, (uint32_t)k);
+  topk_hist<1><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, (uint32_t)k);
+  topk_hist<2><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, (uint32_t)k);
+  topk_count<<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, (uint32_t)k);
+  topk_write<<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, base, idx, idx_bs, (uint32_t)k);
   ESA_LAUNCH_CHECK("topk");
   return ESA_OK;
 }
