@@ -143,18 +143,6 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
   const int64_t tok_base = (int64_t)blockIdx.x * span;
   const int n_tiles_here = (int)(((n - tok_base < span ? n - tok_base : span) + 31) / 32);
 
-  // ---- this workgroup's K' rows: global -> registers, all in flight at once
-  uint4 piece[kPieces];
-#pragma unroll
-  for (int i = 0; i < kPieces; ++i) {
-    const int id = tid + kThreads * i;                   // row = id / 16, 16-byte column = id % 16
-    int row = id >> 4;
-    row = row < span ? row : span - 1;                   // short shares: surplus threads repeat the last row
-    int64_t tok = tok_base + row;
-    tok = tok < n ? tok : n - 1;                         // a repeated token changes no maximum and is never stored
-    piece[i] = *(const uint4*)(kmid + tok * kDc + (id & 15) * 8);
-  }
-
   bf16x8 a[kMT][kKSteps];
   float aux[kMT][16];                    // PASS 0: running row maxima.  PASS 1: mu of the lane's rows.
   auto load_query_block = [&](int qb) {
@@ -190,77 +178,119 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
     }
   };
 
-  // The K' pieces were issued first, so they overlap the loads of the first query block.
-  load_query_block(0);
+  // One 32-token tile against this wave's queries.
+  auto compute_tile = [&](int nt) {
+    bf16x8 bfr[kKSteps];
 #pragma unroll
-  for (int i = 0; i < kPieces; ++i) {
+    for (int ks = 0; ks < kKSteps; ++ks)
+      bfr[ks] = *(const bf16x8*)&ktile[(32 * nt + r) * kTileLd + 16 * ks + 8 * hi];
+    f32x16 acc[kMT];
+#pragma unroll
+    for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < kKSteps; ++ks)
+#pragma unroll
+      for (int mt = 0; mt < kMT; ++mt)
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][ks], bfr[ks], acc[mt], 0, 0, 0);
+    if (PASS == 0) {
+#pragma unroll
+      for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) aux[mt][v] = fmaxf(aux[mt][v], acc[mt][v]);
+    } else {
+      float best = -INFINITY;
+#pragma unroll
+      for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) best = fmaxf(best, acc[mt][v] - aux[mt][v]);
+      best = fmaxf(best, __shfl_xor(best, 32, 64));
+      if (hi == 0) atomicMax(&colmax[32 * nt + r], ordered_key(best));   // LDS, exact, order-free
+    }
+  };
+
+  // PASS 0: 32 running maxima per lane, each to be reduced over the 32 lanes of a half-wave: a butterfly
+  // that halves the number of values per step (31 exchanges instead of 160); lane r ends up with value r.
+  auto flush_row_maxima = [&](int q0) {
+    float red[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) red[i] = aux[i / 16][i % 16];
+#pragma unroll
+    for (int off = 16, cnt = 32; off > 0; off >>= 1, cnt >>= 1) {
+      const bool upper = (r & off) != 0;
+#pragma unroll
+      for (int i = 0; i < cnt / 2; ++i) {
+        const float lo_v = red[i], hi_v = red[i + cnt / 2];
+        const float keep = upper ? hi_v : lo_v, send = upper ? lo_v : hi_v;
+        red[i] = fmaxf(keep, __shfl_xor(send, off, 64));
+      }
+    }
+    const int mt = r / 16, v = r % 16;
+    const int qrow = q0 + 32 * mt + 8 * (v / 4) + 4 * hi + (v % 4);
+    if (qrow < l_c) part_max[((int64_t)b * l_c + qrow) * gridDim.x + blockIdx.x] = red[0];
+  };
+
+  // ---- first query block.  Its fragments are requested first, then this workgroup's K' rows, one
+  // 16-byte piece per thread and tile, all in flight at once.  Loads complete in order, so tile t can
+  // be copied to LDS and used as soon as piece t has arrived, while the later pieces are still
+  // landing: memory streaming and matrix work overlap without any dependent round trips.
+  load_query_block(0);
+  auto piece_src = [&](int i) -> const uint4* {
+    const int id = tid + kThreads * i;                   // row = id / 16 (tile i), 16-byte column = id % 16
+    int row = id >> 4;
+    row = row < span ? row : span - 1;                   // short shares: surplus threads repeat the last row
+    int64_t tok = tok_base + row;
+    tok = tok < n ? tok : n - 1;                         // a repeated token changes no maximum and is never stored
+    return (const uint4*)(kmid + tok * kDc + (id & 15) * 8);
+  };
+  auto piece_dst = [&](int i) -> uint4* {
     const int id = tid + kThreads * i;
     int row = id >> 4;
     row = row < span ? row : span - 1;                   // identical data to an identical place
-    *(uint4*)&ktile[row * kTileLd + (id & 15) * 8] = piece[i];
-  }
+    return (uint4*)&ktile[row * kTileLd + (id & 15) * 8];
+  };
+  static_assert(kPieces == 16, "the staging below is written out for sixteen pieces");
+  const uint4 p0 = *piece_src(0), p1 = *piece_src(1), p2 = *piece_src(2), p3 = *piece_src(3);
+  const uint4 p4 = *piece_src(4), p5 = *piece_src(5), p6 = *piece_src(6), p7 = *piece_src(7);
+  const uint4 p8 = *piece_src(8), p9 = *piece_src(9), p10 = *piece_src(10), p11 = *piece_src(11);
+  const uint4 p12 = *piece_src(12), p13 = *piece_src(13), p14 = *piece_src(14), p15 = *piece_src(15);
   if (PASS == 1)
     for (int i = tid; i < span; i += kThreads) colmax[i] = kOrderedKeyOfMinusInf;
-  __syncthreads();
-
-  for (int qb = 0; qb * kQPerBlock < l_c; ++qb) {
-    const int q0 = qb * kQPerBlock + wave * kQPerWave;
-    int n_mt = (l_c - q0 + 31) / 32;     // 32-query tiles of this wave that hold at least one query
+  {
+    int n_mt = (l_c - wave * kQPerWave + 31) / 32;       // 32-query tiles of this wave that hold a query
     n_mt = n_mt < 0 ? 0 : (n_mt > kMT ? kMT : n_mt);
-    if (qb > 0) load_query_block(qb);
+#define ESA_SCORE_STAGE(s, pa, pb)                              \
+  do {                                                          \
+    *piece_dst(2 * (s)) = pa;                                   \
+    *piece_dst(2 * (s) + 1) = pb;                               \
+    __syncthreads();                                            \
+    if (n_mt > 0) {                                             \
+      if (2 * (s) < n_tiles_here) compute_tile(2 * (s));        \
+      if (2 * (s) + 1 < n_tiles_here) compute_tile(2 * (s) + 1); \
+    }                                                           \
+  } while (0)
+    ESA_SCORE_STAGE(0, p0, p1);
+    ESA_SCORE_STAGE(1, p2, p3);
+    ESA_SCORE_STAGE(2, p4, p5);
+    ESA_SCORE_STAGE(3, p6, p7);
+    ESA_SCORE_STAGE(4, p8, p9);
+    ESA_SCORE_STAGE(5, p10, p11);
+    ESA_SCORE_STAGE(6, p12, p13);
+    ESA_SCORE_STAGE(7, p14, p15);
+#undef ESA_SCORE_STAGE
+    if (PASS == 0 && n_mt > 0) flush_row_maxima(wave * kQPerWave);
+  }
 
+  // ---- further query blocks (chunks longer than 512 tokens) run against the tile already in LDS
+  for (int qb = 1; qb * kQPerBlock < l_c; ++qb) {
+    const int q0 = qb * kQPerBlock + wave * kQPerWave;
+    int n_mt = (l_c - q0 + 31) / 32;
+    n_mt = n_mt < 0 ? 0 : (n_mt > kMT ? kMT : n_mt);
+    load_query_block(qb);
     if (n_mt > 0) {
-      for (int nt = 0; nt < n_tiles_here; ++nt) {
-        bf16x8 bfr[kKSteps];
-#pragma unroll
-        for (int ks = 0; ks < kKSteps; ++ks)
-          bfr[ks] = *(const bf16x8*)&ktile[(32 * nt + r) * kTileLd + 16 * ks + 8 * hi];
-        f32x16 acc[kMT];
-#pragma unroll
-        for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < kKSteps; ++ks)
-#pragma unroll
-          for (int mt = 0; mt < kMT; ++mt)
-            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][ks], bfr[ks], acc[mt], 0, 0, 0);
-        if (PASS == 0) {
-#pragma unroll
-          for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) aux[mt][v] = fmaxf(aux[mt][v], acc[mt][v]);
-        } else {
-          float best = -INFINITY;
-#pragma unroll
-          for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) best = fmaxf(best, acc[mt][v] - aux[mt][v]);
-          best = fmaxf(best, __shfl_xor(best, 32, 64));
-          if (hi == 0) atomicMax(&colmax[32 * nt + r], ordered_key(best));   // LDS, exact, order-free
-        }
-      }
-    }
-
-    if (PASS == 0 && n_mt > 0) {
-      // 32 running maxima per lane, each to be reduced over the 32 lanes of a half-wave: a butterfly that
-      // halves the number of values per step (31 exchanges instead of 160); lane r ends up with value r.
-      float red[32];
-#pragma unroll
-      for (int i = 0; i < 32; ++i) red[i] = aux[i / 16][i % 16];
-#pragma unroll
-      for (int off = 16, cnt = 32; off > 0; off >>= 1, cnt >>= 1) {
-        const bool upper = (r & off) != 0;
-#pragma unroll
-        for (int i = 0; i < cnt / 2; ++i) {
-          const float lo_v = red[i], hi_v = red[i + cnt / 2];
-          const float keep = upper ? hi_v : lo_v, send = upper ? lo_v : hi_v;
-          red[i] = fmaxf(keep, __shfl_xor(send, off, 64));
-        }
-      }
-      const int mt = r / 16, v = r % 16;
-      const int qrow = q0 + 32 * mt + 8 * (v / 4) + 4 * hi + (v % 4);
-      if (qrow < l_c) part_max[((int64_t)b * l_c + qrow) * gridDim.x + blockIdx.x] = red[0];
+      for (int nt = 0; nt < n_tiles_here; ++nt) compute_tile(nt);
+      if (PASS == 0) flush_row_maxima(q0);
     }
   }
 
