@@ -27,6 +27,18 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
+# HBM bytes per launch from the rocprofv3 counter passes summarised under profiles/ (FETCH_SIZE and
+# WRITE_SIZE per dispatch, each scaled by what the same counter reads for a plain 256 MiB device copy:
+# x2.0 for FETCH_SIZE, x1.0 for WRITE_SIZE), summed over the kernels of the call.  Counters cannot be
+# read from inside this script, so the figure is attached only to the workload it was measured on.
+MEASURED_TRAFFIC_BYTES = {
+    ("C3", 131072, "attend"): 1024.0 * (2.0 * (11596.6 + 16923.5) + (33332.6 + 4096.0)),
+    ("C3", 131072, "score"): 1024.0 * (2.0 * (16685.0 + 16700.0 + 266.5) + (3986.0 + 501.5 + 4.0)),
+    ("C3", 131072, "select"): 1024.0 * (2.0 * (3.8 + 277.8 + 319.8 + 357.8 + 387.2 + 404.7)
+                                        + (24.0 + 4.8 + 106.3 + 0.1 + 3.9 + 9.7)),
+    ("C3", 131072, "gather"): 1024.0 * (2.0 * 4137.1 + 8192.0),
+}
+
 
 def algorithmic_work(cfg, t0, n_mid, k_eff, l_c):
     """Per-step algorithmic FLOPs / bytes of each call (Appendix A of the paper; causal part at half)."""
@@ -55,6 +67,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true",
                     help="time eager launches instead of replaying the step as a captured HIP graph")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain device copy of the key cache (calibrates HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -95,25 +109,16 @@ def main():
 
     calls = ("compress", "score", "select", "gather", "attend")
 
-    def step(events=None):
-        def mark(i):
-            if events is not None:
-                events[i].record()
-        mark(0)
+    def step():
         qc = esa.esa_compress(Q, W_q)
         esa.esa_compress(K[t0:t0 + l_c], W_k, out=kc[t0:t0 + l_c])
-        mark(1)
         if n_mid > cfg.k:
             score = esa.esa_score(qc, kc, i_end, l_start)
         else:
             score = torch.zeros(max(n_mid, 1), dtype=torch.float32, device="cuda")[:n_mid]
-        mark(2)
         idx = esa.esa_select_topk(score, cfg.k, base=i_end)
-        mark(3)
         ks, vs = esa.esa_gather_kv(K, V, idx)
-        mark(4)
         out = esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks, vs)
-        mark(5)
         return out
 
     def timed(fn, n):
@@ -146,15 +151,56 @@ def main():
         torch.cuda.synchronize()
         assert torch.equal(ref, graph_out), "graph replay and eager step disagree"
 
-    # per-call durations from HIP events on the launch stream (torch's current stream)
-    per_call = {c: [] for c in calls}
-    for _ in range(max(5, min(args.steps, 30))):
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
-        step(ev)
+    # Per-call durations from HIP events on the launch stream (torch's current stream).  Each call is
+    # issued `reps` times back to back between two events, as one captured graph (as separate launches
+    # under --eager), so that the figure is the kernels' own duration and not the host's launch gaps.
+    qc_s = esa.esa_compress(Q, W_q)
+    score_s = esa.esa_score(qc_s, kc, i_end, l_start) if n_mid > cfg.k else \
+        torch.zeros(max(n_mid, 1), dtype=torch.float32, device="cuda")[:n_mid]
+    idx_s = esa.esa_select_topk(score_s, cfg.k, base=i_end)
+    ks_s, vs_s = esa.esa_gather_kv(K, V, idx_s)
+
+    def call_compress():
+        esa.esa_compress(Q, W_q, out=qc_s)
+        esa.esa_compress(K[t0:t0 + l_c], W_k, out=kc[t0:t0 + l_c])
+
+    single = {
+        "compress": call_compress,
+        "score": (lambda: esa.esa_score(qc_s, kc, i_end, l_start)) if n_mid > cfg.k else (lambda: None),
+        "select": lambda: esa.esa_select_topk(score_s, cfg.k, base=i_end),
+        "gather": lambda: esa.esa_gather_kv(K, V, idx_s),
+        "attend": lambda: esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s),
+    }
+    reps, rounds = 10, max(3, min(args.steps, 10))
+    call_ms = {}
+    for c in calls:
+        def burst(fn=single[c]):
+            for _ in range(reps):
+                fn()
+        burst()
         torch.cuda.synchronize()
-        for i, c in enumerate(calls):
-            per_call[c].append(ev[i].elapsed_time(ev[i + 1]))
-    call_ms = {c: float(np.mean(v)) for c, v in per_call.items()}
+        run = burst
+        if not args.eager:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                burst()
+            run = g.replay
+        run()
+        samples = []
+        for _ in range(rounds):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            run()
+            e1.record()
+            torch.cuda.synchronize()
+            samples.append(e0.elapsed_time(e1) / reps)
+        call_ms[c] = float(np.mean(samples))
+        del run
+
+    if args.copy_probe:
+        # a plain copy of known size (2 x K bytes moved), the yardstick for the HBM traffic counters
+        torch.empty_like(K).copy_(K)
+        torch.cuda.synchronize()
 
     work = algorithmic_work(cfg, t0, n_mid, k_eff, l_c)
     per_call_report = {}
@@ -176,6 +222,9 @@ def main():
         roofline = {"kernel": "esa_" + dominant, "bound": "hbm", "achieved": round(achieved, 1),
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4),
                     "traffic": None}
+    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.S, dominant))
+    roofline["traffic"] = None if traffic is None else round(traffic)
+    roofline["algorithmic"] = round(work[dominant]["flops"] or work[dominant]["bytes"])
     roofline["per_call"] = per_call_report
     step_flops = sum(w["flops"] for w in work.values())
     roofline["step_tflops"] = round(step_flops / (ms_per_step * 1e-3) / 1e12, 2)
