@@ -323,6 +323,32 @@ def test_decode_step_equals_one_token_chunk_bf16(esa):
         assert set(needles.tolist()) <= set(g["idx"].cpu().numpy().tolist())
 
 
+@pytest.mark.parametrize("name", ["C2", "C3", "C5", "C4"])
+def test_full_size_last_step_in_the_benchmark_launch_configuration(esa, name):
+    """The configurations at their full sizes, last step (the one the benchmark times), launched the
+    way the benchmark launches it: packed weights, compressed-key cache filled 16384 tokens at a time.
+    One step is within the oracle's reach at any of these sizes, so every output is compared."""
+    cfg = get_config(name)
+    t0 = chunk_starts(cfg)[-1]
+    t1 = min(t0 + cfg.l_C, cfg.S)
+    layer = make_layer(cfg, q_rows=(t0, t1))
+    layer.q_row0 = t0
+    replaced, kc64 = plant_gap(layer, [t0], TAU_E2E["bf16"])
+    say(f"{name} full size S={cfg.S}, step at t0={t0} (l_C={t1 - t0}, k={cfg.k}), {replaced.shape[0]} rows replaced")
+    dev = pack_layer_weights(esa, layer_to_dev(layer))
+    kc_dev = torch.zeros((cfg.S, cfg.d_c), dtype=torch.bfloat16, device="cuda")
+    for r0 in range(0, t0, 16384):
+        r1 = min(r0 + 16384, t0)
+        esa.esa_compress(dev["K"][r0:r1], dev["W_k"], out=kc_dev[r0:r1])
+    rows = np.unique(np.concatenate([np.arange(0, t0, 997), replaced[replaced < t0]]))
+    _assert_compressed_close(to_f64(kc_dev[torch.from_numpy(rows).cuda()]), kc64[rows],
+                             orc.widen(layer.K[rows], "bf16").reshape(rows.shape[0], -1),
+                             orc.widen(layer.W_k, "bf16"), None, "bf16")
+    g = _check_step(esa, layer, dev, kc64, kc_dev, t0)
+    needles = np.setdiff1d(layer.plan.positions[t0], replaced)
+    assert needles.size and set(needles.tolist()) <= set(g["idx"].cpu().numpy().tolist())
+
+
 def test_step_captured_as_a_graph_replays_identically(esa):
     """The five calls captured once and replayed, with eager work and synchronisations between the
     replays: every replay must reproduce the eager result bit for bit (nothing in the library
