@@ -67,6 +67,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true",
                     help="time eager launches instead of replaying the step as a captured HIP graph")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="independent sequences per step (the decode configuration is also quoted at 16)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of the key cache (calibrates HBM traffic counters)")
     args = ap.parse_args()
@@ -89,21 +91,32 @@ def main():
     k_eff = min(cfg.k, n_mid)
 
     t_gen = time.time()
-    layer = make_layer(cfg, q_rows=(t0, t0 + l_c))
-    layer.q_row0 = t0
+    B = args.batch
+    layers = [make_layer(cfg, batch=b, q_rows=(t0, t0 + l_c)) for b in range(B)]
+    for layer in layers:
+        layer.q_row0 = t0
+    layer = layers[0]
 
-    def dev(a):
+    def dev(name):
+        a = np.stack([getattr(x, name) for x in layers]) if B > 1 else getattr(layer, name)
         if cfg.dtype == "f32":
             return torch.from_numpy(a).cuda()
         return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
 
-    Q, K, V = dev(layer.Q), dev(layer.K), dev(layer.V)
-    # weights are packed once per layer, at load time
-    W_q, W_k = esa.esa_pack_weights(dev(layer.W_q)), esa.esa_pack_weights(dev(layer.W_k))
+    def rows(t, r0, r1):
+        return t[:, r0:r1] if B > 1 else t[r0:r1]
+
+    Q, K, V = dev("Q"), dev("K"), dev("V")
+    # weights are packed once per layer, at load time (batch elements share the layer's weights)
+    W_q = esa.esa_pack_weights(torch.from_numpy(layer.W_q.view(np.int16)).cuda().view(torch.bfloat16)
+                               if cfg.dtype == "bf16" else torch.from_numpy(layer.W_q).cuda())
+    W_k = esa.esa_pack_weights(torch.from_numpy(layer.W_k.view(np.int16)).cuda().view(torch.bfloat16)
+                               if cfg.dtype == "bf16" else torch.from_numpy(layer.W_k).cuda())
     # state left by the preceding steps: compressed keys of every earlier token
-    kc = torch.zeros((cfg.S, cfg.d_c), dtype=K.dtype, device="cuda")
+    kc = torch.zeros(((B,) if B > 1 else ()) + (cfg.S, cfg.d_c), dtype=K.dtype, device="cuda")
     for r0 in range(0, t0, 16384):
-        esa.esa_compress(K[r0:min(r0 + 16384, t0)], W_k, out=kc[r0:min(r0 + 16384, t0)])
+        r1 = min(r0 + 16384, t0)
+        esa.esa_compress(rows(K, r0, r1), W_k, out=rows(kc, r0, r1))
     torch.cuda.synchronize()
     t_gen = time.time() - t_gen
 
@@ -111,11 +124,11 @@ def main():
 
     def step():
         qc = esa.esa_compress(Q, W_q)
-        esa.esa_compress(K[t0:t0 + l_c], W_k, out=kc[t0:t0 + l_c])
+        esa.esa_compress(rows(K, t0, t0 + l_c), W_k, out=rows(kc, t0, t0 + l_c))
         if n_mid > cfg.k:
             score = esa.esa_score(qc, kc, i_end, l_start)
         else:
-            score = torch.zeros(max(n_mid, 1), dtype=torch.float32, device="cuda")[:n_mid]
+            score = torch.zeros(((B,) if B > 1 else ()) + (n_mid,), dtype=torch.float32, device="cuda")
         idx = esa.esa_select_topk(score, cfg.k, base=i_end)
         ks, vs = esa.esa_gather_kv(K, V, idx)
         out = esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks, vs)
@@ -156,13 +169,13 @@ def main():
     # under --eager), so that the figure is the kernels' own duration and not the host's launch gaps.
     qc_s = esa.esa_compress(Q, W_q)
     score_s = esa.esa_score(qc_s, kc, i_end, l_start) if n_mid > cfg.k else \
-        torch.zeros(max(n_mid, 1), dtype=torch.float32, device="cuda")[:n_mid]
+        torch.zeros(((B,) if B > 1 else ()) + (n_mid,), dtype=torch.float32, device="cuda")
     idx_s = esa.esa_select_topk(score_s, cfg.k, base=i_end)
     ks_s, vs_s = esa.esa_gather_kv(K, V, idx_s)
 
     def call_compress():
         esa.esa_compress(Q, W_q, out=qc_s)
-        esa.esa_compress(K[t0:t0 + l_c], W_k, out=kc[t0:t0 + l_c])
+        esa.esa_compress(rows(K, t0, t0 + l_c), W_k, out=rows(kc, t0, t0 + l_c))
 
     single = {
         "compress": call_compress,
@@ -203,6 +216,9 @@ def main():
         torch.cuda.synchronize()
 
     work = algorithmic_work(cfg, t0, n_mid, k_eff, l_c)
+    for w in work.values():   # batch elements are independent sequences
+        w["flops"] *= B
+        w["bytes"] *= B
     per_call_report = {}
     for c in calls:
         us = 1e3 * call_ms[c]
@@ -222,7 +238,7 @@ def main():
         roofline = {"kernel": "esa_" + dominant, "bound": "hbm", "achieved": round(achieved, 1),
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4),
                     "traffic": None}
-    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.S, dominant))
+    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.S, dominant)) if B == 1 else None
     roofline["traffic"] = None if traffic is None else round(traffic)
     roofline["algorithmic"] = round(work[dominant]["flops"] or work[dominant]["bytes"])
     roofline["per_call"] = per_call_report
@@ -234,7 +250,7 @@ def main():
         cpu_baseline = cpu_oracle_baseline(layer, cfg, t0, l_c)
 
     unit = "tokens/s"
-    value = l_c / (ms_per_step * 1e-3)
+    value = B * l_c / (ms_per_step * 1e-3)
     result = {
         "metric": "ESA prefill tokens/s per layer at 128k ctx" if not cfg.decode else "ESA decode step",
         "value": round(value, 1), "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -244,7 +260,7 @@ def main():
                                "%d middle tokens; one step = compress+score+select+gather+attend for one chunk"
                                % (cfg.name, cfg.H, cfg.H_kv, cfg.d, cfg.S, l_c, t0, cfg.l_I, cfg.l_L, cfg.k,
                                   cfg.d_c, n_mid),
-                   "global_batch": 1, "seq_len": cfg.S, "parallelism": "single GPU"},
+                   "global_batch": B, "seq_len": cfg.S, "parallelism": "single GPU"},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
         "launch_mode": mode, "eager_ms_per_step": round(eager_ms, 4), "setup_s": round(t_gen, 1),
     }

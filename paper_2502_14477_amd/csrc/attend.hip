@@ -4,6 +4,7 @@
 // (t0 - l_start): everything before the chunk plus the chunk up to itself (Algorithm 1).
 #include "esa_common.h"
 #include "attend_mfma.h"
+#include "attend_decode.h"
 #include "keyspace.h"
 
 namespace esa {
@@ -89,6 +90,7 @@ __global__ __launch_bounds__(256) void attend_fma(const T* __restrict__ q, int l
 size_t attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch) {
   if (l_c <= 0 || h <= 0 || h_kv <= 0 || d <= 0 || batch <= 0) return 256;
   if (attend_mfma_supported(l_c, h, h_kv, d, dtype)) return attend_mfma_workspace_bytes(l_c, h, h_kv, d, batch);
+  if (attend_decode_supported(l_c, h, h_kv, d, dtype)) return attend_decode_workspace_bytes(l_c, h, batch);
   return 256;
 }
 
@@ -102,6 +104,12 @@ int launch_attend(const void* q, int l_c, int h, int h_kv, int d, const void* k_
       attend_mfma_aligned(q, k_cache, v_cache, k_sel, v_sel, out, tok_stride, q_bs, cache_bs, sel_bs, out_bs)) {
     return launch_attend_mfma(q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, sg.i_end, sg.l_start, k_sel,
                               v_sel, n_sel, scale, out, lse, batch, q_bs, cache_bs, sel_bs, out_bs, ws, ws_bytes, st);
+  }
+  if (attend_decode_supported(l_c, h, h_kv, d, dtype) && (int64_t)batch * l_c <= 65535 &&
+      attend_decode_covers(n_fixed + l_c, l_c, h_kv, batch) &&
+      attend_mfma_aligned(q, k_cache, v_cache, k_sel, v_sel, out, tok_stride, q_bs, cache_bs, sel_bs, out_bs)) {
+    return launch_attend_decode(q, l_c, h, h_kv, k_cache, v_cache, tok_stride, t0, sg.i_end, sg.l_start, k_sel, v_sel,
+                                n_sel, scale, out, lse, batch, q_bs, cache_bs, sel_bs, out_bs, ws, ws_bytes, st);
   }
   const int64_t esz = (dtype == ESA_F32) ? 4 : 2;
   KeySpace ks;

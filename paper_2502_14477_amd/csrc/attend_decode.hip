@@ -1,0 +1,338 @@
+// Selected attention (Eq. 1) for decode-sized chunks (fewer than 16 current tokens), bf16 storage,
+// head size 128.  A decode step reads every attended key and value once (17 MB per sequence at the
+// Llama shape) for a few hundred FLOPs per byte less than the matrix cores need, so the kernel is
+// built around memory parallelism: the virtual key sequence [ I | M_k | L | C ] is cut into slices,
+// one workgroup per (slice, KV head, current token, batch element), and the G query heads that share
+// the KV head are served by the same loads.  Slices are merged with the log-sum-exp rule of
+// Algorithm 1 by a second small kernel.
+#include "esa_common.h"
+#include "attend_decode.h"
+#include "keyspace.h"
+
+namespace esa {
+namespace {
+
+constexpr int kD = 128;            // head size
+constexpr int kLanesPerKey = 16;   // 16 lanes x 16 bytes = one 256-byte key row of one KV head
+constexpr int kGroups = 16;        // key rows in flight per workgroup and load instruction (256 threads)
+constexpr int kUnroll = 4;         // independent loads per lane before the first use
+constexpr int kMaxSlice = 1024;    // keys per workgroup (logits are kept in LDS)
+constexpr int kMaxSplits = 128;   // the merge kernel holds two slices per lane
+constexpr int kTargetWorkgroups = 1024;
+
+// Sum over the 16 lanes of a DPP row; every lane receives the total.
+__device__ __forceinline__ float row16_sum(float v) {
+  int x;
+  x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
+  v += __int_as_float(x);
+  x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+  v += __int_as_float(x);
+  x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true);   // row_half_mirror
+  v += __int_as_float(x);
+  x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true);   // row_mirror
+  v += __int_as_float(x);
+  return v;
+}
+
+__device__ __forceinline__ void unpack8(const uint4& r, float* f) {
+  f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xFFFF0000u);
+  f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xFFFF0000u);
+  f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xFFFF0000u);
+  f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xFFFF0000u);
+}
+
+struct DecodeArgs {
+  const bf16_t* q;
+  KeySpace ks;
+  int64_t n_fixed;
+  float scale_log2e;
+  int l_c, h_kv, splits, slice;
+  float* part_o;     // [rows][splits][128]
+  float* part_ml;    // [rows][splits][2]  (max of the base-2 logits, sum of 2^(logit - max))
+  int64_t q_bs, cache_bs_bytes, sel_bs_bytes;
+};
+
+template <int G>
+__global__ __launch_bounds__(256) void attend_decode_bf16(DecodeArgs a) {
+  __shared__ float logit[G][kMaxSlice];
+  __shared__ float red[4][G * kD];
+  __shared__ float head_m[G], head_l[G];
+
+  const int tid = threadIdx.x, sub = tid % kLanesPerKey, group = tid / kLanesPerKey;
+  const int split = blockIdx.x, g = blockIdx.y, c = blockIdx.z % a.l_c, b = blockIdx.z / a.l_c;
+  const int h = a.h_kv * G;
+  KeySpace ks = a.ks;
+  ks.k_cache += (int64_t)b * a.cache_bs_bytes;
+  ks.v_cache += (int64_t)b * a.cache_bs_bytes;
+  if (ks.n_sel > 0) {
+    ks.k_sel += (int64_t)b * a.sel_bs_bytes;
+    ks.v_sel += (int64_t)b * a.sel_bs_bytes;
+  }
+  const int64_t n_keys = a.n_fixed + c + 1;
+  const int64_t j_lo = (int64_t)split * a.slice;
+  const int cnt = (int)(n_keys - j_lo < a.slice ? (n_keys - j_lo > 0 ? n_keys - j_lo : 0) : a.slice);
+  const int64_t row0 = ((int64_t)b * a.l_c + c) * h + (int64_t)g * G;   // first of this workgroup's G output rows
+  const int64_t head_off = (int64_t)g * kD * 2 + sub * 16;              // byte offset inside a token row
+
+  if (cnt == 0) {   // slice past this token's causal limit
+    if (tid < G) {
+      float* ml = a.part_ml + ((row0 + tid) * a.splits + split) * 2;
+      ml[0] = -INFINITY;
+      ml[1] = 0.f;
+    }
+    return;
+  }
+
+  // this lane's 8 elements of each of the G queries, pre-scaled so that logits are base-2 exponents
+  float qf[G][8];
+#pragma unroll
+  for (int hh = 0; hh < G; ++hh) {
+    const uint4 r = *(const uint4*)(a.q + (int64_t)b * a.q_bs + ((int64_t)c * h + g * G + hh) * kD + sub * 8);
+    unpack8(r, qf[hh]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) qf[hh][i] *= a.scale_log2e;
+  }
+
+  // values of the first round of keys: requested now, used after the softmax
+  uint4 v_first[kUnroll];
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const int jj = u * kGroups + group;
+    v_first[u] = make_uint4(0, 0, 0, 0);
+    if (jj < cnt) v_first[u] = *(const uint4*)(key_row(ks, j_lo + jj, true) + head_off);
+  }
+
+  // ---- logits of the slice: 16 lanes per key, kUnroll keys per lane group in flight
+  for (int j0 = 0; j0 < cnt; j0 += kGroups * kUnroll) {
+    uint4 r[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int jj = j0 + u * kGroups + group;
+      r[u] = make_uint4(0, 0, 0, 0);
+      if (jj < cnt) r[u] = *(const uint4*)(key_row(ks, j_lo + jj, false) + head_off);
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int jj = j0 + u * kGroups + group;
+      float kf[8];
+      unpack8(r[u], kf);
+      float mine = 0.f;
+#pragma unroll
+      for (int hh = 0; hh < G; ++hh) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s = __fmaf_rn(qf[hh][i], kf[i], s);
+        s = row16_sum(s);
+        if (sub == hh) mine = s;
+      }
+      if (sub < G && jj < cnt) logit[sub][jj] = mine;
+    }
+  }
+  __syncthreads();
+
+  // ---- per head: maximum, probabilities (unnormalised) and their sum
+  for (int hh = tid >> 6; hh < G; hh += 4) {
+    const int lane = tid & 63;
+    float m = -INFINITY;
+    for (int jj = lane; jj < cnt; jj += 64) m = fmaxf(m, logit[hh][jj]);
+    m = wave_max(m);
+    float l = 0.f;
+    for (int jj = lane; jj < cnt; jj += 64) {
+      const float p = exp2f(logit[hh][jj] - m);
+      logit[hh][jj] = p;
+      l += p;
+    }
+    l = wave_sum(l);
+    if (lane == 0) {
+      head_m[hh] = m;
+      head_l[hh] = l;
+    }
+  }
+  __syncthreads();
+
+  // ---- weighted sum of the values: lane keeps 8 output dims of each head for its key subset
+  float acc[G][8];
+#pragma unroll
+  for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[hh][i] = 0.f;
+  for (int j0 = 0; j0 < cnt; j0 += kGroups * kUnroll) {
+    uint4 r[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int jj = j0 + u * kGroups + group;
+      r[u] = v_first[u];
+      if (j0 > 0) {
+        r[u] = make_uint4(0, 0, 0, 0);
+        if (jj < cnt) r[u] = *(const uint4*)(key_row(ks, j_lo + jj, true) + head_off);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int jj = j0 + u * kGroups + group;
+      if (jj < cnt) {
+        float vf[8];
+        unpack8(r[u], vf);
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) {
+          const float p = logit[hh][jj];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc[hh][i] = __fmaf_rn(p, vf[i], acc[hh][i]);
+        }
+      }
+    }
+  }
+  // the four lane groups of a wave, then the four waves
+#pragma unroll
+  for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float v = acc[hh][i];
+      v += __shfl_xor(v, 16, 64);
+      v += __shfl_xor(v, 32, 64);
+      acc[hh][i] = v;
+    }
+  if ((tid & 63) < kLanesPerKey) {
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) red[tid >> 6][hh * kD + sub * 8 + i] = acc[hh][i];
+  }
+  __syncthreads();
+  for (int e = tid; e < G * kD; e += 256) {
+    const float o = (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
+    const int hh = e / kD, dim = e % kD;
+    a.part_o[((row0 + hh) * a.splits + split) * kD + dim] = o;
+  }
+  if (tid < G) {
+    float* ml = a.part_ml + ((row0 + tid) * a.splits + split) * 2;
+    ml[0] = head_m[tid];
+    ml[1] = head_l[tid];
+  }
+}
+
+// One workgroup per output row (batch element, current token, query head): slices combined by their
+// maxima and sums.  Every lane first fetches the (max, sum) pairs of up to two slices, so the weights
+// are known after one round trip; the four waves then each add a quarter of the slices' partial
+// outputs (independent loads, two output dims per lane) and the quarters meet in LDS.
+__global__ __launch_bounds__(256) void attend_decode_merge(const float* __restrict__ part_o,
+                                                           const float* __restrict__ part_ml, int splits, int l_c,
+                                                           int h, bf16_t* __restrict__ out, int64_t out_bs,
+                                                           float* __restrict__ lse) {
+  __shared__ float red[4][kD];
+  const int64_t row = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float2* ml = (const float2*)(part_ml + row * splits * 2);
+  float2 a0 = make_float2(-INFINITY, 0.f), a1 = make_float2(-INFINITY, 0.f);
+  if (lane < splits) a0 = ml[lane];
+  if (lane + 64 < splits) a1 = ml[lane + 64];
+  const float m = wave_max(fmaxf(a0.x, a1.x));
+  const float w0 = a0.y > 0.f ? exp2f(a0.x - m) : 0.f;
+  const float w1 = a1.y > 0.f ? exp2f(a1.x - m) : 0.f;
+  const float l = wave_sum(__fmaf_rn(w0, a0.y, w1 * a1.y));
+  float o0 = 0.f, o1 = 0.f;
+  const float* po = part_o + row * splits * kD + lane * 2;
+#pragma unroll 4
+  for (int s = wave; s < splits; s += 4) {
+    const float w = s < 64 ? __shfl(w0, s, 64) : __shfl(w1, s - 64, 64);
+    const float2 o = *(const float2*)(po + (int64_t)s * kD);
+    o0 += w != 0.f ? w * o.x : 0.f;    // slices past the causal limit hold no output
+    o1 += w != 0.f ? w * o.y : 0.f;
+  }
+  red[wave][lane * 2] = o0;
+  red[wave][lane * 2 + 1] = o1;
+  __syncthreads();
+  if (wave == 0) {
+    o0 = (red[0][lane * 2] + red[1][lane * 2]) + (red[2][lane * 2] + red[3][lane * 2]);
+    o1 = (red[0][lane * 2 + 1] + red[1][lane * 2 + 1]) + (red[2][lane * 2 + 1] + red[3][lane * 2 + 1]);
+    const int64_t b = row / ((int64_t)l_c * h), r = row % ((int64_t)l_c * h);
+    const float inv = 1.f / l;
+    const uint32_t packed = (uint32_t)f32_to_bf16(o0 * inv) | ((uint32_t)f32_to_bf16(o1 * inv) << 16);
+    *(uint32_t*)(out + b * out_bs + r * kD + lane * 2) = packed;
+    if (lse && lane == 0) lse[row] = (m + log2f(l)) * 0.6931471805599453f;
+  }
+}
+
+struct Plan {
+  int splits, slice;
+};
+
+// Slices of at most kMaxSlice keys (a multiple of the 64 keys one workgroup has in flight), enough of
+// them to put about kTargetWorkgroups on the chip.  splits == 0: more keys than the kernel covers.
+Plan plan_for(int64_t n_keys_max, int l_c, int h_kv, int batch) {
+  const int64_t per_slice_wgs = (int64_t)l_c * h_kv * batch;
+  int64_t want = (kTargetWorkgroups + per_slice_wgs - 1) / per_slice_wgs;
+  if (want > kMaxSplits) want = kMaxSplits;
+  if (want < 1) want = 1;
+  int64_t slice = (n_keys_max + want - 1) / want;
+  slice = (slice + 63) / 64 * 64;
+  if (slice > kMaxSlice) slice = kMaxSlice;
+  const int64_t splits = (n_keys_max + slice - 1) / slice;
+  Plan p;
+  p.slice = (int)slice;
+  p.splits = splits > kMaxSplits ? 0 : (int)splits;
+  return p;
+}
+
+}  // namespace
+
+bool attend_decode_supported(int l_c, int h, int h_kv, int d, int dtype) {
+  if (dtype != ESA_BF16 || d != kD || l_c >= 16 || h % h_kv != 0) return false;
+  const int group = h / h_kv;
+  return group == 1 || group == 2 || group == 4 || group == 8;
+}
+
+bool attend_decode_covers(int64_t n_keys_max, int l_c, int h_kv, int batch) {
+  return plan_for(n_keys_max, l_c, h_kv, batch).splits > 0;
+}
+
+size_t attend_decode_workspace_bytes(int l_c, int h, int batch) {
+  const size_t rows = (size_t)batch * l_c * h;
+  return align_up(rows * kMaxSplits * kD * sizeof(float), 256) + align_up(rows * kMaxSplits * 2 * sizeof(float), 256);
+}
+
+int launch_attend_decode(const void* q, int l_c, int h, int h_kv, const void* k_cache, const void* v_cache,
+                         int64_t tok_stride, int64_t t0, int64_t i_end, int64_t l_start, const void* k_sel,
+                         const void* v_sel, int n_sel, float scale, void* out, float* lse, int batch, int64_t q_bs,
+                         int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes, hipStream_t st) {
+  const int64_t n_fixed = i_end + n_sel + (t0 - l_start);
+  const Plan p = plan_for(n_fixed + l_c, l_c, h_kv, batch);
+  if (p.splits <= 0) ESA_FAIL(ESA_EUNSUPPORTED, "attend_decode: %lld keys exceed the kernel's range", (long long)(n_fixed + l_c));
+  if (ws_bytes < attend_decode_workspace_bytes(l_c, h, batch)) ESA_FAIL(ESA_EWORKSPACE, "attend_decode: workspace too small");
+  const size_t rows = (size_t)batch * l_c * h;
+  DecodeArgs a;
+  a.q = (const bf16_t*)q;
+  a.ks.k_cache = (const char*)k_cache;
+  a.ks.v_cache = (const char*)v_cache;
+  a.ks.k_sel = (const char*)k_sel;
+  a.ks.v_sel = (const char*)v_sel;
+  a.ks.tok_bytes = tok_stride * 2;
+  a.ks.sel_bytes = (int64_t)h_kv * kD * 2;
+  a.ks.i_end = i_end;
+  a.ks.n_sel = n_sel;
+  a.ks.l_start = l_start;
+  a.n_fixed = n_fixed;
+  a.scale_log2e = scale * 1.4426950408889634f;
+  a.l_c = l_c;
+  a.h_kv = h_kv;
+  a.splits = p.splits;
+  a.slice = p.slice;
+  a.part_o = (float*)ws;
+  a.part_ml = (float*)((char*)ws + align_up(rows * kMaxSplits * kD * sizeof(float), 256));
+  a.q_bs = q_bs;
+  a.cache_bs_bytes = cache_bs * 2;
+  a.sel_bs_bytes = sel_bs * 2;
+  const dim3 grid(p.splits, h_kv, batch * l_c);
+  switch (h / h_kv) {
+    case 1: attend_decode_bf16<1><<<grid, 256, 0, st>>>(a); break;
+    case 2: attend_decode_bf16<2><<<grid, 256, 0, st>>>(a); break;
+    case 4: attend_decode_bf16<4><<<grid, 256, 0, st>>>(a); break;
+    default: attend_decode_bf16<8><<<grid, 256, 0, st>>>(a); break;
+  }
+  ESA_LAUNCH_CHECK("attend_decode_bf16");
+  attend_decode_merge<<<(unsigned)rows, 256, 0, st>>>(a.part_o, a.part_ml, p.splits, l_c, h, (bf16_t*)out, out_bs, lse);
+  ESA_LAUNCH_CHECK("attend_decode_merge");
+  return ESA_OK;
+}
+
+}  // namespace esa

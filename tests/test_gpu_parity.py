@@ -204,6 +204,11 @@ def test_score_batched(esa):
     ("f32", 2, 1, 32, 500, 499, 1, 4, 16, 9),            # decode step
     ("bf16", 32, 8, 128, 8192, 7680, 512, 128, 2048, 2048),
     ("bf16", 32, 8, 128, 6000, 5999, 1, 128, 2048, 2048),
+    ("bf16", 32, 8, 128, 40, 39, 1, 128, 2048, 0),       # decode, fewer keys than one slice
+    ("bf16", 8, 8, 128, 3000, 2990, 3, 16, 500, 200),    # three current tokens (causal inside C), G = 1
+    ("bf16", 16, 2, 128, 2500, 2485, 15, 8, 300, 1000),  # G = 8, largest chunk of the decode kernel
+    ("bf16", 4, 2, 128, 150000, 149999, 1, 128, 120000, 0),  # slices near their maximum length
+    ("bf16", 4, 2, 128, 150000, 149999, 1, 128, 140000, 0),  # more keys than the decode kernel covers
     ("bf16", 8, 2, 128, 1500, 1203, 77, 16, 100, 55),    # ragged sizes
     ("bf16", 4, 4, 64, 900, 800, 100, 8, 64, 31)])
 def test_attend_matches_oracle(esa, dtype, H, H_kv, d, S, t0, l_C, l_I, l_L, n_sel):
