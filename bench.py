@@ -67,11 +67,15 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true",
                     help="time eager launches instead of replaying the step as a captured HIP graph")
+    ap.add_argument("--two-branches", action="store_true",
+                    help="run the selection-independent part (key compression, attention over I, L, C) on a second "
+                         "stream beside compress/score/select/gather, and finish with esa_attend_finish")
     ap.add_argument("--batch", type=int, default=1,
                     help="independent sequences per step (the decode configuration is also quoted at 16)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of the key cache (calibrates HBM traffic counters)")
     args = ap.parse_args()
+    args.single_stream = not args.two_branches
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
 
@@ -122,17 +126,32 @@ def main():
 
     calls = ("compress", "score", "select", "gather", "attend")
 
+    side = torch.cuda.Stream()
+
     def step():
+        # Two branches (Algorithm 1's split of the key set): the key compression (needed by later steps
+        # only) and the attention over [I, L, C] do not depend on the selection, so they are enqueued on
+        # a second stream and run beside compress -> score -> select -> gather; the selected keys and the
+        # merge follow on the main stream.  Captured, the branches become parallel paths of the graph.
+        main = torch.cuda.current_stream()
+        if not args.single_stream:
+            side.wait_stream(main)
+            with torch.cuda.stream(side):
+                esa.esa_compress(rows(K, t0, t0 + l_c), W_k, out=rows(kc, t0, t0 + l_c))
+                esa.esa_attend_local(Q, K, V, t0, cfg.l_I, cfg.l_L)
+        else:
+            esa.esa_compress(rows(K, t0, t0 + l_c), W_k, out=rows(kc, t0, t0 + l_c))
         qc = esa.esa_compress(Q, W_q)
-        esa.esa_compress(rows(K, t0, t0 + l_c), W_k, out=rows(kc, t0, t0 + l_c))
         if n_mid > cfg.k:
             score = esa.esa_score(qc, kc, i_end, l_start)
         else:
             score = torch.zeros(((B,) if B > 1 else ()) + (n_mid,), dtype=torch.float32, device="cuda")
         idx = esa.esa_select_topk(score, cfg.k, base=i_end)
         ks, vs = esa.esa_gather_kv(K, V, idx)
-        out = esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks, vs)
-        return out
+        if not args.single_stream:
+            main.wait_stream(side)
+            return esa.esa_attend_finish(Q, K, V, t0, cfg.l_I, cfg.l_L, ks, vs)
+        return esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks, vs)
 
     def timed(fn, n):
         torch.cuda.synchronize()
@@ -149,11 +168,11 @@ def main():
     if not args.eager:
         # The step is launch-bound on the host (about twenty small kernels), so it is captured once
         # as a HIP graph and replayed; every kernel of the step runs in every replay.
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
+        warm = torch.cuda.Stream()
+        warm.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(warm):
             step()
-        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.current_stream().wait_stream(warm)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             graph_out = step()
@@ -183,10 +202,12 @@ def main():
         "select": lambda: esa.esa_select_topk(score_s, cfg.k, base=i_end),
         "gather": lambda: esa.esa_gather_kv(K, V, idx_s),
         "attend": lambda: esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s),
+        "attend_local": lambda: esa.esa_attend_local(Q, K, V, t0, cfg.l_I, cfg.l_L),
+        "attend_finish": lambda: esa.esa_attend_finish(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s),
     }
     reps, rounds = 10, max(3, min(args.steps, 10))
     call_ms = {}
-    for c in calls:
+    for c in single:
         def burst(fn=single[c]):
             for _ in range(reps):
                 fn()
@@ -227,6 +248,8 @@ def main():
             rep["tflops"] = round(work[c]["flops"] / (us * 1e-6) / 1e12, 2)
         rep["gbs"] = round(work[c]["bytes"] / (us * 1e-6) / 1e9, 1)
         per_call_report[c] = rep
+    for c in ("attend_local", "attend_finish"):   # the two-call form of attend, as the step launches it
+        per_call_report[c] = {"us": round(1e3 * call_ms[c], 2)}
     dominant = max(calls, key=lambda c: call_ms[c])
     if work[dominant]["flops"]:
         achieved = work[dominant]["flops"] / (call_ms[dominant] * 1e-3) / 1e12
@@ -262,7 +285,7 @@ def main():
                                   cfg.d_c, n_mid),
                    "global_batch": B, "seq_len": cfg.S, "parallelism": "single GPU"},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
-        "launch_mode": mode, "eager_ms_per_step": round(eager_ms, 4), "setup_s": round(t_gen, 1),
+        "launch_mode": mode + (", one stream" if args.single_stream else ", two branches"), "eager_ms_per_step": round(eager_ms, 4), "setup_s": round(t_gen, 1),
     }
     print(json.dumps(result))
 

@@ -149,6 +149,35 @@ ESA_API int esa_attend(const void* q, int l_c, int h, int h_kv, int d,
                int dtype, int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs,
                void* workspace, size_t ws_bytes, void* stream);
 
+/*
+ * Eq. 1 in two calls, cut where Algorithm 1 cuts it: the keys that do not depend on the selection
+ * and the keys that do, each part a softmax of its own (running maximum and sum kept), the two merged
+ * by their log-sum-exp weights.  Here the first part is [ I | L | C ] (Algorithm 1 puts I with the
+ * selected tokens; it is known before the selection, so it goes with the early part) and the
+ * second is M_k.  esa_attend_local can therefore be enqueued on another stream at the start of the
+ * step and run beside compress / score / select / gather; esa_attend_finish needs the gathered
+ * rows and must be ordered after esa_attend_local (event or same stream).
+ *   esa_attend_local   arguments as esa_attend, without the gathered rows and the outputs; leaves
+ *                      partial results in `workspace`
+ *   esa_attend_finish  arguments exactly as esa_attend, same `workspace`; writes out / lse
+ * Both calls must be given identical sizes, strides and workspace.  The pair computes what
+ * esa_attend computes, to rounding (the slices' boundaries differ).  Shapes outside the
+ * matrix-core kernel (fp32, head sizes other than 128, chunks shorter than 16 tokens) are served
+ * whole by esa_attend_finish; esa_attend_local then enqueues nothing.
+ */
+ESA_API int esa_attend_local(const void* q, int l_c, int h, int h_kv, int d,
+               const void* k_cache, const void* v_cache, int64_t tok_stride,
+               int64_t t0, int64_t l_i, int64_t l_l, float scale,
+               int dtype, int batch, int64_t q_bs, int64_t cache_bs,
+               void* workspace, size_t ws_bytes, void* stream);
+ESA_API int esa_attend_finish(const void* q, int l_c, int h, int h_kv, int d,
+               const void* k_cache, const void* v_cache, int64_t tok_stride,
+               int64_t t0, int64_t l_i, int64_t l_l,
+               const void* k_sel, const void* v_sel, int n_sel,
+               float scale, void* out, float* lse,
+               int dtype, int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs,
+               void* workspace, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

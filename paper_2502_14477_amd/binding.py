@@ -61,6 +61,10 @@ def _load() -> ctypes.CDLL:
     L.esa_attend.restype = i32
     L.esa_attend.argtypes = [vp, i32, i32, i32, i32, vp, vp, i64, i64, i64, i64, vp, vp, i32, f32, vp, vp,
                              i32, i32, i64, i64, i64, i64, vp, sz, vp]
+    L.esa_attend_finish.restype = i32
+    L.esa_attend_finish.argtypes = L.esa_attend.argtypes
+    L.esa_attend_local.restype = i32
+    L.esa_attend_local.argtypes = [vp, i32, i32, i32, i32, vp, vp, i64, i64, i64, i64, f32, i32, i32, i64, i64, vp, sz, vp]
     return L
 
 
@@ -68,7 +72,7 @@ lib = _load()
 
 EXPORTS = ("esa_version", "esa_last_error", "esa_segments", "esa_pack_weights", "esa_compress", "esa_score_workspace_bytes",
            "esa_score", "esa_select_topk_workspace_bytes", "esa_select_topk", "esa_gather_kv",
-           "esa_attend_workspace_bytes", "esa_attend")
+           "esa_attend_workspace_bytes", "esa_attend", "esa_attend_local", "esa_attend_finish")
 
 
 def _check(code: int) -> None:
@@ -215,9 +219,32 @@ def esa_gather_kv(k_cache: torch.Tensor, v_cache: torch.Tensor, idx: torch.Tenso
     return (ks, vs) if had_batch else (ks[0], vs[0])
 
 
+def esa_attend_local(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, t0: int, l_i: int, l_l: int,
+                     scale: Optional[float] = None) -> None:
+    """First half of the two-call form of esa_attend: the keys that do not depend on the selection.
+    Leaves partial results in the attend workspace for esa_attend_finish (same sizes, ordered after it)."""
+    qb, _ = _batched(q, 3)
+    kb, _ = _batched(k_cache, 3)
+    vb, _ = _batched(v_cache, 3)
+    B, l_c, h, d = qb.shape
+    h_kv = kb.shape[2]
+    assert qb.is_contiguous() and kb.stride(3) == 1 and kb.stride(2) == d and vb.stride() == kb.stride()
+    assert kb.shape[1] >= t0 + l_c, "the cache must already hold the current tokens"
+    scale = float(d) ** -0.5 if scale is None else float(scale)
+    nbytes = lib.esa_attend_workspace_bytes(l_c, h, h_kv, d, _dtype(q), B)
+    ws = _workspace(nbytes, q.device, "attend")
+    _check(lib.esa_attend_local(_ptr(qb), l_c, h, h_kv, d, _ptr(kb), _ptr(vb), kb.stride(1), t0, l_i, l_l, scale,
+                                _dtype(q), B, qb.stride(0), kb.stride(0), _ptr(ws), ws.numel(), _stream()))
+
+
+def esa_attend_finish(q, k_cache, v_cache, t0, l_i, l_l, k_sel, v_sel, scale=None, return_lse=False):
+    """Second half of the two-call form: the selected keys, then the merge.  Arguments as esa_attend."""
+    return esa_attend(q, k_cache, v_cache, t0, l_i, l_l, k_sel, v_sel, scale, return_lse, _entry=lib.esa_attend_finish)
+
+
 def esa_attend(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, t0: int, l_i: int, l_l: int,
                k_sel: Optional[torch.Tensor], v_sel: Optional[torch.Tensor], scale: Optional[float] = None,
-               return_lse: bool = False):
+               return_lse: bool = False, _entry=None):
     """q [B?, l_c, h, d]; caches [B?, S, h_kv, d] holding the current tokens at rows t0..; gathered
     buffers [B?, n_sel, h_kv, d] -> out [B?, l_c, h, d] (and lse [B?, l_c, h] fp32)."""
     qb, had_batch = _batched(q, 3)
@@ -241,7 +268,7 @@ def esa_attend(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, t0
     scale = float(d) ** -0.5 if scale is None else float(scale)
     nbytes = lib.esa_attend_workspace_bytes(l_c, h, h_kv, d, _dtype(q), B)
     ws = _workspace(nbytes, q.device, "attend")
-    _check(lib.esa_attend(_ptr(qb), l_c, h, h_kv, d, _ptr(kb), _ptr(vb), kb.stride(1), t0, l_i, l_l, _ptr(ksb),
+    _check((_entry or lib.esa_attend)(_ptr(qb), l_c, h, h_kv, d, _ptr(kb), _ptr(vb), kb.stride(1), t0, l_i, l_l, _ptr(ksb),
                           _ptr(vsb), n_sel, scale, _ptr(out), _ptr(lse), _dtype(q), B, qb.stride(0), kb.stride(0),
                           sel_bs, out.stride(0), _ptr(ws), ws.numel(), _stream()))
     if not had_batch:

@@ -94,7 +94,7 @@ size_t attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int ba
   return 256;
 }
 
-int launch_attend(const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
+int launch_attend(int part, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
                   int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, const void* k_sel, const void* v_sel,
                   int n_sel, float scale, void* out, float* lse, int dtype, int batch, int64_t q_bs,
                   int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes, hipStream_t st) {
@@ -102,9 +102,11 @@ int launch_attend(const void* q, int l_c, int h, int h_kv, int d, const void* k_
   const int64_t n_fixed = sg.i_end + n_sel + (t0 - sg.l_start);
   if (attend_mfma_supported(l_c, h, h_kv, d, dtype) &&
       attend_mfma_aligned(q, k_cache, v_cache, k_sel, v_sel, out, tok_stride, q_bs, cache_bs, sel_bs, out_bs)) {
-    return launch_attend_mfma(q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, sg.i_end, sg.l_start, k_sel,
+    return launch_attend_mfma(part, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, sg.i_end, sg.l_start, k_sel,
                               v_sel, n_sel, scale, out, lse, batch, q_bs, cache_bs, sel_bs, out_bs, ws, ws_bytes, st);
   }
+  // every other shape is computed whole by the finishing (or the only) call
+  if (part == kAttendLocal) return ESA_OK;
   if (attend_decode_supported(l_c, h, h_kv, d, dtype) && (int64_t)batch * l_c <= 65535 &&
       attend_decode_covers(n_fixed + l_c, l_c, h_kv, batch) &&
       attend_mfma_aligned(q, k_cache, v_cache, k_sel, v_sel, out, tok_stride, q_bs, cache_bs, sel_bs, out_bs)) {

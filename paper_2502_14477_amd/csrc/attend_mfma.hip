@@ -29,6 +29,7 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kD = 128;             // head size
@@ -43,6 +44,7 @@ constexpr int kVElems = kD * kVLd;
 constexpr int kStageElems = kKElems + kVElems;
 constexpr int kLdsBytes = 2 * kStageElems * 2;
 constexpr int kMaxSplits = 8;
+constexpr int kMaxSlots = 2 * kMaxSplits;   // two-call form: local slices, then selected slices
 constexpr int kMinLc = 16;          // shorter chunks go to the plain kernel
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -51,8 +53,8 @@ struct AttendArgs {
   const bf16_t* q;
   bf16_t* out;
   float* lse;
-  float* part_o;      // [batch][n_split][l_c][h][128] unnormalised partial outputs
-  float* part_ml;     // [batch][n_split][l_c][h][2]   running maximum (log2 domain) and sum
+  uint16_t* part_o;   // [batch][n_slot][l_c][h][128] fp16 partial outputs, each normalised by its own sum
+  float* part_ml;     // [batch][n_slot][l_c][h][2]   running maximum (log2 domain) and sum
   const char* k_cache;
   const char* v_cache;
   const char* k_sel;
@@ -62,6 +64,9 @@ struct AttendArgs {
   int l_c, h, h_kv, group, qpt, n_qt, n_split, batch;
   int xcd_mapping;                  // 1: (batch, KV head) pairs are a multiple of 8
   uint32_t n_fixed;
+  int with_chunk;     // 1: the virtual sequence ends with the current chunk (causal); 0: every key is visible to every row
+  int slot0, n_slot;  // partial results go to slots [slot0, slot0 + n_split) of n_slot
+  int to_slots;       // 1: write partial results even when n_split == 1
   float c2;           // scale * log2(e)
   int64_t q_bs, out_bs, cache_bs_bytes, sel_bs_bytes;
 };
@@ -70,6 +75,11 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   f32x2 f = {lo, hi};
   bf16x2 b = __builtin_convertvector(f, bf16x2);
   return *(uint32_t*)&b;
+}
+
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
+  f16x2 h = {(_Float16)lo, (_Float16)hi};
+  return *(uint32_t*)&h;
 }
 
 // Row of virtual key j: which buffer, and the byte offset inside it (branch-free).
@@ -115,7 +125,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   // ---- this workgroup's rows and key slice
   const int q0 = qt * a.qpt;
   const int c_last = (q0 + a.qpt < a.l_c ? q0 + a.qpt : a.l_c) - 1;
-  const uint32_t n_vis = a.n_fixed + c_last + 1;                   // keys the tile's last token sees
+  const uint32_t n_vis = a.n_fixed + (a.with_chunk ? c_last + 1 : 0);   // keys the tile's last token sees
   const uint32_t n_tiles = (n_vis + kKT - 1) / kKT;
   const uint32_t tile_begin = (uint32_t)((uint64_t)n_tiles * split / a.n_split);
   const uint32_t tile_end = (uint32_t)((uint64_t)n_tiles * (split + 1) / a.n_split);
@@ -127,7 +137,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   const int c = q0 + (wave % tph) * 32 + r;
   const bool c_ok = c < a.l_c;
   const int cc = c_ok ? c : a.l_c - 1;                             // rows past the chunk repeat its last token
-  const uint32_t vis = a.n_fixed + cc + 1;
+  const uint32_t vis = a.n_fixed + (a.with_chunk ? cc + 1 : 0);
   const uint32_t lim = vis < k_end ? vis : k_end;                  // first virtual key this lane's query may NOT see
   const uint32_t lim_lo = __shfl(lim, 0, 64);                      // smallest limit in the wave (r = 0)
   bf16x8 qf[kD / 16];
@@ -320,56 +330,77 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   }
 #undef ESA_TILE_LOAD
 
-  // ---- results: accumulator register v of tile md is head-dim 32*md + 8*(v/4) + 4*hi + v%4 of this lane's query
+  // ---- results.  Accumulator register v of tile md is head-dim 32*md + 8*(v/4) + 4*hi + v%4 of this
+  // lane's query, so a lane holds its whole output row in 8-byte pieces.  The rows are normalised,
+  // narrowed to 16 bits and turned into whole 256-byte rows in LDS (free by now), from where each wave
+  // writes its own 32 rows with fully coalesced 16-byte stores.  Final outputs are bf16; partial
+  // results of a key slice are fp16 (normalised values are bounded by max |v|, and fp16's 11-bit
+  // significand keeps their rounding well below that of the bf16 output) next to fp32 (maximum, sum).
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  if (!c_ok) return;
-  const int64_t row = (int64_t)c * a.h + head;
-  if (a.n_split == 1) {
-    const float inv = 1.f / l_tot;
-    bf16_t* op = a.out + (int64_t)b * a.out_bs + row * kD;
+  const bool final_out = a.n_split == 1 && !a.to_slots;
+  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  __syncthreads();                       // every wave is done with the last tile
+  {
+    uint16_t* ot = (uint16_t*)lds + (wave * 32 + r) * kKLd;
 #pragma unroll
     for (int md = 0; md < 4; ++md)
 #pragma unroll
       for (int vg = 0; vg < 4; ++vg) {
         uint2 w;
-        w.x = pack_bf16x2(o[md][4 * vg + 0] * inv, o[md][4 * vg + 1] * inv);
-        w.y = pack_bf16x2(o[md][4 * vg + 2] * inv, o[md][4 * vg + 3] * inv);
-        *(uint2*)(op + 32 * md + 8 * vg + 4 * hi) = w;
+        if (final_out) {
+          w.x = pack_bf16x2(o[md][4 * vg + 0] * inv, o[md][4 * vg + 1] * inv);
+          w.y = pack_bf16x2(o[md][4 * vg + 2] * inv, o[md][4 * vg + 3] * inv);
+        } else {
+          w.x = pack_f16x2(o[md][4 * vg + 0] * inv, o[md][4 * vg + 1] * inv);
+          w.y = pack_f16x2(o[md][4 * vg + 2] * inv, o[md][4 * vg + 3] * inv);
+        }
+        *(uint2*)(ot + 32 * md + 8 * vg + 4 * hi) = w;
       }
-    if (a.lse && hi == 0) a.lse[(int64_t)b * a.l_c * a.h + row] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2;
+  }
+  __syncthreads();
+  const int c_wave = q0 + (wave % tph) * 32;                        // first current token of this wave's rows
+  uint16_t* dst;
+  if (final_out) {
+    dst = (uint16_t*)a.out + (int64_t)b * a.out_bs + ((int64_t)c_wave * a.h + head) * kD;
   } else {
-    const int64_t prow = ((int64_t)(b * a.n_split + split) * a.l_c) * a.h + row;
-    float* pp = a.part_o + prow * kD;
-#pragma unroll
-    for (int md = 0; md < 4; ++md)
-#pragma unroll
-      for (int vg = 0; vg < 4; ++vg) {
-        float4 w = {o[md][4 * vg + 0], o[md][4 * vg + 1], o[md][4 * vg + 2], o[md][4 * vg + 3]};
-        *(float4*)(pp + 32 * md + 8 * vg + 4 * hi) = w;
-      }
-    if (hi == 0) {
+    const int64_t prow0 = ((int64_t)(b * a.n_slot + a.slot0 + split) * a.l_c) * a.h;
+    dst = a.part_o + (prow0 + (int64_t)c_wave * a.h + head) * kD;
+    if (hi == 0 && c_ok) {
       float2 ml = {m_run, l_tot};
-      *(float2*)(a.part_ml + prow * 2) = ml;
+      *(float2*)(a.part_ml + (prow0 + (int64_t)c * a.h + head) * 2) = ml;
     }
   }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int rw = 4 * i + (lane >> 4), piece = lane & 15;
+    if (c_wave + rw < a.l_c) {
+      const uint4 w = *(const uint4*)((const uint16_t*)lds + (wave * 32 + rw) * kKLd + piece * 8);
+      *(uint4*)(dst + (int64_t)rw * a.h * kD + piece * 8) = w;
+    }
+  }
+  if (final_out && a.lse && hi == 0 && c_ok)
+    a.lse[(int64_t)b * a.l_c * a.h + (int64_t)c * a.h + head] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2;
 }
 
-// Algorithm 1's merge over the key slices: weights 2^(m_s - M) with the maximum subtracted first.
-// 32 lanes per row (four head-dims each), eight rows per workgroup.
-__global__ __launch_bounds__(256) void esa_attend_merge(const float* __restrict__ part_o,
-                                                        const float* __restrict__ part_ml, int n_split, int64_t rows,
-                                                        bf16_t* __restrict__ out, float* __restrict__ lse,
-                                                        int64_t out_bs, int64_t lse_bs) {
+// Algorithm 1's merge over partial results: weights 2^(m_s - M) with the maximum subtracted first.
+// The slots in use are [0, ns_a) and [slot_b, slot_b + ns_b) of n_slot.  32 lanes per row (four
+// head-dims each), eight rows per workgroup.
+__global__ __launch_bounds__(256) void esa_attend_merge(const uint16_t* __restrict__ part_o,
+                                                        const float* __restrict__ part_ml, int n_slot, int ns_a,
+                                                        int slot_b, int ns_b, int64_t rows, bf16_t* __restrict__ out,
+                                                        float* __restrict__ lse, int64_t out_bs, int64_t lse_bs) {
   const int64_t row = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);
   const int d4 = (threadIdx.x & 31) * 4;
   const int b = blockIdx.y;
   if (row >= rows) return;
-  float m[kMaxSplits], l[kMaxSplits];
+  float m[kMaxSlots], l[kMaxSlots];
   float M = -INFINITY;
 #pragma unroll
-  for (int s = 0; s < kMaxSplits; ++s) {
-    if (s < n_split) {
-      const float2 ml = *(const float2*)(part_ml + (((int64_t)b * n_split + s) * rows + row) * 2);
+  for (int s = 0; s < kMaxSlots; ++s) {
+    m[s] = -INFINITY;
+    l[s] = 0.f;
+    if (s < ns_a || (s >= slot_b && s < slot_b + ns_b)) {
+      const float2 ml = *(const float2*)(part_ml + (((int64_t)b * n_slot + s) * rows + row) * 2);
       m[s] = ml.x;
       l[s] = ml.y;
       M = fmaxf(M, ml.x);
@@ -378,15 +409,16 @@ __global__ __launch_bounds__(256) void esa_attend_merge(const float* __restrict_
   float L = 0.f;
   float4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int s = 0; s < kMaxSplits; ++s) {
-    if (s < n_split && m[s] != -INFINITY) {       // a slice this query saw nothing of carries no weight
-      const float w = __builtin_amdgcn_exp2f(m[s] - M);
-      const float4 po = *(const float4*)(part_o + (((int64_t)b * n_split + s) * rows + row) * kD + d4);
-      L += w * l[s];
-      acc.x += w * po.x;
-      acc.y += w * po.y;
-      acc.z += w * po.z;
-      acc.w += w * po.w;
+  for (int s = 0; s < kMaxSlots; ++s) {
+    if (m[s] != -INFINITY) {       // unused slots, and slices this query saw nothing of, carry no weight
+      const float w = __builtin_amdgcn_exp2f(m[s] - M) * l[s];     // the slice's outputs are normalised by its sum
+      const uint2 po = *(const uint2*)(part_o + (((int64_t)b * n_slot + s) * rows + row) * kD + d4);
+      const f16x2 p01 = *(const f16x2*)&po.x, p23 = *(const f16x2*)&po.y;
+      L += w;
+      acc.x += w * (float)p01[0];
+      acc.y += w * (float)p01[1];
+      acc.z += w * (float)p23[0];
+      acc.w += w * (float)p23[1];
     }
   }
   const float inv = 1.f / L;
@@ -421,17 +453,40 @@ bool attend_mfma_aligned(const void* q, const void* k_cache, const void* v_cache
   return (p % 16 == 0) && (s % 8 == 0);
 }
 
-size_t attend_mfma_workspace_bytes(int l_c, int h, int h_kv, int d, int batch) {
-  const int ns = choose_splits(l_c, h / h_kv, h_kv, batch);
-  if (ns == 1) return 256;
-  const size_t rows = (size_t)batch * ns * l_c * h;
-  return align_up(rows * kD * sizeof(float), 256) + align_up(rows * 2 * sizeof(float), 256);
+namespace {
+
+// Planned slice counts.  One call: `all` slices of the whole virtual sequence.  Two calls: the local
+// part [ I | L | C ] runs beside other work, so it gets fewer, longer slices than the selected part,
+// which is on the critical path and should cover the chip by itself.
+struct SplitPlan {
+  int all, local, sel;
+};
+SplitPlan plan_splits(int l_c, int group, int h_kv, int batch) {
+  SplitPlan p;
+  p.all = choose_splits(l_c, group, h_kv, batch);
+  p.sel = p.all;
+  p.local = p.all > 1 ? p.all / 2 : 1;
+  return p;
 }
 
-int launch_attend_mfma(const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
-                       int64_t tok_stride, int64_t t0, int64_t i_end, int64_t l_start, const void* k_sel,
-                       const void* v_sel, int n_sel, float scale, void* out, float* lse, int batch, int64_t q_bs,
-                       int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes, hipStream_t st) {
+size_t slots_bytes(int n_slot, int l_c, int h, int batch) {
+  const size_t rows = (size_t)batch * n_slot * l_c * h;
+  return align_up(rows * kD * sizeof(uint16_t), 256) + align_up(rows * 2 * sizeof(float), 256);
+}
+
+}  // namespace
+
+size_t attend_mfma_workspace_bytes(int l_c, int h, int h_kv, int d, int batch) {
+  const SplitPlan p = plan_splits(l_c, h / h_kv, h_kv, batch);
+  const int n_slot = p.local + p.sel > p.all ? p.local + p.sel : p.all;
+  return slots_bytes(n_slot, l_c, h, batch);
+}
+
+int launch_attend_mfma(int part, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache,
+                       const void* v_cache, int64_t tok_stride, int64_t t0, int64_t i_end, int64_t l_start,
+                       const void* k_sel, const void* v_sel, int n_sel, float scale, void* out, float* lse, int batch,
+                       int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes,
+                       hipStream_t st) {
   if (!(scale > 0.f)) ESA_FAIL(ESA_EINVAL, "esa_attend: scale must be positive");
   if (t0 + l_c >= ((int64_t)1 << 31) || tok_stride * 2 >= ((int64_t)1 << 32))
     ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend: positions beyond 2^31 are not supported by the matrix-core kernel");
@@ -445,9 +500,6 @@ int launch_attend_mfma(const void* q, int l_c, int h, int h_kv, int d, const voi
   a.v_sel = (const char*)v_sel;
   a.tok_bytes = (uint32_t)(tok_stride * 2);
   a.sel_bytes = (uint32_t)((int64_t)h_kv * d * 2);
-  a.i_end = (uint32_t)i_end;
-  a.n_sel = (uint32_t)n_sel;
-  a.l_start = (uint32_t)l_start;
   a.l_c = l_c;
   a.h = h;
   a.h_kv = h_kv;
@@ -455,26 +507,35 @@ int launch_attend_mfma(const void* q, int l_c, int h, int h_kv, int d, const voi
   a.qpt = kRows / a.group;
   a.n_qt = (l_c + a.qpt - 1) / a.qpt;
   a.batch = batch;
-  a.n_fixed = (uint32_t)(i_end + n_sel + (t0 - l_start));
   a.c2 = scale * kLog2e;
   a.q_bs = q_bs;
   a.out_bs = out_bs;
   a.cache_bs_bytes = cache_bs * 2;
   a.sel_bs_bytes = sel_bs * 2;
-  int ns = choose_splits(l_c, a.group, h_kv, batch);
-  const int64_t min_tiles = ((int64_t)a.n_fixed + (l_c < a.qpt ? l_c : a.qpt) + kKT - 1) / kKT;   // first row tile
-  if (ns > min_tiles) ns = (int)min_tiles;
-  a.n_split = ns;
   a.xcd_mapping = ((batch * h_kv) % 8 == 0) ? 1 : 0;
+
+  const SplitPlan plan = plan_splits(l_c, a.group, h_kv, batch);
+  const int first_rows = l_c < a.qpt ? l_c : a.qpt;
+  auto clamp = [](int ns, int64_t keys_of_first_tile) {
+    const int64_t tiles = (keys_of_first_tile + kKT - 1) / kKT;
+    return (int)(ns > tiles ? (tiles > 0 ? tiles : 1) : ns);
+  };
+  // slices in use: one call -> `all`; two calls -> local in slots [0, ns_local), selected in [plan.local, +ns_sel)
+  const int ns_all = clamp(plan.all, i_end + n_sel + (t0 - l_start) + first_rows);
+  const int ns_local = clamp(plan.local, i_end + (t0 - l_start) + first_rows);
+  const int ns_sel = n_sel > 0 ? clamp(plan.sel, n_sel) : 0;
+  const int n_slot = part == kAttendAll ? ns_all : plan.local + plan.sel;
+
   a.part_o = nullptr;
   a.part_ml = nullptr;
-  if (ns > 1) {
-    const size_t rows = (size_t)batch * ns * l_c * h;
-    const size_t need = align_up(rows * kD * sizeof(float), 256) + align_up(rows * 2 * sizeof(float), 256);
+  if (part != kAttendAll || ns_all > 1) {
+    const size_t need = slots_bytes(n_slot, l_c, h, batch);
     if (!ws || ws_bytes < need) ESA_FAIL(ESA_EWORKSPACE, "esa_attend: workspace needs %zu bytes", need);
-    a.part_o = (float*)ws;
-    a.part_ml = (float*)((char*)ws + align_up(rows * kD * sizeof(float), 256));
+    const size_t rows = (size_t)batch * n_slot * l_c * h;
+    a.part_o = (uint16_t*)ws;
+    a.part_ml = (float*)((char*)ws + align_up(rows * kD * sizeof(uint16_t), 256));
   }
+  a.n_slot = n_slot;
   static bool lds_limit_raised = false;          // idempotent; a race only repeats the call
   if (!lds_limit_raised) {
     hipError_t e = hipFuncSetAttribute((const void*)attend_mfma_bf16, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -482,12 +543,45 @@ int launch_attend_mfma(const void* q, int l_c, int h, int h_kv, int d, const voi
     if (e != hipSuccess) return hip_failed(e, "hipFuncSetAttribute(attend_mfma_bf16)");
     lds_limit_raised = true;
   }
-  const int64_t n_wg = (int64_t)batch * h_kv * a.n_qt * ns;
-  attend_mfma_bf16<<<dim3((unsigned)n_wg), kThreads, kLdsBytes, st>>>(a);
-  if (ns > 1) {
-    const int64_t rows = (int64_t)l_c * h;
-    esa_attend_merge<<<dim3((unsigned)((rows + 7) / 8), batch), 256, 0, st>>>(a.part_o, a.part_ml, ns, rows,
-                                                                              (bf16_t*)out, lse, out_bs, rows);
+  const int64_t rows = (int64_t)l_c * h;
+  const dim3 merge_grid((unsigned)((rows + 7) / 8), batch);
+  if (part == kAttendAll) {
+    a.i_end = (uint32_t)i_end;
+    a.n_sel = (uint32_t)n_sel;
+    a.l_start = (uint32_t)l_start;
+    a.n_fixed = (uint32_t)(i_end + n_sel + (t0 - l_start));
+    a.with_chunk = 1;
+    a.n_split = ns_all;
+    a.slot0 = 0;
+    a.to_slots = 0;
+    attend_mfma_bf16<<<dim3((unsigned)((int64_t)batch * h_kv * a.n_qt * ns_all)), kThreads, kLdsBytes, st>>>(a);
+    if (ns_all > 1)
+      esa_attend_merge<<<merge_grid, 256, 0, st>>>(a.part_o, a.part_ml, n_slot, ns_all, 0, 0, rows, (bf16_t*)out, lse,
+                                                   out_bs, rows);
+  } else if (part == kAttendLocal) {
+    a.i_end = (uint32_t)i_end;
+    a.n_sel = 0;
+    a.l_start = (uint32_t)l_start;
+    a.n_fixed = (uint32_t)(i_end + (t0 - l_start));
+    a.with_chunk = 1;
+    a.n_split = ns_local;
+    a.slot0 = 0;
+    a.to_slots = 1;
+    attend_mfma_bf16<<<dim3((unsigned)((int64_t)batch * h_kv * a.n_qt * ns_local)), kThreads, kLdsBytes, st>>>(a);
+  } else {
+    if (ns_sel > 0) {
+      a.i_end = 0;
+      a.n_sel = (uint32_t)n_sel;
+      a.l_start = 0;
+      a.n_fixed = (uint32_t)n_sel;
+      a.with_chunk = 0;
+      a.n_split = ns_sel;
+      a.slot0 = plan.local;
+      a.to_slots = 1;
+      attend_mfma_bf16<<<dim3((unsigned)((int64_t)batch * h_kv * a.n_qt * ns_sel)), kThreads, kLdsBytes, st>>>(a);
+    }
+    esa_attend_merge<<<merge_grid, 256, 0, st>>>(a.part_o, a.part_ml, n_slot, ns_local, plan.local, ns_sel, rows,
+                                                 (bf16_t*)out, lse, out_bs, rows);
   }
   ESA_LAUNCH_CHECK("attend_mfma");
   return ESA_OK;

@@ -43,7 +43,7 @@ def oracle_step(layer, kc64, t0):
     return O, lse, sel, F, qc
 
 
-def gpu_step(esa, dev, cfg, t0, kc_dev=None):
+def gpu_step(esa, dev, cfg, t0, kc_dev=None, two_calls=False):
     """The five library calls for the step at t0.  dev: dict of device tensors Q,K,V,W_q,W_k
     (Q may start at row dev['q_row0']).  kc_dev: compressed-key cache [S, d_c]; rows of the current
     tokens are (re)written by esa_compress.  Returns dict of device tensors."""
@@ -69,7 +69,11 @@ def gpu_step(esa, dev, cfg, t0, kc_dev=None):
     else:
         idx = torch.empty(0, dtype=torch.int32, device="cuda")
         ks = vs = None
-    O, lse = esa.esa_attend(q, dev["K"], dev["V"], t0, cfg.l_I, cfg.l_L, ks, vs, return_lse=True)
+    if two_calls:
+        esa.esa_attend_local(q, dev["K"], dev["V"], t0, cfg.l_I, cfg.l_L)
+        O, lse = esa.esa_attend_finish(q, dev["K"], dev["V"], t0, cfg.l_I, cfg.l_L, ks, vs, return_lse=True)
+    else:
+        O, lse = esa.esa_attend(q, dev["K"], dev["V"], t0, cfg.l_I, cfg.l_L, ks, vs, return_lse=True)
     out.update(idx=idx, k_sel=ks, v_sel=vs, O=O, lse=lse)
     return out
 

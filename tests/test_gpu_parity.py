@@ -227,9 +227,15 @@ def test_attend_matches_oracle(esa, dtype, H, H_kv, d, S, t0, l_C, l_I, l_L, n_s
     ks = vs = None
     if n_sel:
         ks, vs = esa.esa_gather_kv(Kd, Vd, torch.from_numpy(sel).cuda())
-    O, lse = esa.esa_attend(f64_to_dev(Q, dtype), Kd, Vd, t0, l_I, l_L, ks, vs, return_lse=True)
+    Qd = f64_to_dev(Q, dtype)
+    O, lse = esa.esa_attend(Qd, Kd, Vd, t0, l_I, l_L, ks, vs, return_lse=True)
     assert np.max(np.abs(to_f64(O) - want_O)) <= O_TOL[dtype]
     assert np.max(np.abs(to_f64(lse) - want_lse)) <= (1e-5 if dtype == "f32" else 1e-3)
+    # the two-call form (Algorithm 1's split: keys known before the selection, then the selected keys)
+    esa.esa_attend_local(Qd, Kd, Vd, t0, l_I, l_L)
+    O2, lse2 = esa.esa_attend_finish(Qd, Kd, Vd, t0, l_I, l_L, ks, vs, return_lse=True)
+    assert np.max(np.abs(to_f64(O2) - want_O)) <= O_TOL[dtype]
+    assert np.max(np.abs(to_f64(lse2) - want_lse)) <= (1e-5 if dtype == "f32" else 1e-3)
 
 
 def test_attend_batched(esa):
@@ -249,11 +255,34 @@ def test_attend_batched(esa):
         assert np.max(np.abs(to_f64(O[b]) - want)) <= O_TOL["bf16"]
 
 
+def test_attend_in_two_calls_batched_with_the_local_part_on_a_side_stream(esa):
+    say("attend batch=3, l_C=96, local part on a second stream")
+    rng = np.random.default_rng(78)
+    B, H, H_kv, d, l_C, l_I, l_L, n_sel = 3, 8, 2, 128, 96, 16, 300, 200
+    t0 = 1400
+    Q = orc.round_to_storage(rng.standard_normal((B, l_C, H, d)), "bf16")
+    K = orc.round_to_storage(rng.standard_normal((B, t0 + l_C, H_kv, d)), "bf16")
+    V = orc.round_to_storage(rng.standard_normal((B, t0 + l_C, H_kv, d)), "bf16")
+    sel = np.stack([np.sort(rng.choice(np.arange(l_I, t0 - l_L), n_sel, replace=False)) for _ in range(B)]).astype(np.int32)
+    Qd, Kd, Vd = f64_to_dev(Q, "bf16"), f64_to_dev(K, "bf16"), f64_to_dev(V, "bf16")
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    side.wait_stream(main)
+    with torch.cuda.stream(side):
+        esa.esa_attend_local(Qd, Kd, Vd, t0, l_I, l_L)
+    ks, vs = esa.esa_gather_kv(Kd, Vd, torch.from_numpy(sel).cuda())
+    main.wait_stream(side)
+    O, lse = esa.esa_attend_finish(Qd, Kd, Vd, t0, l_I, l_L, ks, vs, return_lse=True)
+    for b in range(B):
+        want, want_lse = orc.attend(Q[b], K[b], V[b], t0, l_I, l_L, sel[b], 1.0 / np.sqrt(d))
+        assert np.max(np.abs(to_f64(O[b]) - want)) <= O_TOL["bf16"]
+        assert np.max(np.abs(to_f64(lse[b]) - want_lse)) <= 1e-3
+
+
 # ------------------------------------------------------------------------------------------ whole steps
-def _check_step(esa, layer, dev, kc64, kc_dev, t0, stagewise_too=True):
+def _check_step(esa, layer, dev, kc64, kc_dev, t0, stagewise_too=True, two_calls=False):
     cfg = layer.cfg
     O, lse, sel, F, qc = oracle_step(layer, kc64, t0)
-    g = gpu_step(esa, dev, cfg, t0, kc_dev)
+    g = gpu_step(esa, dev, cfg, t0, kc_dev, two_calls=two_calls)
     got_idx = g["idx"].cpu().numpy()
     assert np.array_equal(got_idx, sel), f"t0={t0}: selected sets differ in {np.sum(got_idx != sel)} slots"
     if g["score"] is not None:
@@ -349,7 +378,10 @@ def test_full_size_last_step_in_the_benchmark_launch_configuration(esa, name):
     _assert_compressed_close(to_f64(kc_dev[torch.from_numpy(rows).cuda()]), kc64[rows],
                              orc.widen(layer.K[rows], "bf16").reshape(rows.shape[0], -1),
                              orc.widen(layer.W_k, "bf16"), None, "bf16")
-    g = _check_step(esa, layer, dev, kc64, kc_dev, t0)
+    g = _check_step(esa, layer, dev, kc64, kc_dev, t0, two_calls=True)
+    one = gpu_step(esa, dev, cfg, t0, kc_dev)     # esa_attend in one call: same selection, same output to rounding
+    assert torch.equal(one["idx"], g["idx"])
+    assert float((one["O"].float() - g["O"].float()).abs().max()) <= O_TOL["bf16"]
     needles = np.setdiff1d(layer.plan.positions[t0], replaced)
     assert needles.size and set(needles.tolist()) <= set(g["idx"].cpu().numpy().tolist())
 
