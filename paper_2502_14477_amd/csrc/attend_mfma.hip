@@ -140,16 +140,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   const uint32_t vis = a.n_fixed + (a.with_chunk ? cc + 1 : 0);
   const uint32_t lim = vis < k_end ? vis : k_end;                  // first virtual key this lane's query may NOT see
   const uint32_t lim_lo = __shfl(lim, 0, 64);                      // smallest limit in the wave (r = 0)
-  bf16x8 qf[kD / 16];
-  {
-    const bf16_t* qp = a.q + (int64_t)b * a.q_bs + ((int64_t)cc * a.h + head) * kD + hi * 8;
-#pragma unroll
-    for (int ks16 = 0; ks16 < kD / 16; ++ks16) qf[ks16] = *(const bf16x8*)(qp + ks16 * 16);
-    // Pin the fragments as arrived values here: otherwise every use inside the tile loop carries a
-    // wait on the vector-memory counter, which would also wait for the tile loads just issued.
-#pragma unroll
-    for (int ks16 = 0; ks16 < kD / 16; ++ks16) asm volatile("" : "+v"(qf[ks16]));
-  }
+  bf16x8 qf[kD / 16];                                              // loaded below, behind the first tile's loads
 
   f32x16 o[4];
 #pragma unroll
@@ -241,10 +232,18 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     *(uint2*)(dst + 3 * kVLd) = d3;
   };
 
-  if (tile_begin < tile_end) {
-    ESA_TILE_LOAD(tile_begin * kKT);
-    tile_store(0);
+  // The first tile's loads go out before the query fragments' so that the two round trips overlap.
+  if (tile_begin < tile_end) ESA_TILE_LOAD(tile_begin * kKT);
+  {
+    const bf16_t* qp = a.q + (int64_t)b * a.q_bs + ((int64_t)cc * a.h + head) * kD + hi * 8;
+#pragma unroll
+    for (int ks16 = 0; ks16 < kD / 16; ++ks16) qf[ks16] = *(const bf16x8*)(qp + ks16 * 16);
+    // Pin the fragments as arrived values here: otherwise every use inside the tile loop carries a
+    // wait on the vector-memory counter, which would also wait for the tile loads just issued.
+#pragma unroll
+    for (int ks16 = 0; ks16 < kD / 16; ++ks16) asm volatile("" : "+v"(qf[ks16]));
   }
+  if (tile_begin < tile_end) tile_store(0);
   for (uint32_t t = tile_begin; t < tile_end; ++t) {
     const uint32_t j0 = t * kKT;
     const int stage = (int)((t - tile_begin) & 1);
@@ -393,33 +392,37 @@ __global__ __launch_bounds__(256) void esa_attend_merge(const uint16_t* __restri
   const int d4 = (threadIdx.x & 31) * 4;
   const int b = blockIdx.y;
   if (row >= rows) return;
+  // Every load of the row goes out before the first use (one round trip): the slices' (maximum, sum)
+  // pairs and their outputs.  A slice that saw no key of this row stored zeros and sum 0.
   float m[kMaxSlots], l[kMaxSlots];
-  float M = -INFINITY;
+  uint2 po[kMaxSlots];
 #pragma unroll
   for (int s = 0; s < kMaxSlots; ++s) {
     m[s] = -INFINITY;
     l[s] = 0.f;
+    po[s] = make_uint2(0u, 0u);
     if (s < ns_a || (s >= slot_b && s < slot_b + ns_b)) {
-      const float2 ml = *(const float2*)(part_ml + (((int64_t)b * n_slot + s) * rows + row) * 2);
+      const int64_t prow = ((int64_t)b * n_slot + s) * rows + row;
+      const float2 ml = *(const float2*)(part_ml + prow * 2);
       m[s] = ml.x;
       l[s] = ml.y;
-      M = fmaxf(M, ml.x);
+      po[s] = *(const uint2*)(part_o + prow * kD + d4);
     }
   }
+  float M = -INFINITY;
+#pragma unroll
+  for (int s = 0; s < kMaxSlots; ++s) M = fmaxf(M, m[s]);
   float L = 0.f;
   float4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int s = 0; s < kMaxSlots; ++s) {
-    if (m[s] != -INFINITY) {       // unused slots, and slices this query saw nothing of, carry no weight
-      const float w = __builtin_amdgcn_exp2f(m[s] - M) * l[s];     // the slice's outputs are normalised by its sum
-      const uint2 po = *(const uint2*)(part_o + (((int64_t)b * n_slot + s) * rows + row) * kD + d4);
-      const f16x2 p01 = *(const f16x2*)&po.x, p23 = *(const f16x2*)&po.y;
-      L += w;
-      acc.x += w * (float)p01[0];
-      acc.y += w * (float)p01[1];
-      acc.z += w * (float)p23[0];
-      acc.w += w * (float)p23[1];
-    }
+    const float w = m[s] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m[s] - M) * l[s];   // outputs are normalised by the slice's sum
+    const f16x2 p01 = *(const f16x2*)&po[s].x, p23 = *(const f16x2*)&po[s].y;
+    L += w;
+    acc.x += w * (float)p01[0];
+    acc.y += w * (float)p01[1];
+    acc.z += w * (float)p23[0];
+    acc.w += w * (float)p23[1];
   }
   const float inv = 1.f / L;
   uint2 w2;

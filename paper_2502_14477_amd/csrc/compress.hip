@@ -5,8 +5,9 @@
 //   * compress_mfma_packed_bf16 — bf16 storage, weights in the packed (output-major) layout written by
 //     esa_pack_weights.  Both MFMA operands then have their reduction elements contiguous in memory
 //     and are loaded straight from global memory, 16 bytes per lane, with no LDS staging.  A
-//     workgroup owns a 16-token x 16-output tile; its four waves each reduce a quarter of d_in and
-//     the four partial tiles are added in a fixed order (deterministic, no atomics).
+//     workgroup owns a 16-token x 16-output tile; its four (many tokens) or sixteen (few tokens:
+//     latency-bound) waves each reduce an equal share of d_in and the partial tiles are added in a
+//     fixed order (deterministic, no atomics).
 //   * compress_mfma_bf16 — bf16 storage, weights as given ([d_in, d_c]); W is transposed through LDS.
 //   * compress_fma — any storage type, shape and weight layout, plain fp32 FMAs in ascending
 //     reduction order.
@@ -141,13 +142,14 @@ __global__ __launch_bounds__(256) void compress_mfma_bf16(const bf16_t* __restri
 // v_mfma_f32_16x16x32_bf16: lane l supplies A[l%16][8*(l/16) .. +7] and B[8*(l/16) .. +7][l%16] and owns
 // C[4*(l/16) .. +3][l%16].  A rows are tokens, B columns are outputs, so a lane reads eight consecutive
 // reduction elements of one token row of x and of one output row of the packed weights.
-__global__ __launch_bounds__(256) void compress_mfma_packed_bf16(const bf16_t* __restrict__ x, int64_t n_tok,
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void compress_mfma_packed_bf16(const bf16_t* __restrict__ x, int64_t n_tok,
                                                                  int64_t d_in, int64_t ldx,
                                                                  const bf16_t* __restrict__ Wt,
                                                                  const bf16_t* __restrict__ bias, int d_c,
                                                                  bf16_t* __restrict__ out, int64_t ldo, int64_t x_bs,
                                                                  int64_t out_bs) {
-  __shared__ float red[4][256];
+  __shared__ float red[NW][256];
   const bf16_t* xb = x + (int64_t)blockIdx.z * x_bs;
   bf16_t* ob = out + (int64_t)blockIdx.z * out_bs;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -156,7 +158,7 @@ __global__ __launch_bounds__(256) void compress_mfma_packed_bf16(const bf16_t* _
   const int col0 = blockIdx.y * 16;
   int64_t tok = tok0 + r;
   tok = tok < n_tok ? tok : n_tok - 1;               // keep the address valid; the row is discarded
-  const int64_t kq = d_in / 4;                       // this wave's share of the reduction (multiple of 32)
+  const int64_t kq = d_in / NW;                      // this wave's share of the reduction (multiple of 32)
   const bf16_t* xp = xb + tok * ldx + wave * kq + q * 8;
   const bf16_t* wp = Wt + (int64_t)(col0 + r) * d_in + wave * kq + q * 8;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -170,10 +172,13 @@ __global__ __launch_bounds__(256) void compress_mfma_packed_bf16(const bf16_t* _
   for (int v = 0; v < 4; ++v) red[wave][(4 * q + v) * 16 + r] = acc[v];
   __syncthreads();
   const int t = threadIdx.x;
+  if (t >= 256) return;
   const int64_t row = tok0 + (t >> 4);
   const int col = col0 + (t & 15);
   if (row < n_tok) {
-    float v = ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
+    float v = red[0][t];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) v += red[w][t];     // fixed order: deterministic
     if (bias) v += bf16_to_f32(bias[col]);
     ob[row * ldo + col] = f32_to_bf16(v);
   }
@@ -211,9 +216,14 @@ int launch_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx, con
   if (dtype == ESA_BF16) {
     const bool vec_ok = (ldx % 8 == 0) && (x_bs % 8 == 0) && (((uintptr_t)x | (uintptr_t)W) % 16 == 0);
     if (packed && vec_ok && d_c % 16 == 0 && d_in % 128 == 0) {
-      compress_mfma_packed_bf16<<<dim3((unsigned)((n_tok + 15) / 16), d_c / 16, batch), 256, 0, st>>>(
-          (const bf16_t*)x, n_tok, d_in, ldx, (const bf16_t*)W, (const bf16_t*)bias, d_c, (bf16_t*)out, ldo, x_bs,
-          out_bs);
+      // few tokens: the reduction is cut sixteen ways so that every lane's loads are all in flight at once
+      const dim3 grid((unsigned)((n_tok + 15) / 16), d_c / 16, batch);
+      if (d_in % 512 == 0 && n_tok <= 4096)
+        compress_mfma_packed_bf16<16><<<grid, 1024, 0, st>>>((const bf16_t*)x, n_tok, d_in, ldx, (const bf16_t*)W,
+                                                             (const bf16_t*)bias, d_c, (bf16_t*)out, ldo, x_bs, out_bs);
+      else
+        compress_mfma_packed_bf16<4><<<grid, 256, 0, st>>>((const bf16_t*)x, n_tok, d_in, ldx, (const bf16_t*)W,
+                                                           (const bf16_t*)bias, d_c, (bf16_t*)out, ldo, x_bs, out_bs);
     } else if (!packed && vec_ok && (d_c % kMCols == 0) && (d_in % kMStep == 0)) {
       compress_mfma_bf16<<<dim3((unsigned)nblk, d_c / kMCols, batch), 256, 0, st>>>(
           (const bf16_t*)x, n_tok, d_in, ldx, (const bf16_t*)W, (const bf16_t*)bias, d_c, (bf16_t*)out, ldo, x_bs,
