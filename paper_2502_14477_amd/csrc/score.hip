@@ -320,15 +320,29 @@ __global__ __launch_bounds__(256) void score_rowmax_reduce(const float* __restri
 // ------------------------------------------------------------------------------------------ decode (l_c = 1)
 // One current token: S is a matrix-vector product over the whole compressed-key cache, pure HBM
 // streaming.  LPR lanes share a K' row (16 bytes each), so a wave reads 64*16 contiguous bytes per
-// step.  Writes S and folds its maximum into mu; score_sub_mu then forms F = S - mu.
+// step, eight steps in flight.  Writes S and the workgroup's maximum of it (no atomics: thousands of
+// workgroups folding into one word serialise in L2); score_sub_mu then reduces those maxima to mu,
+// every workgroup for itself, and forms F = S - mu.
+constexpr int kGemvSteps = 32;
+
+// Sum over groups of LPR consecutive lanes (LPR = 8, 16, 32) with DPP moves; every lane gets the total.
+template <int LPR>
+__device__ __forceinline__ float lanes_sum(float v) {
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));    // quad_perm [1,0,3,2]
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true));   // row_half_mirror
+  if (LPR >= 16) v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true));   // row_mirror
+  if (LPR >= 32) v += __shfl_xor(v, 16, 64);
+  return v;
+}
+
 template <int LPR>
 __global__ __launch_bounds__(256) void score_gemv_bf16(const bf16_t* __restrict__ qc, const bf16_t* __restrict__ kc,
-                                                       int64_t m_lo, int64_t n, uint32_t* __restrict__ mu_keys,
+                                                       int64_t m_lo, int64_t n, float* __restrict__ part,
                                                        float* __restrict__ raw, int64_t q_bs, int64_t kc_bs,
                                                        int64_t raw_bs) {
   constexpr int kDcv = LPR * 8;
   constexpr int kRowsPerStep = 256 / LPR;
-  constexpr int kSteps = 16;
   __shared__ float red[4];
   const int b = blockIdx.y;
   const bf16_t* kmid = kc + (int64_t)b * kc_bs + m_lo * (int64_t)kDcv;
@@ -336,24 +350,27 @@ __global__ __launch_bounds__(256) void score_gemv_bf16(const bf16_t* __restrict_
   float qv[8];
   {
     const uint4 u = *(const uint4*)(qc + (int64_t)b * q_bs + sub * 8);
-    const bf16_t* pq = (const bf16_t*)&u;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) qv[i] = bf16_to_f32(pq[i]);
+    qv[0] = __uint_as_float(u.x << 16); qv[1] = __uint_as_float(u.x & 0xFFFF0000u);
+    qv[2] = __uint_as_float(u.y << 16); qv[3] = __uint_as_float(u.y & 0xFFFF0000u);
+    qv[4] = __uint_as_float(u.z << 16); qv[5] = __uint_as_float(u.z & 0xFFFF0000u);
+    qv[6] = __uint_as_float(u.w << 16); qv[7] = __uint_as_float(u.w & 0xFFFF0000u);
   }
   float best = -INFINITY;
-  const int64_t row0 = (int64_t)blockIdx.x * (kRowsPerStep * kSteps);
-#pragma unroll 4
-  for (int it = 0; it < kSteps; ++it) {
+  const int64_t row0 = (int64_t)blockIdx.x * (kRowsPerStep * kGemvSteps);
+#pragma unroll 8
+  for (int it = 0; it < kGemvSteps; ++it) {
     const int64_t row = row0 + it * kRowsPerStep + grp;
-    float s = 0.f;
-    if (row < n) {
-      const uint4 u = *(const uint4*)(kmid + row * kDcv + sub * 8);
-      const bf16_t* pk = (const bf16_t*)&u;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) s = __fmaf_rn(qv[i], bf16_to_f32(pk[i]), s);
-    }
-#pragma unroll
-    for (int off = LPR / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    uint4 u = make_uint4(0u, 0u, 0u, 0u);
+    if (row < n) u = *(const uint4*)(kmid + row * kDcv + sub * 8);
+    float s = qv[0] * __uint_as_float(u.x << 16);
+    s = __fmaf_rn(qv[1], __uint_as_float(u.x & 0xFFFF0000u), s);
+    s = __fmaf_rn(qv[2], __uint_as_float(u.y << 16), s);
+    s = __fmaf_rn(qv[3], __uint_as_float(u.y & 0xFFFF0000u), s);
+    s = __fmaf_rn(qv[4], __uint_as_float(u.z << 16), s);
+    s = __fmaf_rn(qv[5], __uint_as_float(u.z & 0xFFFF0000u), s);
+    s = __fmaf_rn(qv[6], __uint_as_float(u.w << 16), s);
+    s = __fmaf_rn(qv[7], __uint_as_float(u.w & 0xFFFF0000u), s);
+    s = lanes_sum<LPR>(s);
     if (row < n) {
       if (sub == 0) raw[(int64_t)b * raw_bs + row] = s;
       best = fmaxf(best, s);
@@ -363,11 +380,18 @@ __global__ __launch_bounds__(256) void score_gemv_bf16(const bf16_t* __restrict_
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = best;
   __syncthreads();
   if (threadIdx.x == 0)
-    atomicMax(&mu_keys[b], ordered_key(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]))));
+    part[(int64_t)b * gridDim.x + blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
-__global__ void score_sub_mu(float* __restrict__ raw, int64_t n, const uint32_t* __restrict__ mu_keys, int64_t raw_bs) {
-  const float mu = ordered_key_to_f32(mu_keys[blockIdx.y]);
+__global__ __launch_bounds__(256) void score_sub_mu(float* __restrict__ raw, int64_t n, const float* __restrict__ part,
+                                                    int n_part, int64_t raw_bs) {
+  __shared__ float red[4];
+  float mu = -INFINITY;
+  for (int i = threadIdx.x; i < n_part; i += 256) mu = fmaxf(mu, part[(int64_t)blockIdx.y * n_part + i]);
+  mu = wave_max(mu);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mu;
+  __syncthreads();
+  mu = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
   float* p = raw + (int64_t)blockIdx.y * raw_bs;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
     p[i] = p[i] - mu;
@@ -389,7 +413,12 @@ __global__ void proximity_maxpool(const float* __restrict__ in, float* __restric
 }  // namespace
 
 __host__ inline size_t part_bytes(int l_c, int64_t n_mid, int batch) {
-  return align_up((size_t)mfma_blocks(n_mid) * l_c * batch * 4, 256);
+  size_t blocks = (size_t)mfma_blocks(n_mid) * l_c;
+  if (l_c == 1) {   // the one-token kernel: a partial maximum per workgroup of at least 256 rows
+    const size_t gemv_blocks = (size_t)((n_mid + 255) / 256);
+    blocks = gemv_blocks > blocks ? gemv_blocks : blocks;
+  }
+  return align_up(blocks * batch * 4, 256);
 }
 
 size_t score_workspace_bytes(int l_c, int64_t n_mid, int eps, int batch) {
@@ -413,17 +442,18 @@ int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, in
   const bool vec_ok = dtype == ESA_BF16 && (((uintptr_t)qc | (uintptr_t)kc_cache) % 16 == 0) && q_bs % 8 == 0 &&
                       kc_bs % 8 == 0;
   if (vec_ok && l_c == 1 && (d_c == 64 || d_c == 128 || d_c == 256)) {
-    fill_u32<<<(batch + 255) / 256, 256, 0, st>>>(mu, (int64_t)batch, kOrderedKeyOfMinusInf);
     const int lpr = d_c / 8;
-    const int rows_per_block = (256 / lpr) * 16;
-    const dim3 grid((unsigned)((n + rows_per_block - 1) / rows_per_block), batch);
+    const int rows_per_block = (256 / lpr) * kGemvSteps;
+    const int nblk = (int)((n + rows_per_block - 1) / rows_per_block);
+    const dim3 grid((unsigned)nblk, batch);
     const bf16_t* q = (const bf16_t*)qc;
     const bf16_t* k = (const bf16_t*)kc_cache;
-    if (lpr == 8) score_gemv_bf16<8><<<grid, 256, 0, st>>>(q, k, m_lo, n, mu, raw, q_bs, kc_bs, raw_bs);
-    else if (lpr == 16) score_gemv_bf16<16><<<grid, 256, 0, st>>>(q, k, m_lo, n, mu, raw, q_bs, kc_bs, raw_bs);
-    else score_gemv_bf16<32><<<grid, 256, 0, st>>>(q, k, m_lo, n, mu, raw, q_bs, kc_bs, raw_bs);
+    float* part = (float*)((char*)ws + mu_bytes(l_c, batch));
+    if (lpr == 8) score_gemv_bf16<8><<<grid, 256, 0, st>>>(q, k, m_lo, n, part, raw, q_bs, kc_bs, raw_bs);
+    else if (lpr == 16) score_gemv_bf16<16><<<grid, 256, 0, st>>>(q, k, m_lo, n, part, raw, q_bs, kc_bs, raw_bs);
+    else score_gemv_bf16<32><<<grid, 256, 0, st>>>(q, k, m_lo, n, part, raw, q_bs, kc_bs, raw_bs);
     const int blocks = (int)((n + 1023) / 1024 < 2048 ? (n + 1023) / 1024 : 2048);
-    score_sub_mu<<<dim3(blocks, batch), 256, 0, st>>>(raw, n, mu, raw_bs);
+    score_sub_mu<<<dim3(blocks, batch), 256, 0, st>>>(raw, n, part, nblk, raw_bs);
   } else if (vec_ok && d_c == kDc) {
     const int per = (int)mfma_tiles_per_block(n);
     const int nblk = (int)mfma_blocks(n);
