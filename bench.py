@@ -67,9 +67,12 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true",
                     help="time eager launches instead of replaying the step as a captured HIP graph")
-    ap.add_argument("--two-branches", action="store_true",
-                    help="run the selection-independent part (key compression, attention over I, L, C) on a second "
-                         "stream beside compress/score/select/gather, and finish with esa_attend_finish")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="one stream and esa_attend in one call; by default the selection-independent part (key "
+                         "compression, attention over I, L, C) runs on a second stream beside select and gather and "
+                         "esa_attend_finish adds the selected keys")
+    ap.add_argument("--fork-after", choices=("start", "score"), default="score",
+                    help="where the second stream starts (the score sweeps want every CU for themselves)")
     ap.add_argument("--batch", type=int, default=1,
                     help="independent sequences per step (the decode configuration is also quoted at 16)")
     ap.add_argument("--prompt", action="store_true",
@@ -78,7 +81,8 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of the key cache (calibrates HBM traffic counters)")
     args = ap.parse_args()
-    args.single_stream = not args.two_branches
+    if args.eager:          # the profiling mode: one stream, one dispatch after the other
+        args.single_stream = True
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
 
@@ -136,21 +140,28 @@ def main():
     def step():
         # Two branches (Algorithm 1's split of the key set): the key compression (needed by later steps
         # only) and the attention over [I, L, C] do not depend on the selection, so they are enqueued on
-        # a second stream and run beside compress -> score -> select -> gather; the selected keys and the
-        # merge follow on the main stream.  Captured, the branches become parallel paths of the graph.
+        # a second stream, by default once the score sweeps (which want every CU) are done, and run
+        # beside select -> gather, which leave most of the chip idle; the selected keys and the merge
+        # follow on the main stream.  Captured, the branches become parallel paths of the graph.
         main = torch.cuda.current_stream()
-        if not args.single_stream:
+
+        def fork():
             side.wait_stream(main)
             with torch.cuda.stream(side):
                 esa.esa_compress(rows(K, t0, t0 + l_c), W_k, out=rows(kc, t0, t0 + l_c))
                 esa.esa_attend_local(Q, K, V, t0, cfg.l_I, cfg.l_L)
-        else:
+
+        if args.single_stream:
             esa.esa_compress(rows(K, t0, t0 + l_c), W_k, out=rows(kc, t0, t0 + l_c))
+        elif args.fork_after == "start":
+            fork()
         qc = esa.esa_compress(Q, W_q)
         if n_mid > cfg.k:
             score = esa.esa_score(qc, kc, i_end, l_start)
         else:
             score = torch.zeros(((B,) if B > 1 else ()) + (n_mid,), dtype=torch.float32, device="cuda")
+        if not args.single_stream and args.fork_after == "score":
+            fork()
         idx = esa.esa_select_topk(score, cfg.k, base=i_end)
         ks, vs = esa.esa_gather_kv(K, V, idx)
         if not args.single_stream:
