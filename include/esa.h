@@ -152,29 +152,41 @@ ESA_API int esa_attend(const void* q, int l_c, int h, int h_kv, int d,
 /*
  * Eq. 1 in two calls, cut where Algorithm 1 cuts it: the keys that do not depend on the selection
  * and the keys that do, each part a softmax of its own (running maximum and sum kept), the two merged
- * by their log-sum-exp weights.  Here the first part is [ I | L | C ] (Algorithm 1 puts I with the
- * selected tokens; it is known before the selection, so it goes with the early part) and the
- * second is M_k.  esa_attend_local can therefore be enqueued on another stream at the start of the
- * step and run beside compress / score / select / gather; esa_attend_finish needs the gathered
+ * by their log-sum-exp weights.  esa_attend_local can be enqueued on another stream at the start of
+ * the step and run beside compress / score / select / gather; esa_attend_finish needs the gathered
  * rows and must be ordered after esa_attend_local (event or same stream).
+ *   split = ESA_SPLIT_I_EARLY    early part [ I | L | C ], late part M_k: the initial tokens are known
+ *                                before the selection, so they go with the early part.  Both calls
+ *                                are given the same q and caches; the pair computes what esa_attend
+ *                                computes, to rounding (the slices' boundaries differ).
+ *   split = ESA_SPLIT_ALGORITHM1 early part [ L | C ] (causal), late part [ I | M_k ] (every key
+ *                                visible): Algorithm 1's grouping, for the position encoding of
+ *                                Section 3.2, where the two parts see differently encoded queries
+ *                                and keys.  esa_attend_local is given the queries and the key cache
+ *                                encoded with in-order positions; esa_attend_finish the queries
+ *                                encoded at the fixed position w, the key cache (rows [0, i_end) are
+ *                                read) and the gathered keys encoded at position 0.  Values are the
+ *                                same in both.  One softmax over the union, as in Eq. 1.
  *   esa_attend_local   arguments as esa_attend, without the gathered rows and the outputs; leaves
  *                      partial results in `workspace`
  *   esa_attend_finish  arguments exactly as esa_attend, same `workspace`; writes out / lse
- * Both calls must be given identical sizes, strides and workspace.  The pair computes what
- * esa_attend computes, to rounding (the slices' boundaries differ).  Shapes outside the
- * matrix-core kernel (fp32, head sizes other than 128, chunks shorter than 16 tokens) are served
- * whole by esa_attend_finish; esa_attend_local then enqueues nothing.
+ * Both calls must be given identical sizes, strides, split and workspace.  With ESA_SPLIT_I_EARLY,
+ * shapes outside the matrix-core kernel (fp32, head sizes other than 128, chunks shorter than 16
+ * tokens) are served whole by esa_attend_finish and esa_attend_local enqueues nothing; with
+ * ESA_SPLIT_ALGORITHM1 they run the plain kernel once per part.
  */
+#define ESA_SPLIT_I_EARLY 0
+#define ESA_SPLIT_ALGORITHM1 1
 ESA_API int esa_attend_local(const void* q, int l_c, int h, int h_kv, int d,
                const void* k_cache, const void* v_cache, int64_t tok_stride,
-               int64_t t0, int64_t l_i, int64_t l_l, float scale,
+               int64_t t0, int64_t l_i, int64_t l_l, float scale, int split,
                int dtype, int batch, int64_t q_bs, int64_t cache_bs,
                void* workspace, size_t ws_bytes, void* stream);
 ESA_API int esa_attend_finish(const void* q, int l_c, int h, int h_kv, int d,
                const void* k_cache, const void* v_cache, int64_t tok_stride,
                int64_t t0, int64_t l_i, int64_t l_l,
                const void* k_sel, const void* v_sel, int n_sel,
-               float scale, void* out, float* lse,
+               float scale, int split, void* out, float* lse,
                int dtype, int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs,
                void* workspace, size_t ws_bytes, void* stream);
 

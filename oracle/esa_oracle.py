@@ -194,6 +194,69 @@ def merge_partial_attention(outs, lses):
     return sum(f[..., None] * o for f, o in zip(fac, outs))
 
 
+# ----------------------------------------------------------------------------- Section 3.2: position encoding
+def rope(x: np.ndarray, positions, base: float) -> np.ndarray:
+    """Rotary position encoding of x [n, heads, d] at the given positions [n] (rotate-half form:
+    element i of the first half pairs with element i of the second half, angle pos * base^(-2i/d)).
+    Section 3.2 assumes a model "that utilizes RoPE"; position 0 leaves x unchanged.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    n, _, d = x.shape
+    half = d // 2
+    freq = np.asarray(base, dtype=np.float64) ** (-2.0 * np.arange(half, dtype=np.float64) / d)
+    ang = np.asarray(positions, dtype=np.float64).reshape(n, 1) * freq[None, :]
+    c, s_ = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    x1, x2 = x[:, :, :half], x[:, :, half:]
+    return np.concatenate([x1 * c - x2 * s_, x2 * c + x1 * s_], axis=2)
+
+
+def attend_two_encodings(q_l, q_g, K_l, K_g, V, t0: int, l_I: int, l_L: int, selected, scale: float):
+    """Eq. 1 with Algorithm 1's two groups of keys seen through their own encodings.
+
+    Logits of the local group (L and C, causal inside C) are q_l . K_l, logits of the global group
+    (I and the selected middle tokens, all visible) are q_g . K_g; one softmax over the union
+    ("we fuse the two categories of attention based on their respective weights", Section 3.2),
+    values shared.  q_* [l_C, H, d]; K_*, V [>= t0 + l_C, H_kv, d] indexed by absolute position.
+    Returns O [l_C, H, d] and lse [l_C, H].
+    """
+    q_l, q_g = np.asarray(q_l, dtype=np.float64), np.asarray(q_g, dtype=np.float64)
+    K_l, K_g, V = (np.asarray(a, dtype=np.float64) for a in (K_l, K_g, V))
+    l_C, H, d = q_l.shape
+    G = H // K_l.shape[1]
+    i_end, l_start = segments(t0, l_I, l_L)
+    pos_g = np.concatenate([np.arange(0, i_end, dtype=np.int64), np.asarray(selected, dtype=np.int64)])
+    pos_l = np.arange(l_start, t0 + l_C, dtype=np.int64)
+    visible_l = pos_l[None, :] <= (t0 + np.arange(l_C, dtype=np.int64))[:, None]
+    O = np.empty((l_C, H, d), dtype=np.float64)
+    lse = np.empty((l_C, H), dtype=np.float64)
+    for h in range(H):
+        g = h // G
+        a_g = (q_g[:, h, :] @ K_g[pos_g, g, :].T) * scale
+        a_l = np.where(visible_l, (q_l[:, h, :] @ K_l[pos_l, g, :].T) * scale, -np.inf)
+        a = np.concatenate([a_g, a_l], axis=1)
+        amax = a.max(axis=1, keepdims=True)
+        e = np.exp(a - amax)
+        z = e.sum(axis=1, keepdims=True)
+        O[:, h, :] = (e / z) @ np.concatenate([V[pos_g, g, :], V[pos_l, g, :]], axis=0)
+        lse[:, h] = (amax + np.log(z))[:, 0]
+    return O, lse
+
+
+def attend_reencoded(q_raw, K_raw, V, t0: int, l_I: int, l_L: int, selected, scale: float, w: float, base: float):
+    """Section 3.2 on un-encoded queries and keys: local keys at positions 0 .. n_L + l_C - 1 and local
+    queries at n_L .. n_L + l_C - 1 (n_L = number of local tokens actually present), global queries
+    all at position w, initial and selected keys at position 0."""
+    q_raw, K_raw = np.asarray(q_raw, dtype=np.float64), np.asarray(K_raw, dtype=np.float64)
+    l_C = q_raw.shape[0]
+    i_end, l_start = segments(t0, l_I, l_L)
+    n_L = t0 - l_start
+    K_l = np.zeros_like(K_raw)
+    K_l[l_start:t0 + l_C] = rope(K_raw[l_start:t0 + l_C], np.arange(n_L + l_C), base)
+    q_l = rope(q_raw, n_L + np.arange(l_C), base)
+    q_g = rope(q_raw, np.full(l_C, w, dtype=np.float64), base)
+    return attend_two_encodings(q_l, q_g, K_l, K_raw, V, t0, l_I, l_L, selected, scale)
+
+
 # ----------------------------------------------------------------------------- Eq. 10: plain attention
 def full_causal_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: float) -> np.ndarray:
     """Ordinary causal attention of all S tokens (Eq. 10 applied at every step); S small."""

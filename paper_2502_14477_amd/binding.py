@@ -62,9 +62,11 @@ def _load() -> ctypes.CDLL:
     L.esa_attend.argtypes = [vp, i32, i32, i32, i32, vp, vp, i64, i64, i64, i64, vp, vp, i32, f32, vp, vp,
                              i32, i32, i64, i64, i64, i64, vp, sz, vp]
     L.esa_attend_finish.restype = i32
-    L.esa_attend_finish.argtypes = L.esa_attend.argtypes
+    L.esa_attend_finish.argtypes = [vp, i32, i32, i32, i32, vp, vp, i64, i64, i64, i64, vp, vp, i32, f32, i32, vp, vp,
+                                    i32, i32, i64, i64, i64, i64, vp, sz, vp]
     L.esa_attend_local.restype = i32
-    L.esa_attend_local.argtypes = [vp, i32, i32, i32, i32, vp, vp, i64, i64, i64, i64, f32, i32, i32, i64, i64, vp, sz, vp]
+    L.esa_attend_local.argtypes = [vp, i32, i32, i32, i32, vp, vp, i64, i64, i64, i64, f32, i32, i32, i32, i64, i64,
+                                   vp, sz, vp]
     return L
 
 
@@ -219,10 +221,14 @@ def esa_gather_kv(k_cache: torch.Tensor, v_cache: torch.Tensor, idx: torch.Tenso
     return (ks, vs) if had_batch else (ks[0], vs[0])
 
 
+ESA_SPLIT_I_EARLY, ESA_SPLIT_ALGORITHM1 = 0, 1
+
+
 def esa_attend_local(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, t0: int, l_i: int, l_l: int,
-                     scale: Optional[float] = None) -> None:
-    """First half of the two-call form of esa_attend: the keys that do not depend on the selection.
-    Leaves partial results in the attend workspace for esa_attend_finish (same sizes, ordered after it)."""
+                     scale: Optional[float] = None, split: int = ESA_SPLIT_I_EARLY) -> None:
+    """First half of the two-call form of esa_attend: the keys that do not depend on the selection
+    ([I, L, C], or [L, C] with split = ESA_SPLIT_ALGORITHM1).  Leaves partial results in the attend
+    workspace for esa_attend_finish (same sizes and split, ordered after it)."""
     qb, _ = _batched(q, 3)
     kb, _ = _batched(k_cache, 3)
     vb, _ = _batched(v_cache, 3)
@@ -233,18 +239,20 @@ def esa_attend_local(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tens
     scale = float(d) ** -0.5 if scale is None else float(scale)
     nbytes = lib.esa_attend_workspace_bytes(l_c, h, h_kv, d, _dtype(q), B)
     ws = _workspace(nbytes, q.device, "attend")
-    _check(lib.esa_attend_local(_ptr(qb), l_c, h, h_kv, d, _ptr(kb), _ptr(vb), kb.stride(1), t0, l_i, l_l, scale,
+    _check(lib.esa_attend_local(_ptr(qb), l_c, h, h_kv, d, _ptr(kb), _ptr(vb), kb.stride(1), t0, l_i, l_l, scale, split,
                                 _dtype(q), B, qb.stride(0), kb.stride(0), _ptr(ws), ws.numel(), _stream()))
 
 
-def esa_attend_finish(q, k_cache, v_cache, t0, l_i, l_l, k_sel, v_sel, scale=None, return_lse=False):
-    """Second half of the two-call form: the selected keys, then the merge.  Arguments as esa_attend."""
-    return esa_attend(q, k_cache, v_cache, t0, l_i, l_l, k_sel, v_sel, scale, return_lse, _entry=lib.esa_attend_finish)
+def esa_attend_finish(q, k_cache, v_cache, t0, l_i, l_l, k_sel, v_sel, scale=None, return_lse=False,
+                      split: int = ESA_SPLIT_I_EARLY):
+    """Second half of the two-call form: the selected keys (with the initial tokens if split =
+    ESA_SPLIT_ALGORITHM1), then the merge.  Arguments as esa_attend."""
+    return esa_attend(q, k_cache, v_cache, t0, l_i, l_l, k_sel, v_sel, scale, return_lse, _split=split)
 
 
 def esa_attend(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, t0: int, l_i: int, l_l: int,
                k_sel: Optional[torch.Tensor], v_sel: Optional[torch.Tensor], scale: Optional[float] = None,
-               return_lse: bool = False, _entry=None):
+               return_lse: bool = False, _split: Optional[int] = None):
     """q [B?, l_c, h, d]; caches [B?, S, h_kv, d] holding the current tokens at rows t0..; gathered
     buffers [B?, n_sel, h_kv, d] -> out [B?, l_c, h, d] (and lse [B?, l_c, h] fp32)."""
     qb, had_batch = _batched(q, 3)
@@ -268,9 +276,14 @@ def esa_attend(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, t0
     scale = float(d) ** -0.5 if scale is None else float(scale)
     nbytes = lib.esa_attend_workspace_bytes(l_c, h, h_kv, d, _dtype(q), B)
     ws = _workspace(nbytes, q.device, "attend")
-    _check((_entry or lib.esa_attend)(_ptr(qb), l_c, h, h_kv, d, _ptr(kb), _ptr(vb), kb.stride(1), t0, l_i, l_l, _ptr(ksb),
-                          _ptr(vsb), n_sel, scale, _ptr(out), _ptr(lse), _dtype(q), B, qb.stride(0), kb.stride(0),
-                          sel_bs, out.stride(0), _ptr(ws), ws.numel(), _stream()))
+    if _split is None:
+        _check(lib.esa_attend(_ptr(qb), l_c, h, h_kv, d, _ptr(kb), _ptr(vb), kb.stride(1), t0, l_i, l_l, _ptr(ksb),
+                              _ptr(vsb), n_sel, scale, _ptr(out), _ptr(lse), _dtype(q), B, qb.stride(0), kb.stride(0),
+                              sel_bs, out.stride(0), _ptr(ws), ws.numel(), _stream()))
+    else:
+        _check(lib.esa_attend_finish(_ptr(qb), l_c, h, h_kv, d, _ptr(kb), _ptr(vb), kb.stride(1), t0, l_i, l_l,
+                                     _ptr(ksb), _ptr(vsb), n_sel, scale, _split, _ptr(out), _ptr(lse), _dtype(q), B,
+                                     qb.stride(0), kb.stride(0), sel_bs, out.stride(0), _ptr(ws), ws.numel(), _stream()))
     if not had_batch:
         out = out[0]
         lse = None if lse is None else lse[0]

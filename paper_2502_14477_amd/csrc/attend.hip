@@ -29,9 +29,9 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 // expf/logf.  Serves fp32 storage and every shape the matrix-core kernel does not cover.
 template <typename T>
 __global__ __launch_bounds__(256) void attend_fma(const T* __restrict__ q, int l_c, int h, int h_kv, int d, KeySpace ks,
-                                                  int64_t n_fixed, float scale, T* __restrict__ out,
-                                                  float* __restrict__ lse, int64_t q_bs, int64_t cache_bs_bytes,
-                                                  int64_t sel_bs_bytes, int64_t out_bs) {
+                                                  int64_t n_fixed, int with_chunk, float scale, T* __restrict__ out,
+                                                  float* __restrict__ out32, float* __restrict__ lse, int64_t q_bs,
+                                                  int64_t cache_bs_bytes, int64_t sel_bs_bytes, int64_t out_bs) {
   __shared__ float qs[256];
   __shared__ float p[256];
   __shared__ float red[4];
@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256) void attend_fma(const T* __restrict__ q, int l
   const T* qrow = q + (int64_t)b * q_bs + ((int64_t)c * h + hh) * d;
   if ((int)threadIdx.x < d) qs[threadIdx.x] = load_f32(qrow + threadIdx.x);
   __syncthreads();
-  const int64_t n_keys = n_fixed + c + 1;
+  const int64_t n_keys = n_fixed + (with_chunk ? c + 1 : 0);   // without the chunk every key is visible to every token
   const int nsub = 256 / d, dim = threadIdx.x % d, sub = threadIdx.x / d;
   float m_run = -INFINITY, l_run = 0.f, acc = 0.f;
   for (int64_t j0 = 0; j0 < n_keys; j0 += 256) {
@@ -80,9 +80,33 @@ __global__ __launch_bounds__(256) void attend_fma(const T* __restrict__ q, int l
   if ((int)threadIdx.x < d) {
     float o = 0.f;
     for (int s = 0; s < nsub; ++s) o += accs[s * d + threadIdx.x];
-    store_f32(out + (int64_t)b * out_bs + ((int64_t)c * h + hh) * d + threadIdx.x, o / l_run);
+    if (out32) out32[(((int64_t)b * l_c + c) * h + hh) * d + threadIdx.x] = o / l_run;   // one part of a two-call attention
+    else store_f32(out + (int64_t)b * out_bs + ((int64_t)c * h + hh) * d + threadIdx.x, o / l_run);
   }
   if (lse && threadIdx.x == 0) lse[((int64_t)b * l_c + c) * h + hh] = m_run + logf(l_run);
+}
+
+// Algorithm 1's merge of two attentions over disjoint key sets (normalised outputs and natural-log
+// normalisers): weights exp(lse_i - max).  A part without keys is passed as nullptr.
+template <typename T>
+__global__ void attend_merge_two(const float* __restrict__ o_a, const float* __restrict__ lse_a,
+                                 const float* __restrict__ o_b, const float* __restrict__ lse_b, int64_t rows_per_batch,
+                                 int d, T* __restrict__ out, int64_t out_bs, float* __restrict__ lse) {
+  const int64_t row = blockIdx.x, b = blockIdx.y, r = b * rows_per_batch + row;
+  const float la = lse_a[r], lb = lse_b ? lse_b[r] : -INFINITY;
+  const float m = fmaxf(la, lb);
+  const float wa = expf(la - m), wb = lse_b ? expf(lb - m) : 0.f;
+  const float inv = 1.f / (wa + wb);
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    const float v = (wa * o_a[r * d + i] + (o_b ? wb * o_b[r * d + i] : 0.f)) * inv;
+    store_f32(out + b * out_bs + row * d + i, v);
+  }
+  if (lse && threadIdx.x == 0) lse[r] = m + logf(wa + wb);
+}
+
+size_t generic_parts_bytes(int l_c, int h, int d, int batch) {
+  const size_t rows = (size_t)batch * l_c * h;
+  return 2 * (align_up(rows * d * sizeof(float), 256) + align_up(rows * sizeof(float), 256));
 }
 
 }  // namespace
@@ -90,24 +114,37 @@ __global__ __launch_bounds__(256) void attend_fma(const T* __restrict__ q, int l
 size_t attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch) {
   if (l_c <= 0 || h <= 0 || h_kv <= 0 || d <= 0 || batch <= 0) return 256;
   if (attend_mfma_supported(l_c, h, h_kv, d, dtype)) return attend_mfma_workspace_bytes(l_c, h, h_kv, d, batch);
-  if (attend_decode_supported(l_c, h, h_kv, d, dtype)) return attend_decode_workspace_bytes(l_c, h, batch);
-  return 256;
+  // shapes outside the matrix-core kernel: room for the two parts of a two-call attention
+  const size_t parts = generic_parts_bytes(l_c, h, d, batch);
+  if (attend_decode_supported(l_c, h, h_kv, d, dtype)) {
+    const size_t dec = attend_decode_workspace_bytes(l_c, h, batch);
+    return dec > parts ? dec : parts;
+  }
+  return parts;
 }
 
-int launch_attend(int part, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
+int launch_attend(int part, int split, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
                   int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, const void* k_sel, const void* v_sel,
                   int n_sel, float scale, void* out, float* lse, int dtype, int batch, int64_t q_bs,
                   int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes, hipStream_t st) {
   const Segments sg = segments(t0, l_i, l_l);
   const int64_t n_fixed = sg.i_end + n_sel + (t0 - sg.l_start);
-  if (attend_mfma_supported(l_c, h, h_kv, d, dtype) &&
-      attend_mfma_aligned(q, k_cache, v_cache, k_sel, v_sel, out, tok_stride, q_bs, cache_bs, sel_bs, out_bs)) {
-    return launch_attend_mfma(part, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, sg.i_end, sg.l_start, k_sel,
+  const bool mfma_shape = attend_mfma_supported(l_c, h, h_kv, d, dtype);
+  const bool mfma_aligned =
+      attend_mfma_aligned(q, k_cache, v_cache, k_sel, v_sel, out, tok_stride, q_bs, cache_bs, sel_bs, out_bs);
+  // The two calls of a separately encoded attention must take the same kernel: no fallback between them.
+  if (mfma_shape && !mfma_aligned && part != kAttendAll && split == ESA_SPLIT_ALGORITHM1)
+    ESA_FAIL(ESA_EINVAL, "esa_attend (two calls, Algorithm 1 grouping): pointers and strides must be 16-byte aligned");
+  if (mfma_shape && mfma_aligned) {
+    return launch_attend_mfma(part, split, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, sg.i_end, sg.l_start, k_sel,
                               v_sel, n_sel, scale, out, lse, batch, q_bs, cache_bs, sel_bs, out_bs, ws, ws_bytes, st);
   }
-  // every other shape is computed whole by the finishing (or the only) call
-  if (part == kAttendLocal) return ESA_OK;
-  if (attend_decode_supported(l_c, h, h_kv, d, dtype) && (int64_t)batch * l_c <= 65535 &&
+  // Every other shape.  With the initial tokens in the early part the finishing (or the only) call
+  // computes everything; Algorithm 1's grouping (separately encoded parts) runs the plain kernel once
+  // per part and merges.
+  const bool two_parts = part != kAttendAll && split == ESA_SPLIT_ALGORITHM1;
+  if (part == kAttendLocal && !two_parts) return ESA_OK;
+  if (!two_parts && attend_decode_supported(l_c, h, h_kv, d, dtype) && (int64_t)batch * l_c <= 65535 &&
       attend_decode_covers(n_fixed + l_c, l_c, h_kv, batch) &&
       attend_mfma_aligned(q, k_cache, v_cache, k_sel, v_sel, out, tok_stride, q_bs, cache_bs, sel_bs, out_bs)) {
     return launch_attend_decode(q, l_c, h, h_kv, k_cache, v_cache, tok_stride, t0, sg.i_end, sg.l_start, k_sel, v_sel,
@@ -124,13 +161,50 @@ int launch_attend(int part, const void* q, int l_c, int h, int h_kv, int d, cons
   ks.i_end = sg.i_end;
   ks.n_sel = n_sel;
   ks.l_start = sg.l_start;
+  int64_t fixed = n_fixed;
+  int with_chunk = 1;
+  float* o32 = nullptr;
+  float* lse_part = lse;
+  const size_t rows = (size_t)batch * l_c * h;
+  const size_t o_bytes = align_up(rows * d * sizeof(float), 256), l_bytes = align_up(rows * sizeof(float), 256);
+  float* o_a = (float*)ws;
+  float* lse_a = (float*)((char*)ws + o_bytes);
+  float* o_b = (float*)((char*)ws + o_bytes + l_bytes);
+  float* lse_b = (float*)((char*)ws + 2 * o_bytes + l_bytes);
+  if (two_parts) {
+    if (!ws || ws_bytes < generic_parts_bytes(l_c, h, d, batch)) ESA_FAIL(ESA_EWORKSPACE, "esa_attend: workspace too small");
+    if (part == kAttendLocal) {          // [ L | C ]
+      ks.i_end = 0;
+      ks.n_sel = 0;
+      fixed = t0 - sg.l_start;
+      o32 = o_a;
+      lse_part = lse_a;
+    } else {                             // [ I | M_k ], every key visible
+      fixed = sg.i_end + n_sel;
+      with_chunk = 0;
+      o32 = o_b;
+      lse_part = lse_b;
+    }
+  }
   const dim3 grid(l_c, h, batch);
-  if (dtype == ESA_BF16) {
-    attend_fma<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)q, l_c, h, h_kv, d, ks, n_fixed, scale, (bf16_t*)out, lse,
-                                             q_bs, cache_bs * esz, sel_bs * esz, out_bs);
-  } else {
-    attend_fma<float><<<grid, 256, 0, st>>>((const float*)q, l_c, h, h_kv, d, ks, n_fixed, scale, (float*)out, lse,
-                                            q_bs, cache_bs * esz, sel_bs * esz, out_bs);
+  if (!two_parts || part == kAttendLocal || fixed > 0) {
+    if (dtype == ESA_BF16) {
+      attend_fma<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)q, l_c, h, h_kv, d, ks, fixed, with_chunk, scale,
+                                               (bf16_t*)out, o32, lse_part, q_bs, cache_bs * esz, sel_bs * esz, out_bs);
+    } else {
+      attend_fma<float><<<grid, 256, 0, st>>>((const float*)q, l_c, h, h_kv, d, ks, fixed, with_chunk, scale, (float*)out,
+                                              o32, lse_part, q_bs, cache_bs * esz, sel_bs * esz, out_bs);
+    }
+  }
+  if (two_parts && part == kAttendFinish) {
+    const bool have_b = fixed > 0;
+    const dim3 mgrid((unsigned)(l_c * h), batch);
+    if (dtype == ESA_BF16)
+      attend_merge_two<bf16_t><<<mgrid, 64, 0, st>>>(o_a, lse_a, have_b ? o_b : nullptr, have_b ? lse_b : nullptr,
+                                                     (int64_t)l_c * h, d, (bf16_t*)out, out_bs, lse);
+    else
+      attend_merge_two<float><<<mgrid, 64, 0, st>>>(o_a, lse_a, have_b ? o_b : nullptr, have_b ? lse_b : nullptr,
+                                                    (int64_t)l_c * h, d, (float*)out, out_bs, lse);
   }
   ESA_LAUNCH_CHECK("attend_fma");
   return ESA_OK;

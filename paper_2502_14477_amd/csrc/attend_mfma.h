@@ -12,7 +12,7 @@ bool attend_mfma_aligned(const void* q, const void* k_cache, const void* v_cache
 // that does not depend on the selection ([ I | L | C ], partial results only) and the selected part plus merge.
 enum { kAttendAll = 0, kAttendLocal = 1, kAttendFinish = 2 };
 size_t attend_mfma_workspace_bytes(int l_c, int h, int h_kv, int d, int batch);
-int launch_attend_mfma(int part, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
+int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
                        int64_t tok_stride, int64_t t0, int64_t i_end, int64_t l_start, const void* k_sel,
                        const void* v_sel, int n_sel, float scale, void* out, float* lse, int batch, int64_t q_bs,
                        int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes, hipStream_t st);

@@ -485,7 +485,7 @@ size_t attend_mfma_workspace_bytes(int l_c, int h, int h_kv, int d, int batch) {
   return slots_bytes(n_slot, l_c, h, batch);
 }
 
-int launch_attend_mfma(int part, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache,
+int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache,
                        const void* v_cache, int64_t tok_stride, int64_t t0, int64_t i_end, int64_t l_start,
                        const void* k_sel, const void* v_sel, int n_sel, float scale, void* out, float* lse, int batch,
                        int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes,
@@ -525,8 +525,10 @@ int launch_attend_mfma(int part, const void* q, int l_c, int h, int h_kv, int d,
   };
   // slices in use: one call -> `all`; two calls -> local in slots [0, ns_local), selected in [plan.local, +ns_sel)
   const int ns_all = clamp(plan.all, i_end + n_sel + (t0 - l_start) + first_rows);
-  const int ns_local = clamp(plan.local, i_end + (t0 - l_start) + first_rows);
-  const int ns_sel = n_sel > 0 ? clamp(plan.sel, n_sel) : 0;
+  // split == ESA_SPLIT_ALGORITHM1 moves the initial tokens from the early part to the late one
+  const int64_t i_early = split == ESA_SPLIT_ALGORITHM1 ? 0 : i_end, i_late = i_end - i_early;
+  const int ns_local = clamp(plan.local, i_early + (t0 - l_start) + first_rows);
+  const int ns_sel = i_late + n_sel > 0 ? clamp(plan.sel, i_late + n_sel) : 0;
   const int n_slot = part == kAttendAll ? ns_all : plan.local + plan.sel;
 
   a.part_o = nullptr;
@@ -562,10 +564,10 @@ int launch_attend_mfma(int part, const void* q, int l_c, int h, int h_kv, int d,
       esa_attend_merge<<<merge_grid, 256, 0, st>>>(a.part_o, a.part_ml, n_slot, ns_all, 0, 0, rows, (bf16_t*)out, lse,
                                                    out_bs, rows);
   } else if (part == kAttendLocal) {
-    a.i_end = (uint32_t)i_end;
+    a.i_end = (uint32_t)i_early;
     a.n_sel = 0;
     a.l_start = (uint32_t)l_start;
-    a.n_fixed = (uint32_t)(i_end + (t0 - l_start));
+    a.n_fixed = (uint32_t)(i_early + (t0 - l_start));
     a.with_chunk = 1;
     a.n_split = ns_local;
     a.slot0 = 0;
@@ -573,10 +575,10 @@ int launch_attend_mfma(int part, const void* q, int l_c, int h, int h_kv, int d,
     attend_mfma_bf16<<<dim3((unsigned)((int64_t)batch * h_kv * a.n_qt * ns_local)), kThreads, kLdsBytes, st>>>(a);
   } else {
     if (ns_sel > 0) {
-      a.i_end = 0;
+      a.i_end = (uint32_t)i_late;
       a.n_sel = (uint32_t)n_sel;
       a.l_start = 0;
-      a.n_fixed = (uint32_t)n_sel;
+      a.n_fixed = (uint32_t)(i_late + n_sel);
       a.with_chunk = 0;
       a.n_split = ns_sel;
       a.slot0 = plan.local;

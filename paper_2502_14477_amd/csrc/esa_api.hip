@@ -137,12 +137,13 @@ size_t esa_attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, in
   return attend_workspace_bytes(l_c, h, h_kv, d, dtype, batch);
 }
 
-static int attend_checked(int part, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache,
+static int attend_checked(int part, int split, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache,
                           const void* v_cache, int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l,
                           const void* k_sel, const void* v_sel, int n_sel, float scale, void* out, float* lse,
                           int dtype, int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs,
                           void* workspace, size_t ws_bytes, void* stream) {
   if (!dtype_ok(dtype)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend: dtype %d", dtype);
+  if (split != ESA_SPLIT_I_EARLY && split != ESA_SPLIT_ALGORITHM1) ESA_FAIL(ESA_EINVAL, "esa_attend: split %d", split);
   if (l_c <= 0 || h <= 0 || h_kv <= 0 || d <= 0 || batch <= 0 || batch > kMaxBatch || n_sel < 0 || t0 < 0 ||
       l_i < 0 || l_l < 0 || l_c > 65535 || h > 65535)
     ESA_FAIL(ESA_EINVAL, "esa_attend: bad size (l_c=%d h=%d h_kv=%d d=%d batch=%d n_sel=%d t0=%lld)", l_c, h, h_kv, d,
@@ -165,7 +166,7 @@ static int attend_checked(int part, const void* q, int l_c, int h, int h_kv, int
   const size_t need = attend_workspace_bytes(l_c, h, h_kv, d, dtype, batch);
   if (need > 256 && (!workspace || !aligned(workspace, 256) || ws_bytes < need))
     ESA_FAIL(ESA_EWORKSPACE, "esa_attend: workspace needs %zu bytes, 256-byte aligned", need);
-  return launch_attend(part, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, k_sel, v_sel, n_sel, scale,
+  return launch_attend(part, split, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, k_sel, v_sel, n_sel, scale,
                        out, lse, dtype, batch, q_bs, cache_bs, sel_bs, out_bs, workspace, ws_bytes, (hipStream_t)stream);
 }
 
@@ -173,23 +174,23 @@ int esa_attend(const void* q, int l_c, int h, int h_kv, int d, const void* k_cac
                int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, const void* k_sel, const void* v_sel,
                int n_sel, float scale, void* out, float* lse, int dtype, int batch, int64_t q_bs, int64_t cache_bs,
                int64_t sel_bs, int64_t out_bs, void* workspace, size_t ws_bytes, void* stream) {
-  return attend_checked(kAttendAll, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, k_sel, v_sel, n_sel,
+  return attend_checked(kAttendAll, ESA_SPLIT_I_EARLY, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, k_sel, v_sel, n_sel,
                         scale, out, lse, dtype, batch, q_bs, cache_bs, sel_bs, out_bs, workspace, ws_bytes, stream);
 }
 
 int esa_attend_local(const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
-                     int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, float scale, int dtype, int batch,
-                     int64_t q_bs, int64_t cache_bs, void* workspace, size_t ws_bytes, void* stream) {
-  return attend_checked(kAttendLocal, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, nullptr, nullptr,
+                     int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, float scale, int split, int dtype,
+                     int batch, int64_t q_bs, int64_t cache_bs, void* workspace, size_t ws_bytes, void* stream) {
+  return attend_checked(kAttendLocal, split, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, nullptr, nullptr,
                         0, scale, nullptr, nullptr, dtype, batch, q_bs, cache_bs, 0, 0, workspace, ws_bytes, stream);
 }
 
 int esa_attend_finish(const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
                       int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, const void* k_sel, const void* v_sel,
-                      int n_sel, float scale, void* out, float* lse, int dtype, int batch, int64_t q_bs,
+                      int n_sel, float scale, int split, void* out, float* lse, int dtype, int batch, int64_t q_bs,
                       int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* workspace, size_t ws_bytes,
                       void* stream) {
-  return attend_checked(kAttendFinish, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, k_sel, v_sel,
+  return attend_checked(kAttendFinish, split, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, k_sel, v_sel,
                         n_sel, scale, out, lse, dtype, batch, q_bs, cache_bs, sel_bs, out_bs, workspace, ws_bytes,
                         stream);
 }

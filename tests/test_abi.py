@@ -74,3 +74,9 @@ def test_argument_validation_returns_codes_without_a_gpu():
     assert L.esa_attend(*args(4, 2, 48, 0, 100)) == -2
     assert L.esa_attend(*args(4, 2, 64, 200, 100)) == -1
     assert b"middle tokens" in L.esa_last_error()
+    # the two-call form: unknown split
+    assert L.esa_attend_local(fake, 8, 4, 2, 64, fake, fake, 128, 100, 4, 8, ctypes.c_float(0.1), 7, 0, 1, 0, 0,
+                              fake, 1 << 20, None) == -1
+    assert L.esa_attend_finish(fake, 8, 4, 2, 64, fake, fake, 128, 100, 4, 8, fake, fake, 0, ctypes.c_float(0.1), -1,
+                               fake, None, 0, 1, 0, 0, 0, 0, fake, 1 << 20, None) == -1
+    assert b"split" in L.esa_last_error()

@@ -278,6 +278,45 @@ def test_attend_in_two_calls_batched_with_the_local_part_on_a_side_stream(esa):
         assert np.max(np.abs(to_f64(lse[b]) - want_lse)) <= 1e-3
 
 
+@pytest.mark.parametrize("dtype,H,H_kv,d,t0,l_C,l_I,l_L,n_sel", [
+    ("bf16", 8, 2, 128, 1400, 96, 16, 300, 200),     # matrix-core kernel
+    ("bf16", 32, 8, 128, 5000, 512, 128, 2048, 2048),
+    ("bf16", 8, 2, 128, 40, 32, 16, 300, 0),         # early chunk: no middle tokens, I and L touch
+    ("bf16", 8, 2, 128, 0, 64, 16, 300, 0),          # first chunk: nothing but C
+    ("f32", 4, 2, 64, 900, 100, 8, 64, 31),          # plain kernel, one launch per part
+    ("bf16", 8, 2, 128, 2999, 1, 16, 256, 128)])     # decode shape
+def test_attend_with_the_position_encoding_of_section_3_2(esa, dtype, H, H_kv, d, t0, l_C, l_I, l_L, n_sel):
+    """Algorithm 1's grouping with separately encoded queries and keys: esa_attend_local on the in-order
+    encoding of L and C, esa_attend_finish on queries at the fixed position w against I and M_k at
+    position 0.  The encodings are applied on the host (the library takes Q and K as given)."""
+    say(f"attend, Section 3.2 encodings, dtype={dtype} H={H} H_kv={H_kv} d={d} t0={t0} l_C={l_C} n_sel={n_sel}")
+    rng = np.random.default_rng(1000 + t0 + l_C)
+    S, w, base = t0 + l_C, 4096.0, 500000.0
+    q_raw = rng.standard_normal((l_C, H, d))
+    K_raw = rng.standard_normal((S, H_kv, d))
+    V = orc.round_to_storage(rng.standard_normal((S, H_kv, d)), dtype)
+    i_end, l_start = segment_bounds(t0, l_I, l_L)
+    n_L = t0 - l_start
+    K_l = np.zeros_like(K_raw)
+    K_l[l_start:] = orc.rope(K_raw[l_start:], np.arange(n_L + l_C), base)
+    q_l = orc.round_to_storage(orc.rope(q_raw, n_L + np.arange(l_C), base), dtype)
+    q_g = orc.round_to_storage(orc.rope(q_raw, np.full(l_C, w), base), dtype)
+    K_l, K_g = orc.round_to_storage(K_l, dtype), orc.round_to_storage(K_raw, dtype)
+    sel = np.sort(rng.choice(np.arange(i_end, l_start), n_sel, replace=False)).astype(np.int32) if n_sel else \
+        np.empty(0, np.int32)
+    scale = 1.0 / np.sqrt(d)
+    want_O, want_lse = orc.attend_two_encodings(q_l, q_g, K_l, K_g, V, t0, l_I, l_L, sel, scale)
+    Vd, Kld, Kgd = f64_to_dev(V, dtype), f64_to_dev(K_l, dtype), f64_to_dev(K_g, dtype)
+    ks = vs = None
+    if n_sel:
+        ks, vs = esa.esa_gather_kv(Kgd, Vd, torch.from_numpy(sel).cuda())
+    esa.esa_attend_local(f64_to_dev(q_l, dtype), Kld, Vd, t0, l_I, l_L, split=esa.ESA_SPLIT_ALGORITHM1)
+    O, lse = esa.esa_attend_finish(f64_to_dev(q_g, dtype), Kgd, Vd, t0, l_I, l_L, ks, vs, return_lse=True,
+                                   split=esa.ESA_SPLIT_ALGORITHM1)
+    assert np.max(np.abs(to_f64(O) - want_O)) <= O_TOL[dtype]
+    assert np.max(np.abs(to_f64(lse) - want_lse)) <= (1e-5 if dtype == "f32" else 1e-3)
+
+
 # ------------------------------------------------------------------------------------------ whole steps
 def _check_step(esa, layer, dev, kc64, kc_dev, t0, stagewise_too=True, two_calls=False):
     cfg = layer.cfg

@@ -271,6 +271,87 @@ def test_step_selects_planted_tokens_and_decode_equals_prefill_with_one_token():
 
 
 # ------------------------------------------------------------------ Eq. 9, cache overhead, Appendix A
+# ----------------------------------------------------------------------------- Section 3.2
+def test_rope_is_a_rotation_that_composes_and_depends_on_relative_position_only():
+    """Catches: wrong pairing of elements, wrong sign of the sine term, wrong frequency exponent."""
+    rng = np.random.default_rng(5)
+    n, heads, d, base = 7, 3, 8, 10000.0
+    x, y = rng.standard_normal((n, heads, d)), rng.standard_normal((n, heads, d))
+    pos = rng.integers(0, 500, n)
+    assert np.array_equal(orc.rope(x, np.zeros(n), base), x)                       # position 0: identity
+    np.testing.assert_allclose(np.linalg.norm(orc.rope(x, pos, base), axis=2), np.linalg.norm(x, axis=2), rtol=1e-12)
+    np.testing.assert_allclose(orc.rope(orc.rope(x, pos, base), 3 * pos, base), orc.rope(x, 4 * pos, base), atol=1e-9)
+    # <R_a x, R_b y> = <R_(a+s) x, R_(b+s) y>
+    a, b, shift = rng.integers(0, 300, n), rng.integers(0, 300, n), 1234
+    dots = lambda pa, pb: np.einsum("nhd,nhd->nh", orc.rope(x, pa, base), orc.rope(y, pb, base))
+    np.testing.assert_allclose(dots(a, b), dots(a + shift, b + shift), atol=1e-9)
+    # closed form for one pair of elements: element i and i + d/2 turn by pos * base^(-2i/d), counter-clockwise
+    v = np.zeros((1, 1, d))
+    v[0, 0, 1], v[0, 0, 1 + d // 2] = 2.0, 0.5
+    ang = 11.0 * base ** (-2.0 * 1 / d)
+    got = orc.rope(v, [11], base)[0, 0]
+    np.testing.assert_allclose([got[1], got[1 + d // 2]],
+                               [2.0 * np.cos(ang) - 0.5 * np.sin(ang), 0.5 * np.cos(ang) + 2.0 * np.sin(ang)], rtol=1e-12)
+    assert np.count_nonzero(got) == 2
+
+
+def test_two_encodings_reduce_to_eq1_and_fuse_as_algorithm_1_says():
+    """Same tensors for both groups give Eq. 1 back; different tensors equal the two groups' own
+    softmaxes (written out here with scipy) fused by exp(lse) weights (Algorithm 1).
+    Catches: a group's logits taken from the wrong encoding, the causal mask applied to the global
+    group, I placed in the local group."""
+    rng = np.random.default_rng(6)
+    S, H, H_kv, d, l_C, l_I, l_L, t0 = 90, 4, 2, 8, 6, 5, 20, 84
+    Q, K, V = _qkv(S, H, H_kv, d, rng)
+    sel = np.array([7, 19, 33, 40, 61])
+    q = Q[t0:t0 + l_C]
+    want, want_lse = orc.attend(q, K, V, t0, l_I, l_L, sel, 0.3)
+    got, got_lse = orc.attend_two_encodings(q, q, K, K, V, t0, l_I, l_L, sel, 0.3)
+    np.testing.assert_allclose(got, want, atol=1e-12)
+    np.testing.assert_allclose(got_lse, want_lse, atol=1e-12)
+    # different encodings per group
+    q_g, K_g = rng.standard_normal(q.shape), rng.standard_normal(K.shape)
+    O, lse = orc.attend_two_encodings(q, q_g, K, K_g, V, t0, l_I, l_L, sel, 0.3)
+    glob = np.concatenate([np.arange(l_I), sel])
+    for c in range(l_C):
+        for h in range(H):
+            g = h // (H // H_kv)
+            a_g = 0.3 * K_g[glob, g] @ q_g[c, h]
+            loc = np.arange(t0 - l_L, t0 + c + 1)
+            a_l = 0.3 * K[loc, g] @ q[c, h]
+            o_g, o_l = softmax(a_g) @ V[glob, g], softmax(a_l) @ V[loc, g]
+            w_g, w_l = np.exp(logsumexp(a_g)), np.exp(logsumexp(a_l))
+            np.testing.assert_allclose(O[c, h], (w_g * o_g + w_l * o_l) / (w_g + w_l), atol=1e-12)
+            np.testing.assert_allclose(lse[c, h], np.log(w_g + w_l), atol=1e-12)
+
+
+def test_reencoded_positions_follow_section_3_2():
+    """Local logits depend on relative position only, so encoding L and C in order from 0 equals
+    encoding them at their absolute positions; global logits are those of relative position w for
+    every pair.  Catches: local positions not starting where the local window starts, w applied
+    to keys, selected keys encoded at their own position."""
+    rng = np.random.default_rng(7)
+    S, H, H_kv, d, l_C, l_I, l_L, t0, w, base = 80, 2, 1, 16, 4, 3, 12, 70, 37.0, 10000.0
+    Q, K, V = _qkv(S, H, H_kv, d, rng)
+    sel = np.array([9, 21, 22, 50])
+    q = Q[t0:t0 + l_C]
+    O, lse = orc.attend_reencoded(q, K, V, t0, l_I, l_L, sel, 0.25, w, base)
+    K_abs = orc.rope(K, np.arange(S), base)
+    q_abs = orc.rope(q, t0 + np.arange(l_C), base)
+    q_w = orc.rope(q, np.full(l_C, w), base)
+    want, want_lse = orc.attend_two_encodings(q_abs, q_w, K_abs, K, V, t0, l_I, l_L, sel, 0.25)
+    np.testing.assert_allclose(O, want, atol=1e-10)
+    np.testing.assert_allclose(lse, want_lse, atol=1e-10)
+    # a global logit is the dot product at relative position w whatever the key's own position
+    p = 21
+    assert np.isclose(q_w[1, 0] @ K[p, 0], orc.rope(q[1:2], [p + w], base)[0, 0] @ orc.rope(K[p:p + 1], [p], base)[0, 0])
+    # early chunk: fewer local tokens than l_L, no middle tokens
+    O2, _ = orc.attend_reencoded(Q[8:12], K, V, 8, l_I, l_L, np.empty(0, int), 0.25, w, base)
+    want2, _ = orc.attend_two_encodings(orc.rope(Q[8:12], 8 + np.arange(4), base), orc.rope(Q[8:12], np.full(4, w), base),
+                                        K_abs, K, V, 8, l_I, l_L, np.empty(0, int), 0.25)
+    np.testing.assert_allclose(O2, want2, atol=1e-10)
+
+
 def test_cost_model_reproduces_the_papers_numbers():
     g = _golden()
     d_c, d_H, H, H_G = int(g["d_prime"]), int(g["d_H"]), int(g["H"]), int(g["H_G"])
