@@ -71,6 +71,9 @@ def main():
                     help="one stream and esa_attend in one call; by default the selection-independent part (key "
                          "compression, attention over I, L, C) runs on a second stream beside select and gather and "
                          "esa_attend_finish adds the selected keys")
+    ap.add_argument("--fused-gather", action="store_true",
+                    help="variant: esa_attend_indexed follows the indices itself instead of esa_gather_kv + esa_attend "
+                         "(four calls; not the default step)")
     ap.add_argument("--fork-after", choices=("start", "score"), default="score",
                     help="where the second stream starts (the score sweeps want every CU for themselves)")
     ap.add_argument("--batch", type=int, default=1,
@@ -81,8 +84,6 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of the key cache (calibrates HBM traffic counters)")
     args = ap.parse_args()
-    if args.eager:          # the profiling mode: one stream, one dispatch after the other
-        args.single_stream = True
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
 
@@ -97,6 +98,10 @@ def main():
         cfg = cfg.scaled(S=args.seq)
     if args.prompt:
         return whole_prompt(args, cfg, esa, torch, np)
+    # one stream under the profiler (one dispatch after the other) and for decode-sized chunks, where
+    # nothing of the attention can start early and a second graph branch only costs launch latency
+    if args.eager or cfg.l_C < 16:
+        args.single_stream = True
     t0 = chunk_starts(cfg)[-1]
     l_c = min(cfg.l_C, cfg.S - t0)
     i_end, l_start = segment_bounds(t0, cfg.l_I, cfg.l_L)
@@ -163,6 +168,10 @@ def main():
         if not args.single_stream and args.fork_after == "score":
             fork()
         idx = esa.esa_select_topk(score, cfg.k, base=i_end)
+        if args.fused_gather:
+            if not args.single_stream:
+                main.wait_stream(side)
+            return esa.esa_attend_indexed(Q, K, V, t0, cfg.l_I, cfg.l_L, idx)
         ks, vs = esa.esa_gather_kv(K, V, idx)
         if not args.single_stream:
             main.wait_stream(side)
@@ -218,6 +227,7 @@ def main():
         "select": lambda: esa.esa_select_topk(score_s, cfg.k, base=i_end),
         "gather": lambda: esa.esa_gather_kv(K, V, idx_s),
         "attend": lambda: esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s),
+        "attend_indexed": lambda: esa.esa_attend_indexed(Q, K, V, t0, cfg.l_I, cfg.l_L, idx_s),
         "attend_local": lambda: esa.esa_attend_local(Q, K, V, t0, cfg.l_I, cfg.l_L),
         "attend_finish": lambda: esa.esa_attend_finish(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s),
     }
@@ -264,7 +274,7 @@ def main():
             rep["tflops"] = round(work[c]["flops"] / (us * 1e-6) / 1e12, 2)
         rep["gbs"] = round(work[c]["bytes"] / (us * 1e-6) / 1e9, 1)
         per_call_report[c] = rep
-    for c in ("attend_local", "attend_finish"):   # the two-call form of attend, as the step launches it
+    for c in ("attend_indexed", "attend_local", "attend_finish"):   # variants: fused gather, the two-call form
         per_call_report[c] = {"us": round(1e3 * call_ms[c], 2)}
     dominant = max(calls, key=lambda c: call_ms[c])
     if work[dominant]["flops"]:
@@ -301,7 +311,8 @@ def main():
                                   cfg.d_c, n_mid),
                    "global_batch": B, "seq_len": cfg.S, "parallelism": "single GPU"},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
-        "launch_mode": mode + (", one stream" if args.single_stream else ", two branches"), "eager_ms_per_step": round(eager_ms, 4), "setup_s": round(t_gen, 1),
+        "launch_mode": mode + (", one stream" if args.single_stream else ", two branches")
+        + (", gather fused into attend" if args.fused_gather else ""), "eager_ms_per_step": round(eager_ms, 4), "setup_s": round(t_gen, 1),
     }
     print(json.dumps(result))
 

@@ -190,6 +190,27 @@ ESA_API int esa_attend_finish(const void* q, int l_c, int h, int h_kv, int d,
                int dtype, int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs,
                void* workspace, size_t ws_bytes, void* stream);
 
+/*
+ * esa_gather_kv and esa_attend in one call: the selected tokens' keys and values are read from the
+ * caches through the index list (ascending absolute positions, as esa_select_topk writes them), so
+ * no gathered copy is written and read back ("a small number of keys and values are loaded" per
+ * step, Appendix B).  Computes exactly what esa_gather_kv followed by esa_attend computes.  Decode-
+ * sized chunks and the plain kernel follow the indices directly; the matrix-core prefill kernel
+ * works on tiles of consecutive rows and gathers into the workspace first.
+ *   idx  [batch][n_sel] int32, batch stride idx_bs; entries are positions of middle tokens (an entry
+ *        outside [0, l_start) is clamped into it rather than followed)
+ *   workspace esa_attend_indexed_workspace_bytes(...) bytes, 256-byte aligned
+ * Other arguments as esa_attend.
+ */
+ESA_API size_t esa_attend_indexed_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch, int n_sel);
+ESA_API int esa_attend_indexed(const void* q, int l_c, int h, int h_kv, int d,
+               const void* k_cache, const void* v_cache, int64_t tok_stride,
+               int64_t t0, int64_t l_i, int64_t l_l,
+               const int32_t* idx, int n_sel, int64_t idx_bs,
+               float scale, void* out, float* lse,
+               int dtype, int batch, int64_t q_bs, int64_t cache_bs, int64_t out_bs,
+               void* workspace, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

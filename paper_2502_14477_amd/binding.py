@@ -61,6 +61,11 @@ def _load() -> ctypes.CDLL:
     L.esa_attend.restype = i32
     L.esa_attend.argtypes = [vp, i32, i32, i32, i32, vp, vp, i64, i64, i64, i64, vp, vp, i32, f32, vp, vp,
                              i32, i32, i64, i64, i64, i64, vp, sz, vp]
+    L.esa_attend_indexed_workspace_bytes.restype = sz
+    L.esa_attend_indexed_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i32]
+    L.esa_attend_indexed.restype = i32
+    L.esa_attend_indexed.argtypes = [vp, i32, i32, i32, i32, vp, vp, i64, i64, i64, i64, vp, i32, i64, f32, vp, vp,
+                                     i32, i32, i64, i64, i64, vp, sz, vp]
     L.esa_attend_finish.restype = i32
     L.esa_attend_finish.argtypes = [vp, i32, i32, i32, i32, vp, vp, i64, i64, i64, i64, vp, vp, i32, f32, i32, vp, vp,
                                     i32, i32, i64, i64, i64, i64, vp, sz, vp]
@@ -74,7 +79,8 @@ lib = _load()
 
 EXPORTS = ("esa_version", "esa_last_error", "esa_segments", "esa_pack_weights", "esa_compress", "esa_score_workspace_bytes",
            "esa_score", "esa_select_topk_workspace_bytes", "esa_select_topk", "esa_gather_kv",
-           "esa_attend_workspace_bytes", "esa_attend", "esa_attend_local", "esa_attend_finish")
+           "esa_attend_workspace_bytes", "esa_attend", "esa_attend_local", "esa_attend_finish",
+           "esa_attend_indexed_workspace_bytes", "esa_attend_indexed")
 
 
 def _check(code: int) -> None:
@@ -222,6 +228,35 @@ def esa_gather_kv(k_cache: torch.Tensor, v_cache: torch.Tensor, idx: torch.Tenso
 
 
 ESA_SPLIT_I_EARLY, ESA_SPLIT_ALGORITHM1 = 0, 1
+
+
+def esa_attend_indexed(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, t0: int, l_i: int, l_l: int,
+                       idx: Optional[torch.Tensor], scale: Optional[float] = None, return_lse: bool = False):
+    """esa_gather_kv + esa_attend in one call: idx [B?, n_sel] int32 positions of the selected tokens."""
+    qb, had_batch = _batched(q, 3)
+    kb, _ = _batched(k_cache, 3)
+    vb, _ = _batched(v_cache, 3)
+    B, l_c, h, d = qb.shape
+    h_kv = kb.shape[2]
+    assert qb.is_contiguous() and kb.stride(3) == 1 and kb.stride(2) == d and vb.stride() == kb.stride()
+    assert kb.shape[1] >= t0 + l_c, "the cache must already hold the current tokens"
+    n_sel, idx_bs, ib = 0, 0, None
+    if idx is not None and idx.numel() > 0:
+        ib, _ = _batched(idx, 1)
+        assert ib.dtype == torch.int32 and ib.stride(1) == 1 and ib.shape[0] == B
+        n_sel, idx_bs = ib.shape[1], ib.stride(0)
+    out = torch.empty_like(qb)
+    lse = torch.empty((B, l_c, h), dtype=torch.float32, device=q.device) if return_lse else None
+    scale = float(d) ** -0.5 if scale is None else float(scale)
+    nbytes = lib.esa_attend_indexed_workspace_bytes(l_c, h, h_kv, d, _dtype(q), B, n_sel)
+    ws = _workspace(nbytes, q.device, "attend")
+    _check(lib.esa_attend_indexed(_ptr(qb), l_c, h, h_kv, d, _ptr(kb), _ptr(vb), kb.stride(1), t0, l_i, l_l, _ptr(ib),
+                                  n_sel, idx_bs, scale, _ptr(out), _ptr(lse), _dtype(q), B, qb.stride(0), kb.stride(0),
+                                  out.stride(0), _ptr(ws), ws.numel(), _stream()))
+    if not had_batch:
+        out = out[0]
+        lse = None if lse is None else lse[0]
+    return (out, lse) if return_lse else out
 
 
 def esa_attend_local(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, t0: int, l_i: int, l_l: int,

@@ -31,7 +31,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void attend_fma(const T* __restrict__ q, int l_c, int h, int h_kv, int d, KeySpace ks,
                                                   int64_t n_fixed, int with_chunk, float scale, T* __restrict__ out,
                                                   float* __restrict__ out32, float* __restrict__ lse, int64_t q_bs,
-                                                  int64_t cache_bs_bytes, int64_t sel_bs_bytes, int64_t out_bs) {
+                                                  int64_t cache_bs_bytes, int64_t sel_bs_bytes, int64_t idx_bs,
+                                                  int64_t out_bs) {
   __shared__ float qs[256];
   __shared__ float p[256];
   __shared__ float red[4];
@@ -40,7 +41,9 @@ __global__ __launch_bounds__(256) void attend_fma(const T* __restrict__ q, int l
   const int g = hh / (h / h_kv);
   ks.k_cache += (int64_t)b * cache_bs_bytes;
   ks.v_cache += (int64_t)b * cache_bs_bytes;
-  if (ks.n_sel > 0) {
+  if (ks.sel_idx) {
+    ks.sel_idx += (int64_t)b * idx_bs;
+  } else if (ks.n_sel > 0) {
     ks.k_sel += (int64_t)b * sel_bs_bytes;
     ks.v_sel += (int64_t)b * sel_bs_bytes;
   }
@@ -111,6 +114,13 @@ size_t generic_parts_bytes(int l_c, int h, int d, int batch) {
 
 }  // namespace
 
+size_t attend_indexed_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch, int n_sel) {
+  size_t b = attend_workspace_bytes(l_c, h, h_kv, d, dtype, batch);
+  if (l_c > 0 && h > 0 && h_kv > 0 && d > 0 && batch > 0 && n_sel > 0 && attend_mfma_supported(l_c, h, h_kv, d, dtype))
+    b = align_up(b, 256) + 2 * align_up((size_t)n_sel * h_kv * d * 2, 256) * batch;
+  return b;
+}
+
 size_t attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch) {
   if (l_c <= 0 || h <= 0 || h_kv <= 0 || d <= 0 || batch <= 0) return 256;
   if (attend_mfma_supported(l_c, h, h_kv, d, dtype)) return attend_mfma_workspace_bytes(l_c, h, h_kv, d, batch);
@@ -125,9 +135,11 @@ size_t attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int ba
 
 int launch_attend(int part, int split, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
                   int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, const void* k_sel, const void* v_sel,
-                  int n_sel, float scale, void* out, float* lse, int dtype, int batch, int64_t q_bs,
-                  int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes, hipStream_t st) {
+                  int n_sel, const int32_t* sel_idx, int64_t idx_bs, float scale, void* out, float* lse, int dtype,
+                  int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes,
+                  hipStream_t st) {
   const Segments sg = segments(t0, l_i, l_l);
+  if (n_sel == 0) sel_idx = nullptr;
   const int64_t n_fixed = sg.i_end + n_sel + (t0 - sg.l_start);
   const bool mfma_shape = attend_mfma_supported(l_c, h, h_kv, d, dtype);
   const bool mfma_aligned =
@@ -135,6 +147,21 @@ int launch_attend(int part, int split, const void* q, int l_c, int h, int h_kv, 
   // The two calls of a separately encoded attention must take the same kernel: no fallback between them.
   if (mfma_shape && !mfma_aligned && part != kAttendAll && split == ESA_SPLIT_ALGORITHM1)
     ESA_FAIL(ESA_EINVAL, "esa_attend (two calls, Algorithm 1 grouping): pointers and strides must be 16-byte aligned");
+  if (mfma_shape && mfma_aligned && sel_idx) {
+    // The matrix-core kernel addresses whole tiles of consecutive rows, so an index list is turned
+    // into gathered rows first (room for them follows the attention workspace proper).
+    const size_t own = attend_mfma_workspace_bytes(l_c, h, h_kv, d, batch);
+    const size_t rows_bytes = align_up((size_t)n_sel * h_kv * d * 2, 256);
+    if (!ws || ws_bytes < own + 2 * rows_bytes * batch) ESA_FAIL(ESA_EWORKSPACE, "esa_attend_indexed: workspace too small");
+    char* ks_tmp = (char*)ws + own;
+    char* vs_tmp = ks_tmp + rows_bytes * batch;
+    const int rc = launch_gather(k_cache, v_cache, tok_stride, sel_idx, n_sel, h_kv, d, ks_tmp, vs_tmp, dtype, batch,
+                                 cache_bs, idx_bs, (int64_t)(rows_bytes / 2), st);
+    if (rc != ESA_OK) return rc;
+    return launch_attend_mfma(part, split, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, sg.i_end, sg.l_start,
+                              ks_tmp, vs_tmp, n_sel, scale, out, lse, batch, q_bs, cache_bs, (int64_t)(rows_bytes / 2),
+                              out_bs, ws, own, st);
+  }
   if (mfma_shape && mfma_aligned) {
     return launch_attend_mfma(part, split, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, sg.i_end, sg.l_start, k_sel,
                               v_sel, n_sel, scale, out, lse, batch, q_bs, cache_bs, sel_bs, out_bs, ws, ws_bytes, st);
@@ -148,7 +175,7 @@ int launch_attend(int part, int split, const void* q, int l_c, int h, int h_kv, 
       attend_decode_covers(n_fixed + l_c, l_c, h_kv, batch) &&
       attend_mfma_aligned(q, k_cache, v_cache, k_sel, v_sel, out, tok_stride, q_bs, cache_bs, sel_bs, out_bs)) {
     return launch_attend_decode(q, l_c, h, h_kv, k_cache, v_cache, tok_stride, t0, sg.i_end, sg.l_start, k_sel, v_sel,
-                                n_sel, scale, out, lse, batch, q_bs, cache_bs, sel_bs, out_bs, ws, ws_bytes, st);
+                                n_sel, sel_idx, idx_bs, scale, out, lse, batch, q_bs, cache_bs, sel_bs, out_bs, ws, ws_bytes, st);
   }
   const int64_t esz = (dtype == ESA_F32) ? 4 : 2;
   KeySpace ks;
@@ -156,6 +183,7 @@ int launch_attend(int part, int split, const void* q, int l_c, int h, int h_kv, 
   ks.v_cache = (const char*)v_cache;
   ks.k_sel = (const char*)k_sel;
   ks.v_sel = (const char*)v_sel;
+  ks.sel_idx = sel_idx;
   ks.tok_bytes = tok_stride * esz;
   ks.sel_bytes = (int64_t)h_kv * d * esz;
   ks.i_end = sg.i_end;
@@ -190,10 +218,10 @@ int launch_attend(int part, int split, const void* q, int l_c, int h, int h_kv, 
   if (!two_parts || part == kAttendLocal || fixed > 0) {
     if (dtype == ESA_BF16) {
       attend_fma<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)q, l_c, h, h_kv, d, ks, fixed, with_chunk, scale,
-                                               (bf16_t*)out, o32, lse_part, q_bs, cache_bs * esz, sel_bs * esz, out_bs);
+                                               (bf16_t*)out, o32, lse_part, q_bs, cache_bs * esz, sel_bs * esz, idx_bs, out_bs);
     } else {
       attend_fma<float><<<grid, 256, 0, st>>>((const float*)q, l_c, h, h_kv, d, ks, fixed, with_chunk, scale, (float*)out,
-                                              o32, lse_part, q_bs, cache_bs * esz, sel_bs * esz, out_bs);
+                                              o32, lse_part, q_bs, cache_bs * esz, sel_bs * esz, idx_bs, out_bs);
     }
   }
   if (two_parts && part == kAttendFinish) {

@@ -49,7 +49,7 @@ struct DecodeArgs {
   int l_c, h_kv, splits, slice;
   float* part_o;     // [rows][splits][128]
   float* part_ml;    // [rows][splits][2]  (max of the base-2 logits, sum of 2^(logit - max))
-  int64_t q_bs, cache_bs_bytes, sel_bs_bytes;
+  int64_t q_bs, cache_bs_bytes, sel_bs_bytes, idx_bs;
 };
 
 template <int G>
@@ -64,7 +64,9 @@ __global__ __launch_bounds__(256) void attend_decode_bf16(DecodeArgs a) {
   KeySpace ks = a.ks;
   ks.k_cache += (int64_t)b * a.cache_bs_bytes;
   ks.v_cache += (int64_t)b * a.cache_bs_bytes;
-  if (ks.n_sel > 0) {
+  if (ks.sel_idx) {
+    ks.sel_idx += (int64_t)b * a.idx_bs;
+  } else if (ks.n_sel > 0) {
     ks.k_sel += (int64_t)b * a.sel_bs_bytes;
     ks.v_sel += (int64_t)b * a.sel_bs_bytes;
   }
@@ -293,8 +295,9 @@ size_t attend_decode_workspace_bytes(int l_c, int h, int batch) {
 
 int launch_attend_decode(const void* q, int l_c, int h, int h_kv, const void* k_cache, const void* v_cache,
                          int64_t tok_stride, int64_t t0, int64_t i_end, int64_t l_start, const void* k_sel,
-                         const void* v_sel, int n_sel, float scale, void* out, float* lse, int batch, int64_t q_bs,
-                         int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes, hipStream_t st) {
+                         const void* v_sel, int n_sel, const int32_t* sel_idx, int64_t idx_bs, float scale, void* out,
+                         float* lse, int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws,
+                         size_t ws_bytes, hipStream_t st) {
   const int64_t n_fixed = i_end + n_sel + (t0 - l_start);
   const Plan p = plan_for(n_fixed + l_c, l_c, h_kv, batch);
   if (p.splits <= 0) ESA_FAIL(ESA_EUNSUPPORTED, "attend_decode: %lld keys exceed the kernel's range", (long long)(n_fixed + l_c));
@@ -306,6 +309,8 @@ int launch_attend_decode(const void* q, int l_c, int h, int h_kv, const void* k_
   a.ks.v_cache = (const char*)v_cache;
   a.ks.k_sel = (const char*)k_sel;
   a.ks.v_sel = (const char*)v_sel;
+  a.ks.sel_idx = sel_idx;
+  a.idx_bs = idx_bs;
   a.ks.tok_bytes = tok_stride * 2;
   a.ks.sel_bytes = (int64_t)h_kv * kD * 2;
   a.ks.i_end = i_end;

@@ -139,9 +139,9 @@ size_t esa_attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, in
 
 static int attend_checked(int part, int split, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache,
                           const void* v_cache, int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l,
-                          const void* k_sel, const void* v_sel, int n_sel, float scale, void* out, float* lse,
-                          int dtype, int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs,
-                          void* workspace, size_t ws_bytes, void* stream) {
+                          const void* k_sel, const void* v_sel, int n_sel, const int32_t* sel_idx, int64_t idx_bs,
+                          float scale, void* out, float* lse, int dtype, int batch, int64_t q_bs, int64_t cache_bs,
+                          int64_t sel_bs, int64_t out_bs, void* workspace, size_t ws_bytes, void* stream) {
   if (!dtype_ok(dtype)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend: dtype %d", dtype);
   if (split != ESA_SPLIT_I_EARLY && split != ESA_SPLIT_ALGORITHM1) ESA_FAIL(ESA_EINVAL, "esa_attend: split %d", split);
   if (l_c <= 0 || h <= 0 || h_kv <= 0 || d <= 0 || batch <= 0 || batch > kMaxBatch || n_sel < 0 || t0 < 0 ||
@@ -152,7 +152,9 @@ static int attend_checked(int part, int split, const void* q, int l_c, int h, in
   if (d > 256 || 256 % d != 0) ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend: head size %d (32, 64, 128 or 256)", d);
   if (tok_stride < (int64_t)h_kv * d) ESA_FAIL(ESA_EINVAL, "esa_attend: tok_stride smaller than a token");
   if (!q || !k_cache || !v_cache || (part != kAttendLocal && !out)) ESA_FAIL(ESA_EINVAL, "esa_attend: null pointer");
-  if (n_sel > 0 && (!k_sel || !v_sel)) ESA_FAIL(ESA_EINVAL, "esa_attend: null gathered buffer with n_sel > 0");
+  if (n_sel > 0 && !sel_idx && (!k_sel || !v_sel))
+    ESA_FAIL(ESA_EINVAL, "esa_attend: null gathered buffer with n_sel > 0");
+  if (sel_idx && !aligned(sel_idx, 4)) ESA_FAIL(ESA_EINVAL, "esa_attend_indexed: misaligned index list");
   {
     const Segments sg = segments(t0, l_i, l_l);
     if (n_sel > sg.l_start - sg.i_end)
@@ -163,11 +165,12 @@ static int attend_checked(int part, int split, const void* q, int l_c, int h, in
   if (!aligned(q, es) || !aligned(k_cache, es) || !aligned(v_cache, es) || !aligned(k_sel, es) || !aligned(v_sel, es) ||
       !aligned(out, es) || !aligned(lse, 4))
     ESA_FAIL(ESA_EINVAL, "esa_attend: misaligned pointer");
-  const size_t need = attend_workspace_bytes(l_c, h, h_kv, d, dtype, batch);
+  const size_t need = sel_idx ? attend_indexed_workspace_bytes(l_c, h, h_kv, d, dtype, batch, n_sel)
+                              : attend_workspace_bytes(l_c, h, h_kv, d, dtype, batch);
   if (need > 256 && (!workspace || !aligned(workspace, 256) || ws_bytes < need))
     ESA_FAIL(ESA_EWORKSPACE, "esa_attend: workspace needs %zu bytes, 256-byte aligned", need);
-  return launch_attend(part, split, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, k_sel, v_sel, n_sel, scale,
-                       out, lse, dtype, batch, q_bs, cache_bs, sel_bs, out_bs, workspace, ws_bytes, (hipStream_t)stream);
+  return launch_attend(part, split, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, k_sel, v_sel, n_sel,
+                       n_sel > 0 ? sel_idx : nullptr, idx_bs, scale, out, lse, dtype, batch, q_bs, cache_bs, sel_bs, out_bs, workspace, ws_bytes, (hipStream_t)stream);
 }
 
 int esa_attend(const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
@@ -175,14 +178,14 @@ int esa_attend(const void* q, int l_c, int h, int h_kv, int d, const void* k_cac
                int n_sel, float scale, void* out, float* lse, int dtype, int batch, int64_t q_bs, int64_t cache_bs,
                int64_t sel_bs, int64_t out_bs, void* workspace, size_t ws_bytes, void* stream) {
   return attend_checked(kAttendAll, ESA_SPLIT_I_EARLY, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, k_sel, v_sel, n_sel,
-                        scale, out, lse, dtype, batch, q_bs, cache_bs, sel_bs, out_bs, workspace, ws_bytes, stream);
+                        nullptr, 0, scale, out, lse, dtype, batch, q_bs, cache_bs, sel_bs, out_bs, workspace, ws_bytes, stream);
 }
 
 int esa_attend_local(const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
                      int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, float scale, int split, int dtype,
                      int batch, int64_t q_bs, int64_t cache_bs, void* workspace, size_t ws_bytes, void* stream) {
   return attend_checked(kAttendLocal, split, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, nullptr, nullptr,
-                        0, scale, nullptr, nullptr, dtype, batch, q_bs, cache_bs, 0, 0, workspace, ws_bytes, stream);
+                        0, nullptr, 0, scale, nullptr, nullptr, dtype, batch, q_bs, cache_bs, 0, 0, workspace, ws_bytes, stream);
 }
 
 int esa_attend_finish(const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
@@ -191,8 +194,22 @@ int esa_attend_finish(const void* q, int l_c, int h, int h_kv, int d, const void
                       int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* workspace, size_t ws_bytes,
                       void* stream) {
   return attend_checked(kAttendFinish, split, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, k_sel, v_sel,
-                        n_sel, scale, out, lse, dtype, batch, q_bs, cache_bs, sel_bs, out_bs, workspace, ws_bytes,
+                        n_sel, nullptr, 0, scale, out, lse, dtype, batch, q_bs, cache_bs, sel_bs, out_bs, workspace, ws_bytes,
                         stream);
+}
+
+size_t esa_attend_indexed_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch, int n_sel) {
+  return attend_indexed_workspace_bytes(l_c, h, h_kv, d, dtype, batch, n_sel);
+}
+
+int esa_attend_indexed(const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
+                       int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, const int32_t* idx, int n_sel,
+                       int64_t idx_bs, float scale, void* out, float* lse, int dtype, int batch, int64_t q_bs,
+                       int64_t cache_bs, int64_t out_bs, void* workspace, size_t ws_bytes, void* stream) {
+  if (n_sel > 0 && !idx) ESA_FAIL(ESA_EINVAL, "esa_attend_indexed: null index list with n_sel > 0");
+  return attend_checked(kAttendAll, ESA_SPLIT_I_EARLY, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l,
+                        nullptr, nullptr, n_sel, idx, idx_bs, scale, out, lse, dtype, batch, q_bs, cache_bs, 0, out_bs,
+                        workspace, ws_bytes, stream);
 }
 
 }  // extern "C"

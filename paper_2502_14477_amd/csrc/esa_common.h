@@ -102,9 +102,11 @@ int launch_gather(const void* k_cache, const void* v_cache, int64_t tok_stride, 
                   int64_t idx_bs, int64_t sel_bs, hipStream_t st);
 
 size_t attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch);
+size_t attend_indexed_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch, int n_sel);
 int launch_attend(int part, int split, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
                   int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, const void* k_sel, const void* v_sel,
-                  int n_sel, float scale, void* out, float* lse, int dtype, int batch, int64_t q_bs,
-                  int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes, hipStream_t st);
+                  int n_sel, const int32_t* sel_idx, int64_t idx_bs, float scale, void* out, float* lse, int dtype,
+                  int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes,
+                  hipStream_t st);
 
 }  // namespace esa

@@ -317,6 +317,38 @@ def test_attend_with_the_position_encoding_of_section_3_2(esa, dtype, H, H_kv, d
     assert np.max(np.abs(to_f64(lse) - want_lse)) <= (1e-5 if dtype == "f32" else 1e-3)
 
 
+@pytest.mark.parametrize("dtype,B,H,H_kv,d,t0,l_C,l_I,l_L,n_sel", [
+    ("bf16", 1, 32, 8, 128, 5999, 1, 128, 2048, 2048),   # decode: indices followed inside the kernel
+    ("bf16", 3, 8, 2, 128, 2999, 2, 16, 256, 128),
+    ("bf16", 2, 8, 2, 128, 1400, 96, 16, 300, 200),      # matrix-core kernel: gathers into its workspace first
+    ("f32", 1, 4, 2, 64, 900, 100, 8, 64, 31),           # plain kernel
+    ("bf16", 1, 8, 2, 128, 300, 1, 16, 400, 0)])         # nothing selected
+def test_attend_indexed_equals_gather_then_attend(esa, dtype, B, H, H_kv, d, t0, l_C, l_I, l_L, n_sel):
+    say(f"attend_indexed dtype={dtype} B={B} H={H} H_kv={H_kv} d={d} t0={t0} l_C={l_C} n_sel={n_sel}")
+    rng = np.random.default_rng(2000 + t0 + l_C)
+    S = t0 + l_C
+    Q = orc.round_to_storage(rng.standard_normal((B, l_C, H, d)), dtype)
+    K = orc.round_to_storage(rng.standard_normal((B, S, H_kv, d)), dtype)
+    V = orc.round_to_storage(rng.standard_normal((B, S, H_kv, d)), dtype)
+    i_end, l_start = segment_bounds(t0, l_I, l_L)
+    sel = np.stack([np.sort(rng.choice(np.arange(i_end, l_start), n_sel, replace=False)) for _ in range(B)]).astype(np.int32) \
+        if n_sel else np.empty((B, 0), np.int32)
+    Qd, Kd, Vd = f64_to_dev(Q, dtype), f64_to_dev(K, dtype), f64_to_dev(V, dtype)
+    idx = torch.from_numpy(sel).cuda()
+    if B == 1:
+        Qd, Kd, Vd, idx = Qd[0], Kd[0], Vd[0], idx[0]
+    ks = vs = None
+    if n_sel:
+        ks, vs = esa.esa_gather_kv(Kd, Vd, idx)
+    want_O, want_lse = esa.esa_attend(Qd, Kd, Vd, t0, l_I, l_L, ks, vs, return_lse=True)
+    O, lse = esa.esa_attend_indexed(Qd, Kd, Vd, t0, l_I, l_L, idx, return_lse=True)
+    assert torch.equal(O, want_O) and torch.equal(lse, want_lse)       # the same arithmetic in the same order
+    for b in range(B):
+        o64, _ = orc.attend(Q[b], K[b], V[b], t0, l_I, l_L, sel[b], 1.0 / np.sqrt(d))
+        got = to_f64(O if B == 1 else O[b])
+        assert np.max(np.abs(got - o64)) <= O_TOL[dtype]
+
+
 # ------------------------------------------------------------------------------------------ whole steps
 def _check_step(esa, layer, dev, kc64, kc_dev, t0, stagewise_too=True, two_calls=False):
     cfg = layer.cfg
