@@ -47,6 +47,7 @@ constexpr int kMaxSplits = 8;
 constexpr int kMaxSlots = 2 * kMaxSplits;   // two-call form: local slices, then selected slices
 constexpr int kMinLc = 16;          // shorter chunks go to the plain kernel
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLazy = 8.f;        // the softmax reference lags the running maximum by at most 2^8
 constexpr float kLn2 = 0.6931471805599453f;
 
 struct AttendArgs {
@@ -284,7 +285,11 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[mt][v]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx * a.c2);
+    // The reference m_run of the exponentials follows the running maximum lazily: it moves only when
+    // a tile's maximum exceeds it by more than 2^kLazy, so probabilities stay below 2^kLazy (harmless
+    // in bf16 and fp32) and the accumulators are rescaled once or twice per row instead of per tile.
+    const float cand = mx * a.c2;
+    const float m_new = cand > m_run + kLazy ? cand : m_run;
     const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
     const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
     m_run = m_new;
@@ -548,6 +553,7 @@ int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h
     if (e != hipSuccess) return hip_failed(e, "hipFuncSetAttribute(attend_mfma_bf16)");
     lds_limit_raised = true;
   }
+  auto launch = [&](int64_t n_wg) { attend_mfma_bf16<<<dim3((unsigned)n_wg), kThreads, kLdsBytes, st>>>(a); };
   const int64_t rows = (int64_t)l_c * h;
   const dim3 merge_grid((unsigned)((rows + 7) / 8), batch);
   if (part == kAttendAll) {
@@ -559,7 +565,7 @@ int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h
     a.n_split = ns_all;
     a.slot0 = 0;
     a.to_slots = 0;
-    attend_mfma_bf16<<<dim3((unsigned)((int64_t)batch * h_kv * a.n_qt * ns_all)), kThreads, kLdsBytes, st>>>(a);
+    launch((int64_t)batch * h_kv * a.n_qt * ns_all);
     if (ns_all > 1)
       esa_attend_merge<<<merge_grid, 256, 0, st>>>(a.part_o, a.part_ml, n_slot, ns_all, 0, 0, rows, (bf16_t*)out, lse,
                                                    out_bs, rows);
@@ -572,7 +578,7 @@ int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h
     a.n_split = ns_local;
     a.slot0 = 0;
     a.to_slots = 1;
-    attend_mfma_bf16<<<dim3((unsigned)((int64_t)batch * h_kv * a.n_qt * ns_local)), kThreads, kLdsBytes, st>>>(a);
+    launch((int64_t)batch * h_kv * a.n_qt * ns_local);
   } else {
     if (ns_sel > 0) {
       a.i_end = (uint32_t)i_late;
@@ -583,7 +589,7 @@ int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h
       a.n_split = ns_sel;
       a.slot0 = plan.local;
       a.to_slots = 1;
-      attend_mfma_bf16<<<dim3((unsigned)((int64_t)batch * h_kv * a.n_qt * ns_sel)), kThreads, kLdsBytes, st>>>(a);
+      launch((int64_t)batch * h_kv * a.n_qt * ns_sel);
     }
     esa_attend_merge<<<merge_grid, 256, 0, st>>>(a.part_o, a.part_ml, n_slot, ns_local, plan.local, ns_sel, rows,
                                                  (bf16_t*)out, lse, out_bs, rows);
