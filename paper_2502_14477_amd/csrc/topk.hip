@@ -158,27 +158,32 @@ __device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t bin)
 // PASS 0: bits 31..21, PASS 1: bits 20..10, PASS 2: bits 9..0.
 template <int PASS>
 __global__ __launch_bounds__(kThreads) void topk_hist(const float* __restrict__ score, int64_t n, int64_t score_bs,
-                                                      uint32_t* __restrict__ ws, int64_t row_words, uint32_t k) {
+                                                      uint32_t* __restrict__ ws, int64_t row_words, uint32_t k,
+                                                      int sub) {
   __shared__ uint32_t h[kBins];
   __shared__ uint32_t wave_sums[kThreads / 64];
   __shared__ uint32_t result[2];
   const float* row = score + (int64_t)blockIdx.y * score_bs;
   uint32_t* w = ws + (int64_t)blockIdx.y * row_words;
+  const int64_t first = (int64_t)blockIdx.x * kTile * sub + (int64_t)threadIdx.x * kItems;
   uint32_t key[kItems];
   bool ok[kItems];
-  load_keys(row, n, (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems, key, ok);
+  load_keys(row, n, first, key, ok);
   for (int i = threadIdx.x; i < kBins; i += kThreads) h[i] = 0u;
   uint32_t prefix, k_rem;
   resolve_prefix<PASS>(w, k, wave_sums, result, &prefix, &k_rem);
   __syncthreads();
+  for (int st = 0; st < sub; ++st) {               // `sub` tiles of kTile scores, one histogram
+    if (st > 0) load_keys(row, n, first + (int64_t)st * kTile, key, ok);
 #pragma unroll
-  for (int e = 0; e < kItems; ++e) {
-    if (PASS == 0) {
-      hist_add(h, ok[e], key[e] >> 21);
-    } else if (PASS == 1) {
-      hist_add(h, ok[e] && (key[e] >> 21) == (prefix >> 21), (key[e] >> 10) & 2047u);
-    } else {
-      hist_add(h, ok[e] && (key[e] >> 10) == (prefix >> 10), key[e] & 1023u);
+    for (int e = 0; e < kItems; ++e) {
+      if (PASS == 0) {
+        hist_add(h, ok[e], key[e] >> 21);
+      } else if (PASS == 1) {
+        hist_add(h, ok[e] && (key[e] >> 21) == (prefix >> 21), (key[e] >> 10) & 2047u);
+      } else {
+        hist_add(h, ok[e] && (key[e] >> 10) == (prefix >> 10), key[e] & 1023u);
+      }
     }
   }
   __syncthreads();
@@ -190,21 +195,25 @@ __global__ __launch_bounds__(kThreads) void topk_hist(const float* __restrict__ 
 // Per block: how many scores lie above T and how many equal T.
 __global__ __launch_bounds__(kThreads) void topk_count(const float* __restrict__ score, int64_t n, int64_t score_bs,
                                                        uint32_t* __restrict__ ws, int64_t row_words, int nblk,
-                                                       uint32_t k) {
+                                                       uint32_t k, int sub) {
   __shared__ uint32_t wave_sums[kThreads / 64];
   __shared__ uint32_t result[2];
   const float* row = score + (int64_t)blockIdx.y * score_bs;
   uint32_t* w = ws + (int64_t)blockIdx.y * row_words;
+  const int64_t first = (int64_t)blockIdx.x * kTile * sub + (int64_t)threadIdx.x * kItems;
   uint32_t key[kItems];
   bool ok[kItems];
-  load_keys(row, n, (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems, key, ok);
+  load_keys(row, n, first, key, ok);
   uint32_t T, need;
   resolve_prefix<3>(w, k, wave_sums, result, &T, &need);
   uint32_t gt = 0, eq = 0;
+  for (int st = 0; st < sub; ++st) {
+    if (st > 0) load_keys(row, n, first + (int64_t)st * kTile, key, ok);
 #pragma unroll
-  for (int e = 0; e < kItems; ++e) {
-    gt += (ok[e] && key[e] > T) ? 1u : 0u;
-    eq += (ok[e] && key[e] == T) ? 1u : 0u;
+    for (int e = 0; e < kItems; ++e) {
+      gt += (ok[e] && key[e] > T) ? 1u : 0u;
+      eq += (ok[e] && key[e] == T) ? 1u : 0u;
+    }
   }
   uint32_t tot_gt, tot_eq;
   block_excl_scan(gt, &tot_gt, wave_sums);
@@ -218,16 +227,16 @@ __global__ __launch_bounds__(kThreads) void topk_count(const float* __restrict__
 __global__ __launch_bounds__(kThreads) void topk_write(const float* __restrict__ score, int64_t n, int64_t score_bs,
                                                        const uint32_t* __restrict__ ws, int64_t row_words, int nblk,
                                                        int64_t base, int32_t* __restrict__ idx, int64_t idx_bs,
-                                                       uint32_t k) {
+                                                       uint32_t k, int sub) {
   __shared__ uint32_t wave_sums[kThreads / 64];
   __shared__ uint32_t result[2];
   const float* row = score + (int64_t)blockIdx.y * score_bs;
   const uint32_t* w = ws + (int64_t)blockIdx.y * row_words;
   int32_t* out = idx + (int64_t)blockIdx.y * idx_bs;
-  const int64_t first = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems;
+  const int64_t first0 = (int64_t)blockIdx.x * kTile * sub + (int64_t)threadIdx.x * kItems;
   uint32_t key[kItems];
   bool ok[kItems];
-  load_keys(row, n, first, key, ok);
+  load_keys(row, n, first0, key, ok);
   // scores above / equal to T in the blocks before this one
   uint32_t my_gt = 0, my_eq = 0;
   for (int i = threadIdx.x; i < (int)blockIdx.x; i += kThreads) {
@@ -239,25 +248,31 @@ __global__ __launch_bounds__(kThreads) void topk_write(const float* __restrict__
   block_excl_scan(my_eq, &off_eq, wave_sums);
   uint32_t T, need;                                      // need: equal-to-T scores to take, lowest positions first
   resolve_prefix<3>(w, k, wave_sums, result, &T, &need);
-  uint32_t gt = 0, eq = 0;
+  for (int st = 0; st < sub; ++st) {                     // tiles in position order; the offsets run on
+    const int64_t first = first0 + (int64_t)st * kTile;
+    if (st > 0) load_keys(row, n, first, key, ok);
+    uint32_t gt = 0, eq = 0;
 #pragma unroll
-  for (int e = 0; e < kItems; ++e) {
-    gt += (ok[e] && key[e] > T) ? 1u : 0u;
-    eq += (ok[e] && key[e] == T) ? 1u : 0u;
-  }
-  uint32_t tot;
-  uint32_t g_before = off_gt + block_excl_scan(gt, &tot, wave_sums);
-  uint32_t e_before = off_eq + block_excl_scan(eq, &tot, wave_sums);
-#pragma unroll
-  for (int e = 0; e < kItems; ++e) {
-    if (!ok[e]) continue;
-    const bool is_gt = key[e] > T, is_eq = key[e] == T;
-    if (is_gt || (is_eq && e_before < need)) {
-      const uint32_t slot = g_before + (e_before < need ? e_before : need);
-      if (slot < k) out[slot] = (int32_t)(base + first + e);
+    for (int e = 0; e < kItems; ++e) {
+      gt += (ok[e] && key[e] > T) ? 1u : 0u;
+      eq += (ok[e] && key[e] == T) ? 1u : 0u;
     }
-    g_before += is_gt ? 1u : 0u;
-    e_before += is_eq ? 1u : 0u;
+    uint32_t tot_g, tot_e;
+    uint32_t g_before = off_gt + block_excl_scan(gt, &tot_g, wave_sums);
+    uint32_t e_before = off_eq + block_excl_scan(eq, &tot_e, wave_sums);
+#pragma unroll
+    for (int e = 0; e < kItems; ++e) {
+      if (!ok[e]) continue;
+      const bool is_gt = key[e] > T, is_eq = key[e] == T;
+      if (is_gt || (is_eq && e_before < need)) {
+        const uint32_t slot = g_before + (e_before < need ? e_before : need);
+        if (slot < k) out[slot] = (int32_t)(base + first + e);
+      }
+      g_before += is_gt ? 1u : 0u;
+      e_before += is_eq ? 1u : 0u;
+    }
+    off_gt += tot_g;
+    off_eq += tot_e;
   }
 }
 
@@ -284,17 +299,22 @@ int launch_topk(const float* score, int64_t n, int k, int64_t base, int32_t* idx
     ESA_LAUNCH_CHECK("topk_all");
     return ESA_OK;
   }
-  const int64_t nblk64 = (n + kTile - 1) / kTile;
-  const int nblk = (int)nblk64;
+  // One tile of kTile scores per workgroup while that keeps the chip busy (a call is latency-bound
+  // then); with many rows a workgroup takes several tiles, so that the fixed work per workgroup
+  // (prefix resolution, histogram flush) is paid by fewer of them.
+  const int64_t tiles = (n + kTile - 1) / kTile;
+  int64_t sub = (tiles * batch + 767) / 768;
+  sub = sub < 1 ? 1 : (sub > 8 ? 8 : sub);
+  const int nblk = (int)((tiles + sub - 1) / sub);
   const int64_t row_words = (int64_t)(align_up((size_t)topk_row_words(nblk) * sizeof(uint32_t), 256) / sizeof(uint32_t));
   uint32_t* w = (uint32_t*)ws;
   const dim3 grid(nblk, batch);
   topk_init<<<dim3(3, batch), 1024, 0, st>>>(w, row_words);
-  topk_hist<0><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, (uint32_t)k);
-  topk_hist<1><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, (uint32_t)k);
-  topk_hist<2><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, (uint32_t)k);
-  topk_count<<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, (uint32_t)k);
-  topk_write<<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, base, idx, idx_bs, (uint32_t)k);
+  topk_hist<0><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, (uint32_t)k, (int)sub);
+  topk_hist<1><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, (uint32_t)k, (int)sub);
+  topk_hist<2><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, (uint32_t)k, (int)sub);
+  topk_count<<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, (uint32_t)k, (int)sub);
+  topk_write<<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, base, idx, idx_bs, (uint32_t)k, (int)sub);
   ESA_LAUNCH_CHECK("topk");
   return ESA_OK;
 }

@@ -79,6 +79,18 @@ def test_select_topk_batched_rows_with_stride(esa):
         assert np.array_equal(got[b], orc.select_topk(s[b].astype(np.float64), k, base=3)), b
 
 
+@pytest.mark.parametrize("B,n,k", [(6, 300001, 2048), (16, 259967, 2048), (40, 1500000 // 8, 5)])
+def test_select_topk_many_rows_several_tiles_per_workgroup(esa, B, n, k):
+    """Enough rows that a workgroup takes several tiles (2, 3 and 6 here): offsets run across tiles."""
+    say(f"topk batch={B} n={n} k={k}")
+    rng = np.random.default_rng(B * 31 + k)
+    kinds = ("normal", "ties", "importance", "constant")
+    s = np.stack([_scores(rng, n, kinds[b % 4]) for b in range(B)])
+    got = esa.esa_select_topk(torch.from_numpy(s).cuda(), k, base=11).cpu().numpy()
+    for b in range(B):
+        assert np.array_equal(got[b], orc.select_topk(s[b].astype(np.float64), k, base=11)), b
+
+
 # ------------------------------------------------------------------------------------------ gather
 @pytest.mark.parametrize("dtype,h_kv,d,pad", [("f32", 2, 64, 0), ("bf16", 8, 128, 0), ("bf16", 2, 64, 24),
                                               ("f32", 1, 32, 5), ("bf16", 3, 32, 1)])
