@@ -222,6 +222,9 @@ def test_score_batched(esa):
     ("bf16", 4, 2, 128, 150000, 149999, 1, 128, 120000, 0),  # slices near their maximum length
     ("bf16", 4, 2, 128, 150000, 149999, 1, 128, 140000, 0),  # more keys than the decode kernel covers
     ("bf16", 8, 2, 128, 1500, 1203, 77, 16, 100, 55),    # ragged sizes
+    ("bf16", 4, 4, 128, 2300, 2000, 300, 16, 700, 333),  # matrix-core kernel, one query head per KV head
+    ("bf16", 4, 2, 128, 1900, 1700, 200, 16, 500, 100),  # two query heads per KV head
+    ("bf16", 16, 2, 128, 1000, 936, 64, 16, 400, 77),    # eight query heads per KV head
     ("bf16", 4, 4, 64, 900, 800, 100, 8, 64, 31)])
 def test_attend_matches_oracle(esa, dtype, H, H_kv, d, S, t0, l_C, l_I, l_L, n_sel):
     say(f"attend dtype={dtype} H={H} H_kv={H_kv} d={d} t0={t0} l_C={l_C} l_I={l_I} l_L={l_L} n_sel={n_sel}")
