@@ -98,9 +98,12 @@ def main():
         cfg = cfg.scaled(S=args.seq)
     if args.prompt:
         return whole_prompt(args, cfg, esa, torch, np)
-    # one stream under the profiler (one dispatch after the other) and for decode-sized chunks, where
-    # nothing of the attention can start early and a second graph branch only costs launch latency
-    if args.eager or cfg.l_C < 16:
+    # One stream under the profiler (one dispatch after the other); for decode-sized chunks, where
+    # nothing of the attention can start early and a second graph branch only costs launch latency;
+    # and when the selection-independent keys are too many to be attended to in the shadow of select
+    # and gather (about 25 us): then the two-call form only pays its second prologue and merge slots
+    # (configuration 5: 0.51 ms in one call, 0.58 ms in two).
+    if args.eager or cfg.l_C < 16 or cfg.l_I + cfg.l_L + cfg.l_C > 4096:
         args.single_stream = True
     t0 = chunk_starts(cfg)[-1]
     l_c = min(cfg.l_C, cfg.S - t0)
