@@ -167,7 +167,7 @@ def test_compress_writes_rows_of_a_strided_cache_in_place(esa):
 @pytest.mark.parametrize("dtype,l_c,n,d_c,m_lo", [
     ("f32", 128, 1632, 32, 32), ("f32", 1, 999, 32, 0), ("f32", 5, 63, 16, 7),
     ("bf16", 512, 30080, 128, 128), ("bf16", 1, 20000, 128, 128), ("bf16", 37, 2433, 128, 5),
-    ("bf16", 64, 4097, 64, 0)])
+    ("bf16", 64, 4097, 64, 0), ("bf16", 700, 5003, 128, 3), ("bf16", 1024, 33, 128, 0)])
 def test_score_matches_oracle_and_keeps_eq4_invariants(esa, dtype, l_c, n, d_c, m_lo):
     say(f"score dtype={dtype} l_c={l_c} n={n} d_c={d_c} m_lo={m_lo}")
     rng = np.random.default_rng(l_c * 31 + n)
@@ -206,6 +206,20 @@ def test_score_batched(esa):
     got = to_f64(esa.esa_score(f64_to_dev(qc, "bf16"), f64_to_dev(kc, "bf16"), 100, 1400))
     for b in range(B):
         assert np.max(np.abs(got[b] - orc.importance(qc[b], kc[b, 100:1400]))) <= F_TOL["bf16"]
+
+
+def test_score_batched_on_the_matrix_core_path_with_proximity_influence(esa):
+    say("score batch=3 d_c=128 l_c=100 eps=2")
+    rng = np.random.default_rng(10)
+    B, l_c, S, d_c, eps = 3, 100, 3300, 128, 2
+    qc = orc.round_to_storage(rng.standard_normal((B, l_c, d_c)), "bf16")
+    kc = orc.round_to_storage(rng.standard_normal((B, S, d_c)), "bf16")
+    plain = to_f64(esa.esa_score(f64_to_dev(qc, "bf16"), f64_to_dev(kc, "bf16"), 128, 3203))
+    pooled = to_f64(esa.esa_score(f64_to_dev(qc, "bf16"), f64_to_dev(kc, "bf16"), 128, 3203, eps=eps))
+    for b in range(B):
+        F = orc.importance(qc[b], kc[b, 128:3203])
+        assert np.max(np.abs(plain[b] - F)) <= F_TOL["bf16"]
+        assert np.max(np.abs(pooled[b] - orc.proximity(F, eps))) <= F_TOL["bf16"]
 
 
 # ------------------------------------------------------------------------------------------ attend
