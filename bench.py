@@ -189,11 +189,12 @@ def main():
         torch.cuda.synchronize()
         return 1e3 * (time.perf_counter() - t_start) / n
 
-    for _ in range(max(args.warmup, 1)):
-        step()
-    eager_ms = timed(step, args.steps)
-    ms_per_step, mode = eager_ms, "eager launches"
-    if not args.eager:
+    def time_step():
+        for _ in range(max(args.warmup, 1)):
+            step()
+        eager = timed(step, args.steps)
+        if args.eager:
+            return eager, eager, "eager launches"
         # The step is launch-bound on the host (about twenty small kernels), so it is captured once
         # as a HIP graph and replayed; every kernel of the step runs in every replay.
         warm = torch.cuda.Stream()
@@ -206,10 +207,21 @@ def main():
             graph_out = step()
         for _ in range(max(args.warmup, 1)):
             graph.replay()
-        ms_per_step, mode = timed(graph.replay, args.steps), "HIP graph replay"
+        replay = timed(graph.replay, args.steps)
         ref = step()
         torch.cuda.synchronize()
         assert torch.equal(ref, graph_out), "graph replay and eager step disagree"
+        return eager, replay, "HIP graph replay"
+
+    try:
+        eager_ms, ms_per_step, mode = time_step()
+    except Exception as exc:                # a second graph branch is an optimisation, not a requirement
+        if args.single_stream:
+            raise
+        print("bench.py: two-branch step failed (%s); timing the one-stream step" % exc, file=sys.stderr)
+        torch.cuda.synchronize()
+        args.single_stream = True
+        eager_ms, ms_per_step, mode = time_step()
 
     # Per-call durations from HIP events on the launch stream (torch's current stream).  Each call is
     # issued `reps` times back to back between two events, as one captured graph (as separate launches
