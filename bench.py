@@ -67,10 +67,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true",
                     help="time eager launches instead of replaying the step as a captured HIP graph")
-    ap.add_argument("--single-stream", action="store_true",
-                    help="one stream and esa_attend in one call; by default the selection-independent part (key "
-                         "compression, attention over I, L, C) runs on a second stream beside select and gather and "
-                         "esa_attend_finish adds the selected keys")
+    ap.add_argument("--two-branches", action="store_true",
+                    help="variant: the selection-independent part (key compression, attention over I, L, C) runs on a "
+                         "second stream beside select and gather and esa_attend_finish adds the selected keys; measured "
+                         "equal to the one-stream step at configuration 3, slower at configuration 5")
     ap.add_argument("--fused-gather", action="store_true",
                     help="variant: esa_attend_indexed follows the indices itself instead of esa_gather_kv + esa_attend "
                          "(four calls; not the default step)")
@@ -98,13 +98,9 @@ def main():
         cfg = cfg.scaled(S=args.seq)
     if args.prompt:
         return whole_prompt(args, cfg, esa, torch, np)
-    # One stream under the profiler (one dispatch after the other); for decode-sized chunks, where
-    # nothing of the attention can start early and a second graph branch only costs launch latency;
-    # and when the selection-independent keys are too many to be attended to in the shadow of select
-    # and gather (about 25 us): then the two-call form only pays its second prologue and merge slots
-    # (configuration 5: 0.51 ms in one call, 0.58 ms in two).
-    if args.eager or cfg.l_C < 16 or cfg.l_I + cfg.l_L + cfg.l_C > 4096:
-        args.single_stream = True
+    # One stream unless asked otherwise; always one stream under the profiler (one dispatch after the
+    # other) and for decode-sized chunks, where nothing of the attention can start early.
+    args.single_stream = not args.two_branches or args.eager or cfg.l_C < 16
     t0 = chunk_starts(cfg)[-1]
     l_c = min(cfg.l_C, cfg.S - t0)
     i_end, l_start = segment_bounds(t0, cfg.l_I, cfg.l_L)
