@@ -142,11 +142,10 @@ def main():
     side = torch.cuda.Stream()
 
     def step():
-        # Two branches (Algorithm 1's split of the key set): the key compression (needed by later steps
-        # only) and the attention over [I, L, C] do not depend on the selection, so they are enqueued on
-        # a second stream, by default once the score sweeps (which want every CU) are done, and run
-        # beside select -> gather, which leave most of the chip idle; the selected keys and the merge
-        # follow on the main stream.  Captured, the branches become parallel paths of the graph.
+        # The five calls on one stream.  With --two-branches (Algorithm 1's split of the key set) the key
+        # compression (needed by later steps only) and the attention over [I, L, C], which do not depend
+        # on the selection, go to a second stream once the score sweeps (which want every CU) are done,
+        # and run beside select -> gather; the selected keys and the merge follow on the main stream.
         main = torch.cuda.current_stream()
 
         def fork():
