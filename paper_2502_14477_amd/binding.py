@@ -104,6 +104,29 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else t.data_ptr()
 
 
+_hip = None
+
+
+def _cache_ptr(t: torch.Tensor) -> int:
+    """Device address of a KV cache: a GPU tensor, or pinned host memory (the KV cache offloaded to the
+    host as in Appendix B; the gather kernel then fetches the selected rows over the host link)."""
+    if t.is_cuda:
+        return t.data_ptr()
+    if not t.is_pinned():
+        raise ValueError("a KV cache in host memory must be pinned (torch's pin_memory), pageable memory is not "
+                         "addressable by the GPU")
+    global _hip
+    if _hip is None:
+        _hip = ctypes.CDLL("libamdhip64.so")
+        _hip.hipHostGetDevicePointer.restype = ctypes.c_int
+        _hip.hipHostGetDevicePointer.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p, ctypes.c_uint]
+    dptr = ctypes.c_void_p()
+    err = _hip.hipHostGetDevicePointer(ctypes.byref(dptr), ctypes.c_void_p(t.data_ptr()), 0)
+    if err != 0 or not dptr.value:
+        raise EsaError("hipHostGetDevicePointer failed (%d): the pinned cache is not mapped into the GPU" % err)
+    return dptr.value
+
+
 _ws_cache = {}
 
 
@@ -211,7 +234,8 @@ def esa_select_topk(score: torch.Tensor, k: int, base: int = 0) -> torch.Tensor:
 
 
 def esa_gather_kv(k_cache: torch.Tensor, v_cache: torch.Tensor, idx: torch.Tensor):
-    """caches [B?, S, h_kv, d], idx [B?, n_sel] int32 -> (k_sel, v_sel) [B?, n_sel, h_kv, d]."""
+    """caches [B?, S, h_kv, d] (GPU memory, or pinned host memory for an offloaded cache), idx [B?, n_sel]
+    int32 on the GPU -> (k_sel, v_sel) [B?, n_sel, h_kv, d] on the GPU."""
     kb, had_batch = _batched(k_cache, 3)
     vb, _ = _batched(v_cache, 3)
     ib, _ = _batched(idx, 1)
@@ -219,9 +243,9 @@ def esa_gather_kv(k_cache: torch.Tensor, v_cache: torch.Tensor, idx: torch.Tenso
     n_sel = ib.shape[1]
     assert vb.shape == kb.shape and vb.stride() == kb.stride() and kb.stride(3) == 1 and kb.stride(2) == d
     assert ib.dtype == torch.int32 and ib.shape[0] == B and (n_sel == 0 or ib.stride(1) == 1)
-    ks = torch.empty((B, n_sel, h_kv, d), dtype=k_cache.dtype, device=k_cache.device)
+    ks = torch.empty((B, n_sel, h_kv, d), dtype=k_cache.dtype, device=idx.device)
     vs = torch.empty_like(ks)
-    _check(lib.esa_gather_kv(_ptr(kb), _ptr(vb), kb.stride(1), _ptr(ib), n_sel, h_kv, d, _ptr(ks), _ptr(vs),
+    _check(lib.esa_gather_kv(_cache_ptr(kb), _cache_ptr(vb), kb.stride(1), _ptr(ib), n_sel, h_kv, d, _ptr(ks), _ptr(vs),
                              _dtype(k_cache), B, kb.stride(0), ib.stride(0) if B > 1 else max(n_sel, 1),
                              n_sel * h_kv * d, _stream()))
     return (ks, vs) if had_batch else (ks[0], vs[0])

@@ -113,6 +113,22 @@ def test_gather_is_byte_exact(esa, dtype, h_kv, d, pad):
     assert np.array_equal(to_f64(ks[0]), want)
 
 
+def test_gather_from_a_kv_cache_offloaded_to_pinned_host_memory(esa):
+    """Appendix B's deployment: the KV cache lives in host memory and only the selected rows are
+    loaded per step.  The same kernel reads the pinned cache through its device mapping."""
+    say("gather from pinned host memory")
+    rng = np.random.default_rng(404)
+    S, h_kv, d, n_sel = 20000, 8, 128, 2048
+    K = torch.from_numpy(rng.integers(0, 2**15, (S, h_kv, d), dtype=np.int16)).view(torch.bfloat16).pin_memory()
+    V = torch.from_numpy(rng.integers(0, 2**15, (S, h_kv, d), dtype=np.int16)).view(torch.bfloat16).pin_memory()
+    idx = torch.from_numpy(np.sort(rng.choice(S, n_sel, replace=False)).astype(np.int32))
+    ks, vs = esa.esa_gather_kv(K, V, idx.cuda())
+    assert ks.is_cuda and torch.equal(ks.cpu().view(torch.int16), K[idx.long()].view(torch.int16))
+    assert torch.equal(vs.cpu().view(torch.int16), V[idx.long()].view(torch.int16))
+    with pytest.raises(ValueError):
+        esa.esa_gather_kv(K.clone(), V.clone(), idx.cuda())       # pageable host memory is refused, not dereferenced
+
+
 # ------------------------------------------------------------------------------------------ compress
 @pytest.mark.parametrize("dtype,n_tok,heads,d,d_c,bias", [
     ("f32", 128, 4, 64, 32, False), ("f32", 37, 2, 64, 32, True), ("f32", 1, 4, 64, 32, False),
