@@ -120,7 +120,9 @@ ESA_API int esa_select_topk(const float* score, int64_t n, int k, int64_t base,
  *   k_cache, v_cache [batch][S, h_kv, d]  token stride tok_stride (>= h_kv*d), batch stride cache_bs
  *   idx              [batch][n_sel] token positions (each in [0, S); not checked on the device)
  *   k_sel, v_sel     [batch][n_sel, h_kv, d] contiguous, batch stride sel_bs
- * n_sel == 0 is a no-op.
+ * n_sel == 0 is a no-op.  The caches only have to be addressable by the GPU: with the KV cache
+ * offloaded to pinned, device-mapped host memory (Appendix B) the selected rows are fetched over
+ * the host link by the same call.
  */
 ESA_API int esa_gather_kv(const void* k_cache, const void* v_cache, int64_t tok_stride,
                   const int32_t* idx, int n_sel, int h_kv, int d,
