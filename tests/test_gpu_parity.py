@@ -283,6 +283,41 @@ def test_attend_matches_oracle(esa, dtype, H, H_kv, d, S, t0, l_C, l_I, l_L, n_s
     assert np.max(np.abs(to_f64(lse2) - want_lse)) <= (1e-5 if dtype == "f32" else 1e-3)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_attend_random_shapes_all_three_forms(esa, seed):
+    """Seeded random geometry (segment lengths, chunk length, group size, batch, selection size): the one-call,
+    two-call and index-driven forms against the oracle."""
+    rng = np.random.default_rng(9000 + seed)
+    G = int(rng.choice([1, 2, 4, 8]))
+    H_kv = int(rng.choice([1, 2, 3]))
+    H, d, B = G * H_kv, 128, int(rng.choice([1, 1, 2, 3]))
+    l_C = int(rng.choice([1, 7, 16, 33, 64, 100, 257, 300]))
+    l_I, l_L = int(rng.integers(0, 70)), int(rng.integers(0, 400))
+    t0 = int(rng.integers(0, 1500))
+    i_end, l_start = segment_bounds(t0, l_I, l_L)
+    n_mid = l_start - i_end
+    n_sel = int(rng.integers(0, min(n_mid, 300) + 1)) if n_mid > 0 else 0
+    say(f"attend random seed={seed}: B={B} H={H} H_kv={H_kv} t0={t0} l_C={l_C} l_I={l_I} l_L={l_L} n_sel={n_sel}")
+    S = t0 + l_C
+    Q = orc.round_to_storage(rng.standard_normal((B, l_C, H, d)), "bf16")
+    K = orc.round_to_storage(rng.standard_normal((B, S, H_kv, d)), "bf16")
+    V = orc.round_to_storage(rng.standard_normal((B, S, H_kv, d)), "bf16")
+    sel = np.stack([np.sort(rng.choice(np.arange(i_end, l_start), n_sel, replace=False)) for _ in range(B)]).astype(np.int32) \
+        if n_sel else np.empty((B, 0), np.int32)
+    Qd, Kd, Vd, idx = f64_to_dev(Q, "bf16"), f64_to_dev(K, "bf16"), f64_to_dev(V, "bf16"), torch.from_numpy(sel).cuda()
+    ks = vs = None
+    if n_sel:
+        ks, vs = esa.esa_gather_kv(Kd, Vd, idx)
+    O1 = esa.esa_attend(Qd, Kd, Vd, t0, l_I, l_L, ks, vs)
+    esa.esa_attend_local(Qd, Kd, Vd, t0, l_I, l_L)
+    O2 = esa.esa_attend_finish(Qd, Kd, Vd, t0, l_I, l_L, ks, vs)
+    O3 = esa.esa_attend_indexed(Qd, Kd, Vd, t0, l_I, l_L, idx)
+    for b in range(B):
+        want, _ = orc.attend(Q[b], K[b], V[b], t0, l_I, l_L, sel[b], 1.0 / np.sqrt(d))
+        for O in (O1, O2, O3):
+            assert np.max(np.abs(to_f64(O[b]) - want)) <= O_TOL["bf16"]
+
+
 def test_attend_batched(esa):
     say("attend batch=2 decode")
     rng = np.random.default_rng(77)
