@@ -224,6 +224,22 @@ def test_score_batched(esa):
         assert np.max(np.abs(got[b] - orc.importance(qc[b], kc[b, 100:1400]))) <= F_TOL["bf16"]
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_score_random_shapes(esa, seed):
+    rng = np.random.default_rng(7000 + seed)
+    dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+    d_c = int(rng.choice([128, 128, 64, 32])) if dtype == "bf16" else int(rng.choice([32, 48]))
+    B, l_c = int(rng.choice([1, 2, 3])), int(rng.choice([1, 5, 31, 64, 200, 513]))
+    n, m_lo, eps = int(rng.integers(1, 9000)), int(rng.integers(0, 300)), int(rng.choice([0, 0, 1, 4]))
+    say(f"score random seed={seed}: dtype={dtype} B={B} l_c={l_c} n={n} d_c={d_c} m_lo={m_lo} eps={eps}")
+    qc = orc.round_to_storage(rng.standard_normal((B, l_c, d_c)), dtype)
+    kc = orc.round_to_storage(rng.standard_normal((B, m_lo + n + 3, d_c)), dtype)
+    got = to_f64(esa.esa_score(f64_to_dev(qc, dtype), f64_to_dev(kc, dtype), m_lo, m_lo + n, eps=eps))
+    for b in range(B):
+        want = orc.proximity(orc.importance(qc[b], kc[b, m_lo:m_lo + n]), eps)
+        assert np.max(np.abs(got[b] - want)) <= F_TOL[dtype]
+
+
 def test_score_batched_on_the_matrix_core_path_with_proximity_influence(esa):
     say("score batch=3 d_c=128 l_c=100 eps=2")
     rng = np.random.default_rng(10)
