@@ -27,6 +27,7 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
+VARIANT_CALLS = ("attend_indexed", "attend_local", "attend_finish", "attend_reencoded")   # timed beside the step
 # HBM bytes per launch from the rocprofv3 counter passes summarised under profiles/ (FETCH_SIZE and
 # WRITE_SIZE per dispatch, each scaled by what the same counter reads for a plain 256 MiB device copy:
 # x2.0 for FETCH_SIZE, x1.0 for WRITE_SIZE), summed over the kernels of the call.  Counters cannot be
@@ -240,9 +241,11 @@ def main():
         "attend_indexed": lambda: esa.esa_attend_indexed(Q, K, V, t0, cfg.l_I, cfg.l_L, idx_s),
         "attend_local": lambda: esa.esa_attend_local(Q, K, V, t0, cfg.l_I, cfg.l_L),
         "attend_finish": lambda: esa.esa_attend_finish(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s),
+        # Section 3.2 inside the library (the inputs stand in for un-encoded ones: same work)
+        "attend_reencoded": lambda: esa.esa_attend_reencoded(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s, 4096.0, 5e5),
     }
     if args.eager:      # under the profiler: only the step's own launches, so that per-kernel averages are the step's
-        for c in ("attend_indexed", "attend_local", "attend_finish"):
+        for c in VARIANT_CALLS:
             del single[c]
     reps, rounds = 10, max(3, min(args.steps, 10))
     call_ms = {}
@@ -287,7 +290,7 @@ def main():
             rep["tflops"] = round(work[c]["flops"] / (us * 1e-6) / 1e12, 2)
         rep["gbs"] = round(work[c]["bytes"] / (us * 1e-6) / 1e9, 1)
         per_call_report[c] = rep
-    for c in ("attend_indexed", "attend_local", "attend_finish"):   # variants: fused gather, the two-call form
+    for c in VARIANT_CALLS:   # variants: fused gather, the two-call form, Section 3.2's re-encoding
         if c in call_ms:
             per_call_report[c] = {"us": round(1e3 * call_ms[c], 2)}
     dominant = max(calls, key=lambda c: call_ms[c])

@@ -213,6 +213,45 @@ ESA_API int esa_attend_indexed(const void* q, int l_c, int h, int h_kv, int d,
                int dtype, int batch, int64_t q_bs, int64_t cache_bs, int64_t out_bs,
                void* workspace, size_t ws_bytes, void* stream);
 
+/*
+ * Rotary position encoding of rows (Section 3.2 assumes a model that uses it): row i of
+ * x [n_tok][heads][d] is turned to position pos0 + i*pos_step, i.e. element j of a head's first half
+ * and element j of its second half rotate by the angle pos * base^(-2j/d) (rotate-half pairing).
+ * Position 0 leaves a row unchanged.  pos_step = 0 puts every row at pos0 (Section 3.2's fixed
+ * distance w of the global queries), pos_step = 1 numbers them in order (its local window).
+ * Computed in fp64 and rounded once into the storage type.
+ *   x, out  device pointers, row strides ldx / ldo and batch strides x_bs / out_bs in elements;
+ *           out may equal x when the strides are equal (in place), otherwise they must not overlap
+ *   d       a power of two from 2 to 256
+ * Errors: ESA_EINVAL (sizes, null or misaligned pointer, base <= 0), ESA_EUNSUPPORTED (dtype, d).
+ */
+ESA_API int esa_rope(const void* x, int64_t n_tok, int heads, int d, int64_t ldx,
+               double pos0, double pos_step, double base,
+               void* out, int64_t ldo, int dtype, int batch, int64_t x_bs, int64_t out_bs, void* stream);
+
+/*
+ * Eq. 1 with the position re-encoding of Section 3.2, on queries and key caches that carry NO
+ * position encoding yet: the local keys (the rows of L and C present) are encoded at positions
+ * 0, 1, ... in order and the chunk's queries at the positions that follow the local window; for
+ * the global part every query sits at the fixed position w and the initial and selected keys at
+ * position 0; the two groups of logits share one softmax (Algorithm 1's merge of the two partial
+ * attentions).  The library encodes the chunk's queries twice and the local rows of the key cache
+ * once into its workspace (esa_rope's arithmetic), then runs the local and the global part.
+ *   q, k_cache, k_sel   un-encoded; v_cache, v_sel, out, lse, sizes and strides as esa_attend
+ *   w, rope_base        the global queries' position and the encoding's base
+ *   workspace           esa_attend_reencoded_workspace_bytes(..., l_l) bytes, 256-byte aligned
+ * For bf16 storage with head size 128 and chunks of 16 tokens or more, pointers and strides must
+ * be 16-byte aligned (ESA_EINVAL otherwise).  Other errors as esa_attend.
+ */
+ESA_API size_t esa_attend_reencoded_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch, int64_t l_l);
+ESA_API int esa_attend_reencoded(const void* q, int l_c, int h, int h_kv, int d,
+               const void* k_cache, const void* v_cache, int64_t tok_stride,
+               int64_t t0, int64_t l_i, int64_t l_l,
+               const void* k_sel, const void* v_sel, int n_sel,
+               float scale, double w, double rope_base, void* out, float* lse,
+               int dtype, int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs,
+               void* workspace, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

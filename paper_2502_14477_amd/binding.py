@@ -72,6 +72,14 @@ def _load() -> ctypes.CDLL:
     L.esa_attend_local.restype = i32
     L.esa_attend_local.argtypes = [vp, i32, i32, i32, i32, vp, vp, i64, i64, i64, i64, f32, i32, i32, i32, i64, i64,
                                    vp, sz, vp]
+    f64 = ctypes.c_double
+    L.esa_rope.restype = i32
+    L.esa_rope.argtypes = [vp, i64, i32, i32, i64, f64, f64, f64, vp, i64, i32, i32, i64, i64, vp]
+    L.esa_attend_reencoded_workspace_bytes.restype = sz
+    L.esa_attend_reencoded_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i64]
+    L.esa_attend_reencoded.restype = i32
+    L.esa_attend_reencoded.argtypes = [vp, i32, i32, i32, i32, vp, vp, i64, i64, i64, i64, vp, vp, i32, f32, f64, f64,
+                                       vp, vp, i32, i32, i64, i64, i64, i64, vp, sz, vp]
     return L
 
 
@@ -80,7 +88,8 @@ lib = _load()
 EXPORTS = ("esa_version", "esa_last_error", "esa_segments", "esa_pack_weights", "esa_compress", "esa_score_workspace_bytes",
            "esa_score", "esa_select_topk_workspace_bytes", "esa_select_topk", "esa_gather_kv",
            "esa_attend_workspace_bytes", "esa_attend", "esa_attend_local", "esa_attend_finish",
-           "esa_attend_indexed_workspace_bytes", "esa_attend_indexed")
+           "esa_attend_indexed_workspace_bytes", "esa_attend_indexed", "esa_rope",
+           "esa_attend_reencoded_workspace_bytes", "esa_attend_reencoded")
 
 
 def _check(code: int) -> None:
@@ -277,6 +286,55 @@ def esa_attend_indexed(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Te
     _check(lib.esa_attend_indexed(_ptr(qb), l_c, h, h_kv, d, _ptr(kb), _ptr(vb), kb.stride(1), t0, l_i, l_l, _ptr(ib),
                                   n_sel, idx_bs, scale, _ptr(out), _ptr(lse), _dtype(q), B, qb.stride(0), kb.stride(0),
                                   out.stride(0), _ptr(ws), ws.numel(), _stream()))
+    if not had_batch:
+        out = out[0]
+        lse = None if lse is None else lse[0]
+    return (out, lse) if return_lse else out
+
+
+def esa_rope(x: torch.Tensor, pos0: float, pos_step: float, base: float, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Rotary encoding of x [B?, n_tok, heads, d]: row i goes to position pos0 + i*pos_step.  `out` may be
+    x itself (in place) or a view with the same shape (e.g. rows of a cache)."""
+    xb, had_batch = _batched(x, 3)
+    B, n_tok, heads, d = xb.shape
+    if out is None:
+        ob = torch.empty((B, n_tok, heads, d), dtype=x.dtype, device=x.device)
+        out = ob if had_batch else ob[0]
+    else:
+        ob, _ = _batched(out, 3)
+        assert ob.shape == xb.shape and ob.dtype == xb.dtype
+    for t in (xb, ob):
+        assert t.stride(3) == 1 and t.stride(2) == d
+    _check(lib.esa_rope(_ptr(xb), n_tok, heads, d, xb.stride(1), float(pos0), float(pos_step), float(base), _ptr(ob),
+                        ob.stride(1), _dtype(x), B, xb.stride(0), ob.stride(0), _stream()))
+    return out
+
+
+def esa_attend_reencoded(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, t0: int, l_i: int, l_l: int,
+                         k_sel: Optional[torch.Tensor], v_sel: Optional[torch.Tensor], w: float, rope_base: float,
+                         scale: Optional[float] = None, return_lse: bool = False):
+    """Section 3.2's attention on un-encoded q, key cache and gathered keys (shapes as esa_attend)."""
+    qb, had_batch = _batched(q, 3)
+    kb, _ = _batched(k_cache, 3)
+    vb, _ = _batched(v_cache, 3)
+    B, l_c, h, d = qb.shape
+    h_kv = kb.shape[2]
+    assert qb.is_contiguous() and kb.stride(3) == 1 and kb.stride(2) == d and vb.stride() == kb.stride()
+    assert kb.shape[1] >= t0 + l_c, "the cache must already hold the current tokens"
+    n_sel, sel_bs, ksb, vsb = 0, 0, None, None
+    if k_sel is not None and k_sel.numel() > 0:
+        ksb, _ = _batched(k_sel, 3)
+        vsb, _ = _batched(v_sel, 3)
+        assert ksb.is_contiguous() and vsb.is_contiguous() and ksb.shape == vsb.shape
+        n_sel, sel_bs = ksb.shape[1], ksb.stride(0)
+    out = torch.empty_like(qb)
+    lse = torch.empty((B, l_c, h), dtype=torch.float32, device=q.device) if return_lse else None
+    scale = float(d) ** -0.5 if scale is None else float(scale)
+    nbytes = lib.esa_attend_reencoded_workspace_bytes(l_c, h, h_kv, d, _dtype(q), B, l_l)
+    ws = _workspace(nbytes, q.device, "attend")
+    _check(lib.esa_attend_reencoded(_ptr(qb), l_c, h, h_kv, d, _ptr(kb), _ptr(vb), kb.stride(1), t0, l_i, l_l, _ptr(ksb),
+                                    _ptr(vsb), n_sel, scale, float(w), float(rope_base), _ptr(out), _ptr(lse), _dtype(q), B,
+                                    qb.stride(0), kb.stride(0), sel_bs, out.stride(0), _ptr(ws), ws.numel(), _stream()))
     if not had_batch:
         out = out[0]
         lse = None if lse is None else lse[0]

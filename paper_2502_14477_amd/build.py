@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libesa.so")
 
-SOURCES = ["esa_api.hip", "compress.hip", "score.hip", "topk.hip", "gather.hip", "attend.hip", "attend_mfma.hip", "attend_decode.hip"]
+SOURCES = ["esa_api.hip", "compress.hip", "score.hip", "topk.hip", "gather.hip", "attend.hip", "attend_mfma.hip", "attend_decode.hip", "rope.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -238,4 +238,57 @@ int launch_attend(int part, int split, const void* q, int l_c, int h, int h_kv, 
   return ESA_OK;
 }
 
+size_t attend_reencoded_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch, int64_t l_l) {
+  if (l_c <= 0 || h <= 0 || h_kv <= 0 || d <= 0 || batch <= 0 || l_l < 0) return 256;
+  const size_t esz = (dtype == ESA_F32) ? 4 : 2;
+  const size_t q_bytes = align_up((size_t)batch * l_c * h * d * esz, 256);
+  const size_t kv_bytes = align_up((size_t)batch * (size_t)(l_l + l_c) * h_kv * d * esz, 256);
+  return align_up(attend_workspace_bytes(l_c, h, h_kv, d, dtype, batch), 256) + 2 * q_bytes + 2 * kv_bytes;
+}
+
+// Section 3.2 on un-encoded queries and keys.  The workspace holds, behind the attention workspace
+// proper, the chunk's queries in their two encodings and a dense re-encoded copy of the local rows
+// [l_start, t0 + l_c) of the key cache with the matching value rows; the local part then runs on
+// that copy as a sequence of its own (no initial tokens, window = all of it), the global part on
+// the caller's un-encoded caches (position 0 is the identity), merged by Algorithm 1's rule.
+int launch_attend_reencoded(const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
+                            int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, const void* k_sel,
+                            const void* v_sel, int n_sel, float scale, double w, double base, void* out, float* lse,
+                            int dtype, int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs,
+                            void* ws, size_t ws_bytes, hipStream_t st) {
+  const Segments sg = segments(t0, l_i, l_l);
+  const int64_t n_loc = t0 - sg.l_start, rows = n_loc + l_c;
+  const size_t esz = (dtype == ESA_F32) ? 4 : 2;
+  const size_t own = align_up(attend_workspace_bytes(l_c, h, h_kv, d, dtype, batch), 256);
+  const size_t q_bytes = align_up((size_t)batch * l_c * h * d * esz, 256);
+  const size_t kv_bytes = align_up((size_t)batch * (size_t)rows * h_kv * d * esz, 256);
+  if (!ws || ws_bytes < own + 2 * q_bytes + 2 * kv_bytes)
+    ESA_FAIL(ESA_EWORKSPACE, "esa_attend_reencoded: workspace needs %zu bytes", own + 2 * q_bytes + 2 * kv_bytes);
+  char* q_loc = (char*)ws + own;
+  char* q_glob = q_loc + q_bytes;
+  char* k_loc = q_glob + q_bytes;
+  char* v_loc = k_loc + kv_bytes;
+  const int64_t q_row = (int64_t)h * d, kv_row = (int64_t)h_kv * d;
+  const int64_t qw_bs = (int64_t)l_c * q_row, kvw_bs = rows * kv_row;
+  if (attend_mfma_supported(l_c, h, h_kv, d, dtype) &&
+      !attend_mfma_aligned(q_loc, k_cache, v_cache, k_sel, v_sel, out, tok_stride, qw_bs, cache_bs, sel_bs, out_bs))
+    ESA_FAIL(ESA_EINVAL, "esa_attend_reencoded: pointers and strides must be 16-byte aligned for this shape");
+
+  RopeJob jobs[4];
+  jobs[0] = RopeJob{q, q_loc, l_c, q_row, q_row, q_bs, qw_bs, (double)n_loc, 1.0, h, 1};     // local queries, in order
+  jobs[1] = RopeJob{q, q_glob, l_c, q_row, q_row, q_bs, qw_bs, w, 0.0, h, 1};                // global queries, all at w
+  const char* k_rows = (const char*)k_cache + (size_t)sg.l_start * tok_stride * esz;
+  const char* v_rows = (const char*)v_cache + (size_t)sg.l_start * tok_stride * esz;
+  jobs[2] = RopeJob{k_rows, k_loc, rows, tok_stride, kv_row, cache_bs, kvw_bs, 0.0, 1.0, h_kv, 1};   // local keys from 0
+  jobs[3] = RopeJob{v_rows, v_loc, rows, tok_stride, kv_row, cache_bs, kvw_bs, 0.0, 0.0, h_kv, 0};   // their values
+  int rc = launch_rope_jobs(jobs, 4, d, base, dtype, batch, st);
+  if (rc != ESA_OK) return rc;
+  rc = launch_attend(kAttendLocal, ESA_SPLIT_ALGORITHM1, q_loc, l_c, h, h_kv, d, k_loc, v_loc, kv_row, n_loc, 0, n_loc,
+                     nullptr, nullptr, 0, nullptr, 0, scale, nullptr, nullptr, dtype, batch, qw_bs, kvw_bs, 0, 0, ws, own, st);
+  if (rc != ESA_OK) return rc;
+  return launch_attend(kAttendFinish, ESA_SPLIT_ALGORITHM1, q_glob, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i,
+                       l_l, k_sel, v_sel, n_sel, nullptr, 0, scale, out, lse, dtype, batch, qw_bs, cache_bs, sel_bs, out_bs,
+                       ws, own, st);
+}
+
 }  // namespace esa

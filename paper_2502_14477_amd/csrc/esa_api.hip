@@ -137,11 +137,11 @@ size_t esa_attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, in
   return attend_workspace_bytes(l_c, h, h_kv, d, dtype, batch);
 }
 
-static int attend_checked(int part, int split, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache,
+// Argument checks shared by every form of the attention call (everything but the workspace size).
+static int attend_args_ok(int part, int split, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache,
                           const void* v_cache, int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l,
-                          const void* k_sel, const void* v_sel, int n_sel, const int32_t* sel_idx, int64_t idx_bs,
-                          float scale, void* out, float* lse, int dtype, int batch, int64_t q_bs, int64_t cache_bs,
-                          int64_t sel_bs, int64_t out_bs, void* workspace, size_t ws_bytes, void* stream) {
+                          const void* k_sel, const void* v_sel, int n_sel, const int32_t* sel_idx, const void* out,
+                          const float* lse, int dtype, int batch) {
   if (!dtype_ok(dtype)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend: dtype %d", dtype);
   if (split != ESA_SPLIT_I_EARLY && split != ESA_SPLIT_ALGORITHM1) ESA_FAIL(ESA_EINVAL, "esa_attend: split %d", split);
   if (l_c <= 0 || h <= 0 || h_kv <= 0 || d <= 0 || batch <= 0 || batch > kMaxBatch || n_sel < 0 || t0 < 0 ||
@@ -165,6 +165,17 @@ static int attend_checked(int part, int split, const void* q, int l_c, int h, in
   if (!aligned(q, es) || !aligned(k_cache, es) || !aligned(v_cache, es) || !aligned(k_sel, es) || !aligned(v_sel, es) ||
       !aligned(out, es) || !aligned(lse, 4))
     ESA_FAIL(ESA_EINVAL, "esa_attend: misaligned pointer");
+  return ESA_OK;
+}
+
+static int attend_checked(int part, int split, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache,
+                          const void* v_cache, int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l,
+                          const void* k_sel, const void* v_sel, int n_sel, const int32_t* sel_idx, int64_t idx_bs,
+                          float scale, void* out, float* lse, int dtype, int batch, int64_t q_bs, int64_t cache_bs,
+                          int64_t sel_bs, int64_t out_bs, void* workspace, size_t ws_bytes, void* stream) {
+  const int rc = attend_args_ok(part, split, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, k_sel, v_sel,
+                                n_sel, sel_idx, out, lse, dtype, batch);
+  if (rc != ESA_OK) return rc;
   const size_t need = sel_idx ? attend_indexed_workspace_bytes(l_c, h, h_kv, d, dtype, batch, n_sel)
                               : attend_workspace_bytes(l_c, h, h_kv, d, dtype, batch);
   if (need > 256 && (!workspace || !aligned(workspace, 256) || ws_bytes < need))
@@ -210,6 +221,45 @@ int esa_attend_indexed(const void* q, int l_c, int h, int h_kv, int d, const voi
   return attend_checked(kAttendAll, ESA_SPLIT_I_EARLY, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l,
                         nullptr, nullptr, n_sel, idx, idx_bs, scale, out, lse, dtype, batch, q_bs, cache_bs, 0, out_bs,
                         workspace, ws_bytes, stream);
+}
+
+int esa_rope(const void* x, int64_t n_tok, int heads, int d, int64_t ldx, double pos0, double pos_step, double base,
+             void* out, int64_t ldo, int dtype, int batch, int64_t x_bs, int64_t out_bs, void* stream) {
+  if (!dtype_ok(dtype)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_rope: dtype %d", dtype);
+  if (n_tok < 0 || heads <= 0 || d <= 0 || batch <= 0 || batch > kMaxBatch || n_tok >= (int64_t)1 << 31)
+    ESA_FAIL(ESA_EINVAL, "esa_rope: bad size (n_tok=%lld heads=%d d=%d batch=%d)", (long long)n_tok, heads, d, batch);
+  if (!rope_head_size_ok(d)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_rope: head size %d (a power of two from 2 to 256)", d);
+  if (ldx < (int64_t)heads * d || ldo < (int64_t)heads * d) ESA_FAIL(ESA_EINVAL, "esa_rope: row stride smaller than the row");
+  if (!(base > 0.0)) ESA_FAIL(ESA_EINVAL, "esa_rope: base must be positive");
+  if (n_tok == 0) return ESA_OK;
+  if (!x || !out) ESA_FAIL(ESA_EINVAL, "esa_rope: null pointer");
+  if (!aligned(x, elem_size(dtype)) || !aligned(out, elem_size(dtype))) ESA_FAIL(ESA_EINVAL, "esa_rope: misaligned pointer");
+  if (x == out && (ldx != ldo || x_bs != out_bs)) ESA_FAIL(ESA_EINVAL, "esa_rope: in place needs equal strides");
+  const RopeJob job{x, out, n_tok, ldx, ldo, x_bs, out_bs, pos0, pos_step, heads, 1};
+  return launch_rope_jobs(&job, 1, d, base, dtype, batch, (hipStream_t)stream);
+}
+
+size_t esa_attend_reencoded_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch, int64_t l_l) {
+  return attend_reencoded_workspace_bytes(l_c, h, h_kv, d, dtype, batch, l_l);
+}
+
+int esa_attend_reencoded(const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
+                         int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, const void* k_sel, const void* v_sel,
+                         int n_sel, float scale, double w, double rope_base, void* out, float* lse, int dtype, int batch,
+                         int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* workspace, size_t ws_bytes,
+                         void* stream) {
+  const int rc = attend_args_ok(kAttendAll, ESA_SPLIT_ALGORITHM1, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i,
+                                l_l, k_sel, v_sel, n_sel, nullptr, out, lse, dtype, batch);
+  if (rc != ESA_OK) return rc;
+  if (!rope_head_size_ok(d)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend_reencoded: head size %d", d);
+  if (!(rope_base > 0.0) || !(w >= 0.0)) ESA_FAIL(ESA_EINVAL, "esa_attend_reencoded: base must be positive and w non-negative");
+  const Segments sg = segments(t0, l_i, l_l);
+  const size_t need = attend_reencoded_workspace_bytes(l_c, h, h_kv, d, dtype, batch, t0 - sg.l_start);
+  if (!workspace || !aligned(workspace, 256) || ws_bytes < need)
+    ESA_FAIL(ESA_EWORKSPACE, "esa_attend_reencoded: workspace needs %zu bytes, 256-byte aligned", need);
+  return launch_attend_reencoded(q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, k_sel, v_sel, n_sel, scale, w,
+                                 rope_base, out, lse, dtype, batch, q_bs, cache_bs, sel_bs, out_bs, workspace, ws_bytes,
+                                 (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -109,4 +109,24 @@ int launch_attend(int part, int split, const void* q, int l_c, int h, int h_kv, 
                   int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes,
                   hipStream_t st);
 
+// Section 3.2: rotary re-encoding.  One launch serves up to four row sets ("jobs"); row i of a job
+// is rotated to position pos0 + i * pos_step, or copied unchanged when rotate == 0.
+constexpr int kMaxRopeJobs = 4;
+struct RopeJob {
+  const void* x;
+  void* out;
+  int64_t n_tok, ldx, ldo, x_bs, out_bs;   // rows; row strides and batch strides in elements
+  double pos0, pos_step;
+  int heads, rotate;
+};
+bool rope_head_size_ok(int d);
+int launch_rope_jobs(const RopeJob* jobs, int n_jobs, int d, double base, int dtype, int batch, hipStream_t st);
+
+size_t attend_reencoded_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch, int64_t l_l);
+int launch_attend_reencoded(const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
+                            int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l, const void* k_sel,
+                            const void* v_sel, int n_sel, float scale, double w, double base, void* out, float* lse,
+                            int dtype, int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs,
+                            void* ws, size_t ws_bytes, hipStream_t st);
+
 }  // namespace esa

@@ -16,7 +16,7 @@ def _declared():
 
 def test_every_declared_symbol_is_exported_and_bound():
     names = _declared()
-    assert len(names) == 16 and "esa_attend" in names and "esa_select_topk" in names
+    assert len(names) == 19 and "esa_attend" in names and "esa_select_topk" in names
     raw = ctypes.CDLL(esa.lib_path())
     for n in names:
         assert hasattr(raw, n), n
@@ -80,3 +80,19 @@ def test_argument_validation_returns_codes_without_a_gpu():
     assert L.esa_attend_finish(fake, 8, 4, 2, 64, fake, fake, 128, 100, 4, 8, fake, fake, 0, ctypes.c_float(0.1), -1,
                                fake, None, 0, 1, 0, 0, 0, 0, fake, 1 << 20, None) == -1
     assert b"split" in L.esa_last_error()
+    # rotary encoding: head size not a power of two, row stride smaller than the row, in place with unequal strides
+    d64 = ctypes.c_double
+    rope = lambda x, heads, d, ldx, out, ldo, base=5e5: L.esa_rope(x, 4, heads, d, ldx, d64(0.0), d64(1.0), d64(base), out,
+                                                                    ldo, 1, 1, 0, 0, None)
+    assert rope(fake, 2, 48, 96, fake, 96) == -2
+    assert rope(fake, 2, 64, 100, fake, 128) == -1
+    assert rope(fake, 2, 64, 128, fake, 256) == -1
+    assert rope(fake, 2, 64, 128, None, 128) == -1
+    assert rope(fake, 2, 64, 128, fake, 128, base=0.0) == -1
+    assert L.esa_rope(None, 0, 2, 64, 128, d64(0.0), d64(1.0), d64(5e5), None, 128, 1, 1, 0, 0, None) == 0   # no rows: no-op
+    # re-encoded attention: workspace too small, negative w
+    re_args = lambda ws_bytes, w: (fake, 8, 4, 2, 64, fake, fake, 128, 100, 4, 8, fake, fake, 0, ctypes.c_float(0.1), d64(w),
+                                   d64(5e5), fake, None, 0, 1, 0, 0, 0, 0, fake, ws_bytes, None)
+    assert L.esa_attend_reencoded(*re_args(16, 4096.0)) == -3
+    assert L.esa_attend_reencoded(*re_args(1 << 30, -1.0)) == -1
+    assert L.esa_attend_reencoded_workspace_bytes(512, 32, 8, 128, 1, 1, 2048) > 2 * 512 * 4096 * 2 + 2 * 2560 * 1024 * 2

@@ -413,6 +413,71 @@ def test_attend_with_the_position_encoding_of_section_3_2(esa, dtype, H, H_kv, d
     assert np.max(np.abs(to_f64(lse) - want_lse)) <= (1e-5 if dtype == "f32" else 1e-3)
 
 
+@pytest.mark.parametrize("dtype,B,n_tok,heads,d,pos0,step,pad", [
+    ("bf16", 1, 700, 8, 128, 0.0, 1.0, 0),           # local keys in order from 0
+    ("bf16", 1, 512, 32, 128, 2048.0, 1.0, 0),       # local queries behind a window of 2048
+    ("bf16", 2, 96, 8, 128, 4096.0, 0.0, 64),        # global queries at w; padded rows; batched
+    ("bf16", 1, 33, 3, 64, 130000.0, 1.0, 8),        # large absolute positions
+    ("f32", 2, 100, 4, 64, 7.5, 1.0, 0),
+    ("f32", 1, 5, 2, 32, 0.0, 0.0, 0)])              # position 0: identity
+def test_rope_matches_the_fp64_definition_rounded_once(esa, dtype, B, n_tok, heads, d, pos0, step, pad):
+    say(f"rope dtype={dtype} B={B} n_tok={n_tok} heads={heads} d={d} pos0={pos0} step={step} pad={pad}")
+    rng = np.random.default_rng(4000 + n_tok + heads)
+    base = 500000.0
+    x = orc.round_to_storage(rng.standard_normal((B, n_tok, heads, d)), dtype)
+    want = np.stack([orc.round_to_storage(orc.rope(x[b], pos0 + step * np.arange(n_tok), base), dtype) for b in range(B)])
+    buf = torch.zeros((B, n_tok, heads * d + pad), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32,
+                      device="cuda")
+    xd = buf[:, :, :heads * d].unflatten(2, (heads, d))
+    xd.copy_(f64_to_dev(x, dtype))
+    got = to_f64(esa.esa_rope(xd, pos0, step, base))
+    # one rounding on each side of the same fp64 value: equal except where the two fp64 results differ in
+    # their last bits across a rounding boundary
+    ulp = np.abs(want) * (2.0 ** -7 if dtype == "bf16" else 2.0 ** -23)
+    assert np.all(np.abs(got - want) <= ulp)
+    assert np.count_nonzero(got != want) <= 1e-5 * want.size
+    if pos0 == 0.0 and step == 0.0:
+        assert np.array_equal(got, x)
+    esa.esa_rope(xd, pos0, step, base, out=xd)      # in place, strided rows
+    assert np.array_equal(to_f64(xd), got)
+    assert pad == 0 or float(buf[:, :, heads * d:].abs().max()) == 0.0
+
+
+@pytest.mark.parametrize("dtype,B,H,H_kv,d,t0,l_C,l_I,l_L,n_sel", [
+    ("bf16", 1, 8, 2, 128, 1400, 96, 16, 300, 200),     # matrix-core kernel
+    ("bf16", 1, 32, 8, 128, 5000, 512, 128, 2048, 2048),
+    ("bf16", 2, 8, 2, 128, 1400, 80, 16, 300, 150),     # batched
+    ("bf16", 1, 8, 2, 128, 40, 32, 16, 300, 0),         # early chunk: no middle tokens, I and L touch
+    ("bf16", 1, 8, 2, 128, 0, 64, 16, 300, 0),          # first chunk: nothing but C
+    ("f32", 1, 4, 2, 64, 900, 100, 8, 64, 31),          # plain kernel, one launch per part
+    ("f32", 2, 4, 2, 64, 900, 7, 8, 64, 31),
+    ("bf16", 1, 8, 2, 128, 2999, 1, 16, 256, 128)])     # decode shape
+def test_attend_reencoded_from_unencoded_queries_and_caches(esa, dtype, B, H, H_kv, d, t0, l_C, l_I, l_L, n_sel):
+    """Section 3.2 inside the library: un-encoded q, K cache and gathered keys in, esa_attend_reencoded
+    encodes and attends; the oracle applies the section's positions in fp64 without intermediate rounding."""
+    say(f"attend re-encoded dtype={dtype} B={B} H={H} H_kv={H_kv} d={d} t0={t0} l_C={l_C} l_I={l_I} l_L={l_L} n_sel={n_sel}")
+    rng = np.random.default_rng(2000 + t0 + l_C + B)
+    S, w, base = t0 + l_C + 3, 4096.0, 500000.0
+    q = orc.round_to_storage(rng.standard_normal((B, l_C, H, d)), dtype)
+    K = orc.round_to_storage(rng.standard_normal((B, S, H_kv, d)), dtype)
+    V = orc.round_to_storage(rng.standard_normal((B, S, H_kv, d)), dtype)
+    i_end, l_start = segment_bounds(t0, l_I, l_L)
+    sel = np.stack([np.sort(rng.choice(np.arange(i_end, l_start), n_sel, replace=False)) for _ in range(B)]).astype(np.int32) \
+        if n_sel else np.empty((B, 0), np.int32)
+    scale = 1.0 / np.sqrt(d)
+    qd, Kd, Vd = f64_to_dev(q, dtype), f64_to_dev(K, dtype), f64_to_dev(V, dtype)
+    K_before = Kd.clone()
+    ks = vs = None
+    if n_sel:
+        ks, vs = esa.esa_gather_kv(Kd, Vd, torch.from_numpy(sel).cuda())
+    O, lse = esa.esa_attend_reencoded(qd, Kd, Vd, t0, l_I, l_L, ks, vs, w, base, return_lse=True)
+    for b in range(B):
+        want_O, want_lse = orc.attend_reencoded(q[b], K[b], V[b], t0, l_I, l_L, sel[b], scale, w, base)
+        assert np.max(np.abs(to_f64(O[b]) - want_O)) <= O_TOL[dtype]
+        assert np.max(np.abs(to_f64(lse[b]) - want_lse)) <= (2e-5 if dtype == "f32" else 4e-3)
+    assert torch.equal(Kd, K_before)                  # the caller's cache stays un-encoded
+
+
 @pytest.mark.parametrize("dtype,B,H,H_kv,d,t0,l_C,l_I,l_L,n_sel", [
     ("bf16", 1, 32, 8, 128, 5999, 1, 128, 2048, 2048),   # decode: indices followed inside the kernel
     ("bf16", 3, 8, 2, 128, 2999, 2, 16, 256, 128),
