@@ -3,6 +3,7 @@ before touching the GPU (no compute calls here)."""
 import ctypes
 import os
 import re
+import subprocess
 
 import paper_2502_14477_amd as esa
 
@@ -96,3 +97,50 @@ def test_argument_validation_returns_codes_without_a_gpu():
     assert L.esa_attend_reencoded(*re_args(16, 4096.0)) == -3
     assert L.esa_attend_reencoded(*re_args(1 << 30, -1.0)) == -1
     assert L.esa_attend_reencoded_workspace_bytes(512, 32, 8, 128, 1, 1, 2048) > 2 * 512 * 4096 * 2 + 2 * 2560 * 1024 * 2
+
+
+C_CLIENT = r"""
+#include <stdio.h>
+#include <string.h>
+#include <dlfcn.h>
+#include "esa.h"
+int main(int argc, char** argv) {
+  void* h = dlopen(argv[1], RTLD_NOW);
+  if (!h) { printf("dlopen: %s\n", dlerror()); return 2; }
+  int (*version)(void) = (int (*)(void))dlsym(h, "esa_version");
+  int (*seg)(int64_t, int64_t, int64_t, int64_t*, int64_t*) =
+      (int (*)(int64_t, int64_t, int64_t, int64_t*, int64_t*))dlsym(h, "esa_segments");
+  const char* (*last)(void) = (const char* (*)(void))dlsym(h, "esa_last_error");
+  size_t (*ws)(int64_t, int, int) = (size_t (*)(int64_t, int, int))dlsym(h, "esa_select_topk_workspace_bytes");
+  if (!version || !seg || !last || !ws) return 3;
+  int64_t i_end = -1, l_start = -1;
+  if (seg(130560, 128, 2048, &i_end, &l_start) != ESA_OK) return 4;
+  if (seg(-1, 0, 0, &i_end, &l_start) != ESA_EINVAL || !strstr(last(), "esa_segments")) return 5;
+  seg(130560, 128, 2048, &i_end, &l_start);
+  printf("%d %lld %lld %zu %d %d\n", version(), (long long)i_end, (long long)l_start, ws(128384, 2048, 1),
+         ESA_SPLIT_ALGORITHM1, ESA_BF16);
+  return 0;
+}
+"""
+
+
+def test_header_is_plain_c_and_the_library_serves_a_c_client(tmp_path):
+    """include/esa.h compiles as C99 and as C++ with no other header of this repository, and a C
+    program that knows nothing but the header can load the library and call its host-side entry points."""
+    inc = os.path.join(ROOT, "include")
+    for lang, std in (("c", "-std=c99"), ("c++", "-std=c++11")):
+        r = subprocess.run(["gcc", "-x", lang, std, "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                            os.path.join(inc, "esa.h")], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+    src = tmp_path / "client.c"
+    src.write_text(C_CLIENT)
+    exe = tmp_path / "client"
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", inc, str(src), "-o", str(exe), "-ldl"],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe), esa.lib_path()], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+    version, i_end, l_start, ws_bytes, split, bf16 = (int(t) for t in r.stdout.split())
+    assert version == esa.esa_version() and (i_end, l_start) == (128, 128512)
+    assert ws_bytes == esa.lib.esa_select_topk_workspace_bytes(128384, 2048, 1)
+    assert split == esa.ESA_SPLIT_ALGORITHM1 and bf16 == esa.ESA_BF16
