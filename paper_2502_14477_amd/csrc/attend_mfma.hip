@@ -16,10 +16,18 @@
 //     O^T [d x queries]   += V_tile^T [d x keys] . P^T [keys x queries]   A = V^T (LDS), B = P (registers)
 // so the softmax over keys is an in-lane reduction over accumulator registers plus one exchange
 // between the two half-waves, and S^T's accumulator layout is directly P^T's B-operand layout once
-// the reduction slots of the second product are assigned to keys accordingly (the V^T tile is
-// stored in LDS in that key order).  V is transposed on its way from global memory to LDS in
-// registers (4x4 blocks of bf16), K is copied as is.  Tiles of 64 keys are double buffered in LDS:
-// one barrier per tile, the next tile's global loads in flight during the current tile's math.
+// the reduction slots of the second product are assigned to keys accordingly.
+//
+// Tiles of 64 keys are double buffered in LDS and arrive there without passing through registers:
+// global_load_lds_dwordx4 deposits 16 bytes per lane at consecutive LDS addresses, so one wave
+// instruction brings four 256-byte rows, and which 16 bytes of its row a lane fetches is chosen
+// such that the rows land XOR-swizzled (K: 16-byte pieces by row % 16, V: 64-byte chunks by
+// row % 4), which makes the fragment reads below free of bank conflicts without padding.  K
+// fragments are plain 16-byte reads.  V stays row-major [key][dim]; its transposed fragments (eight
+// keys of one head dimension per lane) come from ds_read_b64_tr_b16, which hands lane i of a 16-lane
+// group element i%4 of the 8 bytes addressed by lanes 4e + i/4 (e = 0..3): sixteen lanes that point
+// at a 4-key x 16-dim block receive one dimension each, four consecutive keys of it.
+// One barrier per tile; the next tile's loads are in flight during the current tile's math.
 #include "attend_mfma.h"
 #include "keyspace.h"
 
@@ -31,18 +39,18 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef short i16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void global_void;
 
 constexpr int kD = 128;             // head size
 constexpr int kKT = 64;             // virtual keys per tile
 constexpr int kRows = 256;          // query rows per workgroup
 constexpr int kWaves = 8;
 constexpr int kThreads = 64 * kWaves;
-constexpr int kKLd = kD + 8;        // LDS row stride of the K tile in elements (272 B: conflict-free 16-byte reads)
-constexpr int kVLd = kKT + 8;       // LDS row stride of the V^T tile in elements (144 B)
-constexpr int kKElems = kKT * kKLd;
-constexpr int kVElems = kD * kVLd;
-constexpr int kStageElems = kKElems + kVElems;
-constexpr int kLdsBytes = 2 * kStageElems * 2;
+constexpr int kTileElems = kKT * kD;    // one K or V tile in LDS: 64 rows of 256 bytes, unpadded, swizzled
 constexpr int kMaxSplits = 8;
 constexpr int kMaxSlots = 2 * kMaxSplits;   // two-call form: local slices, then selected slices
 constexpr int kMinLc = 16;          // shorter chunks go to the plain kernel
@@ -99,8 +107,12 @@ __device__ __forceinline__ RowRef row_ref(const AttendArgs& a, uint32_t j) {
 }
 
 __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  bf16_t* lds = (bf16_t*)lds_raw;     // [2 stages][K tile | V^T tile]
+  // Two stages of a K tile and a V tile.  Separate arrays, so that the compiler can tell a load into one
+  // stage from a fragment read of the other and does not wait for the load first.
+  __shared__ __attribute__((aligned(1024))) bf16_t k_st0[kTileElems];
+  __shared__ __attribute__((aligned(1024))) bf16_t k_st1[kTileElems];
+  __shared__ __attribute__((aligned(1024))) bf16_t v_st0[kTileElems];
+  __shared__ __attribute__((aligned(1024))) bf16_t v_st1[kTileElems];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, hi = lane >> 5;
 
@@ -150,37 +162,24 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     for (int v = 0; v < 16; ++v) o[md][v] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  // ---- staging of one tile: global -> registers -> LDS.  K: two 16-byte pieces per thread
-  // (key = piece / 16, 16 pieces per 256-byte row).  V: one 4-key x 4-dim block per thread.
-  uint4 k0, k1;
-  uint2 v0, v1, v2, v3;
-  const int kp0 = tid, kp1 = tid + kThreads;
-  const int vb = (lane >> 3) + 8 * (wave & 3);                     // which 4 head-dims (0..31)
-  const int ap = (lane & 7) + 8 * (wave >> 2);                     // 4-key group as stored in LDS (0..15)
-  const int sw = ap & 3;
-  const int ag = (ap & ~3) | (sw == 1 ? 2 : sw == 2 ? 1 : sw);     // 4-key group in key order
-  // Per-thread row numbers inside a tile.  A tile whose 64 keys lie inside one segment of the
-  // virtual sequence (the usual case) is addressed as uniform base + row * stride + column, the base
-  // and stride chosen on the scalar unit; tiles that straddle a segment boundary or the end of
-  // the slice take the general per-row path.
-  const uint32_t kr0 = kp0 >> 4, kr1 = kp1 >> 4, kcol0 = (kp0 & 15) * 16, kcol1 = (kp1 & 15) * 16;
-  const uint32_t vr = 4 * ag, vcol = vb * 8;
-  auto k_src = [&](uint32_t j0, int piece) -> const uint4* {
-    uint32_t j = j0 + (piece >> 4);
-    j = j < k_end ? j : k_end - 1;                                 // the tail repeats a key; masked below
-    const RowRef rr = row_ref(a, j);
-    return (const uint4*)((rr.in_sel ? ksl : kc) + rr.off + (piece & 15) * 16);
+  // ---- staging of one tile: global -> LDS directly, 16 bytes per lane.  A wave instruction fills 1 KB =
+  // four rows; wave w brings row groups w and w + 8 of K and of V.  Lane l fills 16-byte slot l%16 of row
+  // l/16 of its group; the piece of the global row it fetches for that slot undoes the swizzle:
+  // K slot s of row R holds piece s ^ (R%16); V slot s of row R holds piece s%4 of chunk (s/4) ^ (R%4).
+  const uint32_t st_row = 4 * wave + (lane >> 4);                  // first of this lane's two rows (second: + 32)
+  const uint32_t st_slot = lane & 15;
+  const uint32_t kcol = (st_slot ^ (st_row & 15)) * 16;            // byte column of the piece fetched for K
+  const uint32_t vcol = ((((st_slot >> 2) ^ (st_row & 3)) << 2) | (st_slot & 3)) * 16;   // ... for V
+  auto dma16 = [&](const char* src, bf16_t* dst_wave_uniform) {
+    __builtin_amdgcn_global_load_lds((global_void*)src, (lds_void*)dst_wave_uniform, 16, 0, 0);
   };
-  auto v_src = [&](uint32_t j0, int kk) -> const uint2* {
-    uint32_t j = j0 + 4 * ag + kk;
-    j = j < k_end ? j : k_end - 1;
-    const RowRef rr = row_ref(a, j);
-    return (const uint2*)((rr.in_sel ? vsl : vc) + rr.off + vb * 8);
-  };
-  auto tile_load = [&](uint32_t j0) {
+  auto tile_load = [&](uint32_t j0, bf16_t* kt, bf16_t* vt) {
     const uint32_t sel_end = a.i_end + a.n_sel;
     int seg = -1;                                                  // 0: cache rows, 1: gathered rows
     uint32_t row0 = 0;
+    // A tile whose 64 keys lie inside one segment of the virtual sequence (the usual case) is addressed
+    // as uniform base + row * stride + column; tiles that straddle a segment boundary or the end of the
+    // slice take the general per-row path.
     if (j0 + kKT <= a.i_end) {
       seg = 0;
       row0 = j0;
@@ -191,69 +190,40 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
       seg = 0;
       row0 = j0 - sel_end + a.l_start;
     }
+    bf16_t* kd0 = kt + wave * 512;                                 // 1 KB per row group
+    bf16_t* kd1 = kt + (wave + 8) * 512;
+    bf16_t* vd0 = vt + wave * 512;
+    bf16_t* vd1 = vt + (wave + 8) * 512;
     if (seg >= 0) {
       const uint32_t stride = seg ? a.sel_bytes : a.tok_bytes;
       const char* kb = (seg ? ksl : kc) + (uint64_t)row0 * stride;
       const char* vbase = (seg ? vsl : vc) + (uint64_t)row0 * stride;
-      k0 = *(const uint4*)(kb + (kr0 * stride + kcol0));
-      k1 = *(const uint4*)(kb + (kr1 * stride + kcol1));
-      v0 = *(const uint2*)(vbase + (vr * stride + vcol));
-      v1 = *(const uint2*)(vbase + ((vr + 1) * stride + vcol));
-      v2 = *(const uint2*)(vbase + ((vr + 2) * stride + vcol));
-      v3 = *(const uint2*)(vbase + ((vr + 3) * stride + vcol));
+      dma16(kb + (st_row * stride + kcol), kd0);
+      dma16(kb + ((st_row + 32) * stride + kcol), kd1);
+      dma16(vbase + (st_row * stride + vcol), vd0);
+      dma16(vbase + ((st_row + 32) * stride + vcol), vd1);
     } else {
-      k0 = *k_src(j0, kp0);
-      k1 = *k_src(j0, kp1);
-      v0 = *v_src(j0, 0);
-      v1 = *v_src(j0, 1);
-      v2 = *v_src(j0, 2);
-      v3 = *v_src(j0, 3);
+      uint32_t ja = j0 + st_row, jb = j0 + st_row + 32;
+      ja = ja < k_end ? ja : k_end - 1;                            // the tail repeats a key; masked below
+      jb = jb < k_end ? jb : k_end - 1;
+      const RowRef ra = row_ref(a, ja), rb = row_ref(a, jb);
+      dma16((ra.in_sel ? ksl : kc) + ra.off + kcol, kd0);
+      dma16((rb.in_sel ? ksl : kc) + rb.off + kcol, kd1);
+      dma16((ra.in_sel ? vsl : vc) + ra.off + vcol, vd0);
+      dma16((rb.in_sel ? vsl : vc) + rb.off + vcol, vd1);
     }
   };
-#define ESA_TILE_LOAD(j0) tile_load(j0)
-  auto tile_store = [&](int stage) {
-    bf16_t* kt = lds + stage * kStageElems;
-    bf16_t* vt = kt + kKElems;
-    *(uint4*)&kt[(kp0 >> 4) * kKLd + (kp0 & 15) * 8] = k0;
-    *(uint4*)&kt[(kp1 >> 4) * kKLd + (kp1 & 15) * 8] = k1;
-    // 4 keys x 4 dims -> 4 dims x 4 keys
-    uint2 d0, d1, d2, d3;
-    d0.x = (v0.x & 0xFFFFu) | (v1.x << 16);
-    d0.y = (v2.x & 0xFFFFu) | (v3.x << 16);
-    d1.x = (v0.x >> 16) | (v1.x & 0xFFFF0000u);
-    d1.y = (v2.x >> 16) | (v3.x & 0xFFFF0000u);
-    d2.x = (v0.y & 0xFFFFu) | (v1.y << 16);
-    d2.y = (v2.y & 0xFFFFu) | (v3.y << 16);
-    d3.x = (v0.y >> 16) | (v1.y & 0xFFFF0000u);
-    d3.y = (v2.y >> 16) | (v3.y & 0xFFFF0000u);
-    bf16_t* dst = &vt[(4 * vb) * kVLd + 4 * ap];
-    *(uint2*)(dst) = d0;
-    *(uint2*)(dst + kVLd) = d1;
-    *(uint2*)(dst + 2 * kVLd) = d2;
-    *(uint2*)(dst + 3 * kVLd) = d3;
-  };
+  // Every load of this wave has landed in LDS (vmcnt = 0; the other counters are left alone).
+  auto loads_landed = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };
 
-  // The first tile's loads go out before the query fragments' so that the two round trips overlap.
-  if (tile_begin < tile_end) ESA_TILE_LOAD(tile_begin * kKT);
-  {
-    const bf16_t* qp = a.q + (int64_t)b * a.q_bs + ((int64_t)cc * a.h + head) * kD + hi * 8;
-#pragma unroll
-    for (int ks16 = 0; ks16 < kD / 16; ++ks16) qf[ks16] = *(const bf16x8*)(qp + ks16 * 16);
-    // Pin the fragments as arrived values here: otherwise every use inside the tile loop carries a
-    // wait on the vector-memory counter, which would also wait for the tile loads just issued.
-#pragma unroll
-    for (int ks16 = 0; ks16 < kD / 16; ++ks16) asm volatile("" : "+v"(qf[ks16]));
-  }
-  if (tile_begin < tile_end) tile_store(0);
-  for (uint32_t t = tile_begin; t < tile_end; ++t) {
+  // Lane constants of the transposed V reads: inside its 16-lane group lane i points at key i/4 of a
+  // four-key block and at four consecutive dims 4*(i%4).. of the group's sixteen.
+  const int tr_key = (lane & 15) >> 2;
+  const int tr_dim = ((lane >> 4) & 1) * 16 + 4 * (lane & 3);
+
+  // ---- one tile: S^T = K Q^T, online softmax, O^T += V^T P^T
+  auto tile_math = [&](uint32_t t, const bf16_t* kt, const bf16_t* vt) {
     const uint32_t j0 = t * kKT;
-    const int stage = (int)((t - tile_begin) & 1);
-    __syncthreads();                     // tile t is in LDS; every wave is done with tile t-1
-    if (t + 1 < tile_end) ESA_TILE_LOAD(j0 + kKT);
-    const bf16_t* kt = lds + stage * kStageElems;
-    const bf16_t* vt = kt + kKElems;
-
-    // ---- S^T = K Q^T
     f32x16 s[2];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
@@ -263,7 +233,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     for (int ks16 = 0; ks16 < kD / 16; ++ks16)
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt) {
-        const bf16x8 ka = *(const bf16x8*)&kt[(32 * mt + r) * kKLd + 16 * ks16 + 8 * hi];
+        const bf16x8 ka = *(const bf16x8*)&kt[(32 * mt + r) * kD + (((2 * ks16 + hi) ^ (r & 15)) << 3)];
         s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks16], s[mt], 0, 0, 0);
       }
 
@@ -309,6 +279,8 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[md][v] *= corr;
     }
+    // Accumulator register v = 8*(e/4) + e%4 (+ 4*hi in the key number): fragment kp of P^T is S^T's
+    // registers 8*(kp%2) .. + 7 of key tile kp/2, i.e. keys 16*kp + 4*hi + {0..3} and 16*kp + 8 + 4*hi + {0..3}.
     bf16x8 pf[4];
 #pragma unroll
     for (int kp = 0; kp < 4; ++kp) {
@@ -321,18 +293,44 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
       pf[kp] = *(bf16x8*)&w;
     }
 
-    // ---- O^T += V^T P^T
+    // ---- O^T += V^T P^T.  Row key of the V tile holds chunk c (dims 32c .. 32c+31) at chunk slot c ^ (key%4).
 #pragma unroll
     for (int kp = 0; kp < 4; ++kp)
 #pragma unroll
       for (int md = 0; md < 4; ++md) {
-        const bf16x8 va = *(const bf16x8*)&vt[(32 * md + r) * kVLd + 16 * kp + 8 * hi];
-        o[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[kp], o[md], 0, 0, 0);
+        const bf16_t* vp = vt + (16 * kp + 4 * hi + tr_key) * kD + ((md ^ tr_key) << 5) + tr_dim;
+        const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)vp);             // keys 16kp + 4hi + 0..3
+        const i16x4 up = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vp + 8 * kD));  // keys 16kp + 8 + 4hi + 0..3
+        const i16x8 both = __builtin_shufflevector(lo, up, 0, 1, 2, 3, 4, 5, 6, 7);
+        o[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[kp], o[md], 0, 0, 0);
       }
+  };
 
-    if (t + 1 < tile_end) tile_store(stage ^ 1);
+  // The first tile's loads go out before the query fragments' so that the two round trips overlap.
+  if (tile_begin < tile_end) tile_load(tile_begin * kKT, k_st0, v_st0);
+  {
+    const bf16_t* qp = a.q + (int64_t)b * a.q_bs + ((int64_t)cc * a.h + head) * kD + hi * 8;
+#pragma unroll
+    for (int ks16 = 0; ks16 < kD / 16; ++ks16) qf[ks16] = *(const bf16x8*)(qp + ks16 * 16);
+    // Pin the fragments as arrived values here: otherwise every use inside the tile loop carries a
+    // wait on the vector-memory counter.
+#pragma unroll
+    for (int ks16 = 0; ks16 < kD / 16; ++ks16) asm volatile("" : "+v"(qf[ks16]));
   }
-#undef ESA_TILE_LOAD
+  // Two tiles per trip so that every stage is named statically.  At each barrier tile t is in LDS and
+  // every wave is done with tile t-1, whose stage the loads issued right after the barrier overwrite.
+  for (uint32_t t = tile_begin; t < tile_end; t += 2) {
+    loads_landed();
+    __syncthreads();
+    if (t + 1 < tile_end) tile_load((t + 1) * kKT, k_st1, v_st1);
+    tile_math(t, k_st0, v_st0);
+    if (t + 1 < tile_end) {
+      loads_landed();
+      __syncthreads();
+      if (t + 2 < tile_end) tile_load((t + 2) * kKT, k_st0, v_st0);
+      tile_math(t + 1, k_st1, v_st1);
+    }
+  }
 
   // ---- results.  Accumulator register v of tile md is head-dim 32*md + 8*(v/4) + 4*hi + v%4 of this
   // lane's query, so a lane holds its whole output row in 8-byte pieces.  The rows are normalised,
@@ -345,7 +343,8 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   __syncthreads();                       // every wave is done with the last tile
   {
-    uint16_t* ot = (uint16_t*)lds + (wave * 32 + r) * kKLd;
+    // wave w's 32 rows of 256 bytes go to half (w%2) of stage array w/2, 16-byte slots swizzled by row % 16
+    uint16_t* ot = (uint16_t*)(wave < 2 ? k_st0 : wave < 4 ? k_st1 : wave < 6 ? v_st0 : v_st1) + ((wave & 1) * 32 + r) * kD;
 #pragma unroll
     for (int md = 0; md < 4; ++md)
 #pragma unroll
@@ -358,7 +357,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
           w.x = pack_f16x2(o[md][4 * vg + 0] * inv, o[md][4 * vg + 1] * inv);
           w.y = pack_f16x2(o[md][4 * vg + 2] * inv, o[md][4 * vg + 3] * inv);
         }
-        *(uint2*)(ot + 32 * md + 8 * vg + 4 * hi) = w;
+        *(uint2*)(ot + (((4 * md + vg) ^ (r & 15)) << 3) + 4 * hi) = w;
       }
   }
   __syncthreads();
@@ -378,7 +377,8 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   for (int i = 0; i < 8; ++i) {
     const int rw = 4 * i + (lane >> 4), piece = lane & 15;
     if (c_wave + rw < a.l_c) {
-      const uint4 w = *(const uint4*)((const uint16_t*)lds + (wave * 32 + rw) * kKLd + piece * 8);
+      const uint16_t* ob = (const uint16_t*)(wave < 2 ? k_st0 : wave < 4 ? k_st1 : wave < 6 ? v_st0 : v_st1);
+      const uint4 w = *(const uint4*)(ob + ((wave & 1) * 32 + rw) * kD + ((piece ^ (rw & 15)) << 3));
       *(uint4*)(dst + (int64_t)rw * a.h * kD + piece * 8) = w;
     }
   }
@@ -546,14 +546,7 @@ int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h
     a.part_ml = (float*)((char*)ws + align_up(rows * kD * sizeof(uint16_t), 256));
   }
   a.n_slot = n_slot;
-  static bool lds_limit_raised = false;          // idempotent; a race only repeats the call
-  if (!lds_limit_raised) {
-    hipError_t e = hipFuncSetAttribute((const void*)attend_mfma_bf16, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kLdsBytes);
-    if (e != hipSuccess) return hip_failed(e, "hipFuncSetAttribute(attend_mfma_bf16)");
-    lds_limit_raised = true;
-  }
-  auto launch = [&](int64_t n_wg) { attend_mfma_bf16<<<dim3((unsigned)n_wg), kThreads, kLdsBytes, st>>>(a); };
+  auto launch = [&](int64_t n_wg) { attend_mfma_bf16<<<dim3((unsigned)n_wg), kThreads, 0, st>>>(a); };
   const int64_t rows = (int64_t)l_c * h;
   const dim3 merge_grid((unsigned)((rows + 7) / 8), batch);
   if (part == kAttendAll) {
