@@ -171,10 +171,20 @@ int launch_attend(int part, int split, const void* q, int l_c, int h, int h_kv, 
   // per part and merges.
   const bool two_parts = part != kAttendAll && split == ESA_SPLIT_ALGORITHM1;
   if (part == kAttendLocal && !two_parts) return ESA_OK;
+  if (two_parts && attend_decode_supported(l_c, h, h_kv, d, dtype) && (int64_t)batch * l_c <= 65535 &&
+      attend_decode_covers_parts(t0 - sg.l_start + l_c, l_c, h_kv, batch)) {
+    // decode-sized chunk in Algorithm 1's two parts: both calls must agree on this kernel, so nothing
+    // that only one of them knows (the number of selected tokens, its pointers' alignment) may veto it
+    if (!attend_mfma_aligned(q, k_cache, v_cache, k_sel, v_sel, out, tok_stride, q_bs, cache_bs, sel_bs, out_bs))
+      ESA_FAIL(ESA_EINVAL, "esa_attend (two calls, Algorithm 1 grouping): pointers and strides must be 16-byte aligned");
+    return launch_attend_decode(part == kAttendLocal ? 1 : 2, q, l_c, h, h_kv, k_cache, v_cache, tok_stride, t0, sg.i_end,
+                                sg.l_start, k_sel, v_sel, n_sel, sel_idx, idx_bs, scale, out, lse, batch, q_bs, cache_bs,
+                                sel_bs, out_bs, ws, ws_bytes, st);
+  }
   if (!two_parts && attend_decode_supported(l_c, h, h_kv, d, dtype) && (int64_t)batch * l_c <= 65535 &&
       attend_decode_covers(n_fixed + l_c, l_c, h_kv, batch) &&
       attend_mfma_aligned(q, k_cache, v_cache, k_sel, v_sel, out, tok_stride, q_bs, cache_bs, sel_bs, out_bs)) {
-    return launch_attend_decode(q, l_c, h, h_kv, k_cache, v_cache, tok_stride, t0, sg.i_end, sg.l_start, k_sel, v_sel,
+    return launch_attend_decode(0, q, l_c, h, h_kv, k_cache, v_cache, tok_stride, t0, sg.i_end, sg.l_start, k_sel, v_sel,
                                 n_sel, sel_idx, idx_bs, scale, out, lse, batch, q_bs, cache_bs, sel_bs, out_bs, ws, ws_bytes, st);
   }
   const int64_t esz = (dtype == ESA_F32) ? 4 : 2;

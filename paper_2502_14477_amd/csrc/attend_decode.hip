@@ -46,7 +46,9 @@ struct DecodeArgs {
   KeySpace ks;
   int64_t n_fixed;
   float scale_log2e;
-  int l_c, h_kv, splits, slice;
+  int l_c, h_kv, splits, slice;   // splits: slots per output row (the row stride of the partial results)
+  int slot0;         // this launch fills slots slot0 + blockIdx.x
+  int with_chunk;    // 1: the virtual sequence ends with the current tokens (causal); 0: every key is visible
   float* part_o;     // [rows][splits][128]
   float* part_ml;    // [rows][splits][2]  (max of the base-2 logits, sum of 2^(logit - max))
   int64_t q_bs, cache_bs_bytes, sel_bs_bytes, idx_bs;
@@ -59,7 +61,7 @@ __global__ __launch_bounds__(256) void attend_decode_bf16(DecodeArgs a) {
   __shared__ float head_m[G], head_l[G];
 
   const int tid = threadIdx.x, sub = tid % kLanesPerKey, group = tid / kLanesPerKey;
-  const int split = blockIdx.x, g = blockIdx.y, c = blockIdx.z % a.l_c, b = blockIdx.z / a.l_c;
+  const int split = a.slot0 + blockIdx.x, g = blockIdx.y, c = blockIdx.z % a.l_c, b = blockIdx.z / a.l_c;
   const int h = a.h_kv * G;
   KeySpace ks = a.ks;
   ks.k_cache += (int64_t)b * a.cache_bs_bytes;
@@ -70,8 +72,8 @@ __global__ __launch_bounds__(256) void attend_decode_bf16(DecodeArgs a) {
     ks.k_sel += (int64_t)b * a.sel_bs_bytes;
     ks.v_sel += (int64_t)b * a.sel_bs_bytes;
   }
-  const int64_t n_keys = a.n_fixed + c + 1;
-  const int64_t j_lo = (int64_t)split * a.slice;
+  const int64_t n_keys = a.n_fixed + (a.with_chunk ? c + 1 : 0);
+  const int64_t j_lo = (int64_t)blockIdx.x * a.slice;
   const int cnt = (int)(n_keys - j_lo < a.slice ? (n_keys - j_lo > 0 ? n_keys - j_lo : 0) : a.slice);
   const int64_t row0 = ((int64_t)b * a.l_c + c) * h + (int64_t)g * G;   // first of this workgroup's G output rows
   const int64_t head_off = (int64_t)g * kD * 2 + sub * 16;              // byte offset inside a token row
@@ -218,13 +220,13 @@ __global__ __launch_bounds__(256) void attend_decode_bf16(DecodeArgs a) {
 // are known after one round trip; the four waves then each add a quarter of the slices' partial
 // outputs (independent loads, two output dims per lane) and the quarters meet in LDS.
 __global__ __launch_bounds__(256) void attend_decode_merge(const float* __restrict__ part_o,
-                                                           const float* __restrict__ part_ml, int splits, int l_c,
-                                                           int h, bf16_t* __restrict__ out, int64_t out_bs,
+                                                           const float* __restrict__ part_ml, int splits, int stride,
+                                                           int l_c, int h, bf16_t* __restrict__ out, int64_t out_bs,
                                                            float* __restrict__ lse) {
   __shared__ float red[4][kD];
   const int64_t row = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const float2* ml = (const float2*)(part_ml + row * splits * 2);
+  const float2* ml = (const float2*)(part_ml + row * stride * 2);   // slots [0, splits) of `stride` are in use
   float2 a0 = make_float2(-INFINITY, 0.f), a1 = make_float2(-INFINITY, 0.f);
   if (lane < splits) a0 = ml[lane];
   if (lane + 64 < splits) a1 = ml[lane + 64];
@@ -233,7 +235,7 @@ __global__ __launch_bounds__(256) void attend_decode_merge(const float* __restri
   const float w1 = a1.y > 0.f ? exp2f(a1.x - m) : 0.f;
   const float l = wave_sum(__fmaf_rn(w0, a0.y, w1 * a1.y));
   float o0 = 0.f, o1 = 0.f;
-  const float* po = part_o + row * splits * kD + lane * 2;
+  const float* po = part_o + row * stride * kD + lane * 2;
 #pragma unroll 4
   for (int s = wave; s < splits; s += 4) {
     const float w = s < 64 ? __shfl(w0, s, 64) : __shfl(w1, s - 64, 64);
@@ -293,14 +295,40 @@ size_t attend_decode_workspace_bytes(int l_c, int h, int batch) {
   return align_up(rows * kMaxSplits * kD * sizeof(float), 256) + align_up(rows * kMaxSplits * 2 * sizeof(float), 256);
 }
 
-int launch_attend_decode(const void* q, int l_c, int h, int h_kv, const void* k_cache, const void* v_cache,
+bool attend_decode_covers_parts(int64_t n_local_max, int l_c, int h_kv, int batch) {
+  const Plan p = plan_for(n_local_max, l_c, h_kv, batch);
+  return p.splits > 0 && p.splits <= kMaxSplits / 2;
+}
+
+// part: 0 whole key sequence and merge; 1 the local keys [ L | C ] into the first slots; 2 the global
+// keys [ I | M_k ] (every key visible) into the slots behind them, then the merge over both.  The two-part
+// form gives each part at most half of the slots and addresses rows with the full stride, so that the
+// first call needs to know nothing about the second.
+int launch_attend_decode(int part, const void* q, int l_c, int h, int h_kv, const void* k_cache, const void* v_cache,
                          int64_t tok_stride, int64_t t0, int64_t i_end, int64_t l_start, const void* k_sel,
                          const void* v_sel, int n_sel, const int32_t* sel_idx, int64_t idx_bs, float scale, void* out,
                          float* lse, int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws,
                          size_t ws_bytes, hipStream_t st) {
-  const int64_t n_fixed = i_end + n_sel + (t0 - l_start);
-  const Plan p = plan_for(n_fixed + l_c, l_c, h_kv, batch);
-  if (p.splits <= 0) ESA_FAIL(ESA_EUNSUPPORTED, "attend_decode: %lld keys exceed the kernel's range", (long long)(n_fixed + l_c));
+  const int64_t n_local = t0 - l_start, n_global = i_end + n_sel;
+  const int64_t n_fixed = part == 0 ? n_global + n_local : part == 1 ? n_local : n_global;
+  const int with_chunk = part != 2;
+  const int64_t n_part = n_fixed + (with_chunk ? l_c : 0);
+  Plan p;
+  p.splits = 0;
+  p.slice = 64;
+  if (n_part > 0) p = plan_for(n_part, l_c, h_kv, batch);
+  int slot0 = 0, used = p.splits, stride = p.splits;
+  if (part != 0) {
+    const Plan pl = plan_for(n_local + l_c, l_c, h_kv, batch);
+    if (pl.splits <= 0 || pl.splits > kMaxSplits / 2 || (part == 2 && n_part > 0 && (p.splits <= 0 || p.splits > kMaxSplits / 2)))
+      ESA_FAIL(ESA_EUNSUPPORTED, "attend_decode (two parts): a part of %lld keys exceeds the kernel's range",
+               (long long)(part == 1 ? n_local + l_c : n_fixed));
+    stride = kMaxSplits;
+    slot0 = part == 1 ? 0 : pl.splits;
+    used = part == 1 ? pl.splits : pl.splits + p.splits;
+  } else if (p.splits <= 0) {
+    ESA_FAIL(ESA_EUNSUPPORTED, "attend_decode: %lld keys exceed the kernel's range", (long long)(n_fixed + l_c));
+  }
   if (ws_bytes < attend_decode_workspace_bytes(l_c, h, batch)) ESA_FAIL(ESA_EWORKSPACE, "attend_decode: workspace too small");
   const size_t rows = (size_t)batch * l_c * h;
   DecodeArgs a;
@@ -313,30 +341,36 @@ int launch_attend_decode(const void* q, int l_c, int h, int h_kv, const void* k_
   a.idx_bs = idx_bs;
   a.ks.tok_bytes = tok_stride * 2;
   a.ks.sel_bytes = (int64_t)h_kv * kD * 2;
-  a.ks.i_end = i_end;
-  a.ks.n_sel = n_sel;
+  a.ks.i_end = part == 1 ? 0 : i_end;
+  a.ks.n_sel = part == 1 ? 0 : n_sel;
   a.ks.l_start = l_start;
   a.n_fixed = n_fixed;
+  a.with_chunk = with_chunk;
+  a.slot0 = slot0;
   a.scale_log2e = scale * 1.4426950408889634f;
   a.l_c = l_c;
   a.h_kv = h_kv;
-  a.splits = p.splits;
+  a.splits = stride;
   a.slice = p.slice;
   a.part_o = (float*)ws;
   a.part_ml = (float*)((char*)ws + align_up(rows * kMaxSplits * kD * sizeof(float), 256));
   a.q_bs = q_bs;
   a.cache_bs_bytes = cache_bs * 2;
   a.sel_bs_bytes = sel_bs * 2;
-  const dim3 grid(p.splits, h_kv, batch * l_c);
-  switch (h / h_kv) {
-    case 1: attend_decode_bf16<1><<<grid, 256, 0, st>>>(a); break;
-    case 2: attend_decode_bf16<2><<<grid, 256, 0, st>>>(a); break;
-    case 4: attend_decode_bf16<4><<<grid, 256, 0, st>>>(a); break;
-    default: attend_decode_bf16<8><<<grid, 256, 0, st>>>(a); break;
+  if (p.splits > 0) {
+    const dim3 grid(p.splits, h_kv, batch * l_c);
+    switch (h / h_kv) {
+      case 1: attend_decode_bf16<1><<<grid, 256, 0, st>>>(a); break;
+      case 2: attend_decode_bf16<2><<<grid, 256, 0, st>>>(a); break;
+      case 4: attend_decode_bf16<4><<<grid, 256, 0, st>>>(a); break;
+      default: attend_decode_bf16<8><<<grid, 256, 0, st>>>(a); break;
+    }
+    ESA_LAUNCH_CHECK("attend_decode_bf16");
   }
-  ESA_LAUNCH_CHECK("attend_decode_bf16");
-  attend_decode_merge<<<(unsigned)rows, 256, 0, st>>>(a.part_o, a.part_ml, p.splits, l_c, h, (bf16_t*)out, out_bs, lse);
-  ESA_LAUNCH_CHECK("attend_decode_merge");
+  if (part != 1) {
+    attend_decode_merge<<<(unsigned)rows, 256, 0, st>>>(a.part_o, a.part_ml, used, stride, l_c, h, (bf16_t*)out, out_bs, lse);
+    ESA_LAUNCH_CHECK("attend_decode_merge");
+  }
   return ESA_OK;
 }
 

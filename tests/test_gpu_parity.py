@@ -451,7 +451,10 @@ def test_rope_matches_the_fp64_definition_rounded_once(esa, dtype, B, n_tok, hea
     ("bf16", 1, 8, 2, 128, 0, 64, 16, 300, 0),          # first chunk: nothing but C
     ("f32", 1, 4, 2, 64, 900, 100, 8, 64, 31),          # plain kernel, one launch per part
     ("f32", 2, 4, 2, 64, 900, 7, 8, 64, 31),
-    ("bf16", 1, 8, 2, 128, 2999, 1, 16, 256, 128)])     # decode shape
+    ("bf16", 1, 8, 2, 128, 2999, 1, 16, 256, 128),      # decode shape: split-key kernel, one launch per part
+    ("bf16", 3, 32, 8, 128, 6000, 2, 128, 2048, 2048),  # decode, batched, Llama shape
+    ("bf16", 2, 8, 2, 128, 40, 3, 16, 300, 0),          # decode in an early chunk: the global part is I alone
+    ("bf16", 1, 8, 8, 128, 0, 5, 16, 300, 0)])          # decode at the very start: no global keys at all
 def test_attend_reencoded_from_unencoded_queries_and_caches(esa, dtype, B, H, H_kv, d, t0, l_C, l_I, l_L, n_sel):
     """Section 3.2 inside the library: un-encoded q, K cache and gathered keys in, esa_attend_reencoded
     encodes and attends; the oracle applies the section's positions in fp64 without intermediate rounding."""
