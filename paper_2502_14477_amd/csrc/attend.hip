@@ -283,6 +283,13 @@ int launch_attend_reencoded(const void* q, int l_c, int h, int h_kv, int d, cons
   if (attend_mfma_supported(l_c, h, h_kv, d, dtype) &&
       !attend_mfma_aligned(q_loc, k_cache, v_cache, k_sel, v_sel, out, tok_stride, qw_bs, cache_bs, sel_bs, out_bs))
     ESA_FAIL(ESA_EINVAL, "esa_attend_reencoded: pointers and strides must be 16-byte aligned for this shape");
+  // decode-sized chunks on the split-key kernel: the global part must fit its half of the slices too
+  // (checked here so that nothing is enqueued when it does not)
+  if (attend_decode_supported(l_c, h, h_kv, d, dtype) && (int64_t)batch * l_c <= 65535 &&
+      attend_decode_covers_parts(n_loc + l_c, l_c, h_kv, batch) && sg.i_end + n_sel > 0 &&
+      !attend_decode_covers_parts(sg.i_end + n_sel, l_c, h_kv, batch))
+    ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend_reencoded: %lld initial and selected keys exceed the decode kernel's range",
+             (long long)(sg.i_end + n_sel));
 
   RopeJob jobs[4];
   jobs[0] = RopeJob{q, q_loc, l_c, q_row, q_row, q_bs, qw_bs, (double)n_loc, 1.0, h, 1};     // local queries, in order
