@@ -300,6 +300,10 @@ int launch_attend_reencoded(const void* q, int l_c, int h, int h_kv, int d, cons
   jobs[3] = RopeJob{v_rows, v_loc, rows, tok_stride, kv_row, cache_bs, kvw_bs, 0.0, 0.0, h_kv, 0};   // their values
   int rc = launch_rope_jobs(jobs, 4, d, base, dtype, batch, st);
   if (rc != ESA_OK) return rc;
+  if (attend_mfma_supported(l_c, h, h_kv, d, dtype))     // both parts in one launch of the matrix-core kernel
+    return launch_attend_mfma_two_views(q_loc, q_glob, qw_bs, l_c, h, h_kv, d, k_loc, v_loc, n_loc, kvw_bs, k_cache, v_cache,
+                                        tok_stride, cache_bs, sg.i_end, k_sel, v_sel, n_sel, sel_bs, scale, out, lse, batch,
+                                        out_bs, ws, own, st);
   rc = launch_attend(kAttendLocal, ESA_SPLIT_ALGORITHM1, q_loc, l_c, h, h_kv, d, k_loc, v_loc, kv_row, n_loc, 0, n_loc,
                      nullptr, nullptr, 0, nullptr, 0, scale, nullptr, nullptr, dtype, batch, qw_bs, kvw_bs, 0, 0, ws, own, st);
   if (rc != ESA_OK) return rc;

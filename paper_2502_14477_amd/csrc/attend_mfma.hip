@@ -58,26 +58,39 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazy = 8.f;        // the softmax reference lags the running maximum by at most 2^8
 constexpr float kLn2 = 0.6931471805599453f;
 
-struct AttendArgs {
+// What one slice of a launch attends to: a query tensor and a virtual key sequence
+// [ cache rows [0, i_end) | n_sel gathered rows | cache rows [l_start, ..) ].  A launch carries two views;
+// the usual one uses view 0 only, the re-encoded attention of Section 3.2 gives the local keys (their own
+// encoding of queries and keys, causal) to view 0 and the initial and selected keys (queries at the fixed
+// position, every key visible) to view 1, so that both parts run in one launch.
+struct KeyView {
   const bf16_t* q;
+  const char* k_cache;
+  const char* v_cache;
+  int64_t q_bs, cache_bs_bytes;
+  uint32_t tok_bytes;               // row stride of the cache
+  uint32_t i_end, n_sel, l_start;
+  uint32_t n_fixed;                 // keys every row sees
+  int with_chunk;     // 1: the virtual sequence ends with the current chunk (causal); 0: every key is visible to every row
+  int n_split;        // slices of this view (view 0's slices come first)
+  int slot0;          // partial results of slice s go to slot slot0 + s
+};
+
+struct AttendArgs {
+  KeyView view[2];
   bf16_t* out;
   float* lse;
   uint16_t* part_o;   // [batch][n_slot][l_c][h][128] fp16 partial outputs, each normalised by its own sum
   float* part_ml;     // [batch][n_slot][l_c][h][2]   running maximum (log2 domain) and sum
-  const char* k_cache;
-  const char* v_cache;
   const char* k_sel;
   const char* v_sel;
-  uint32_t tok_bytes, sel_bytes;    // row strides of the cache / the gathered buffers
-  uint32_t i_end, n_sel, l_start;
-  int l_c, h, h_kv, group, qpt, n_qt, n_split, batch;
+  uint32_t sel_bytes;               // row stride of the gathered buffers
+  int l_c, h, h_kv, group, qpt, n_qt, batch;
   int xcd_mapping;                  // 1: (batch, KV head) pairs are a multiple of 8
-  uint32_t n_fixed;
-  int with_chunk;     // 1: the virtual sequence ends with the current chunk (causal); 0: every key is visible to every row
-  int slot0, n_slot;  // partial results go to slots [slot0, slot0 + n_split) of n_slot
-  int to_slots;       // 1: write partial results even when n_split == 1
+  int n_slot;         // slots per row in the partial-result arrays
+  int to_slots;       // 1: write partial results even when the launch has a single slice
   float c2;           // scale * log2(e)
-  int64_t q_bs, out_bs, cache_bs_bytes, sel_bs_bytes;
+  int64_t out_bs, sel_bs_bytes;
 };
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
@@ -96,13 +109,13 @@ struct RowRef {
   bool in_sel;
   uint64_t off;
 };
-__device__ __forceinline__ RowRef row_ref(const AttendArgs& a, uint32_t j) {
-  const bool in_i = j < a.i_end;
-  const bool in_s = !in_i && (j < a.i_end + a.n_sel);
-  const uint32_t row = in_i ? j : (in_s ? j - a.i_end : j - a.i_end - a.n_sel + a.l_start);
+__device__ __forceinline__ RowRef row_ref(const KeyView& V, uint32_t sel_bytes, uint32_t j) {
+  const bool in_i = j < V.i_end;
+  const bool in_s = !in_i && (j < V.i_end + V.n_sel);
+  const uint32_t row = in_i ? j : (in_s ? j - V.i_end : j - V.i_end - V.n_sel + V.l_start);
   RowRef r;
   r.in_sel = in_s;
-  r.off = (uint64_t)row * (in_s ? a.sel_bytes : a.tok_bytes);
+  r.off = (uint64_t)row * (in_s ? sel_bytes : V.tok_bytes);
   return r;
 }
 
@@ -117,7 +130,8 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, hi = lane >> 5;
 
   // ---- which (batch element, KV head, row tile, key slice) is this workgroup
-  const int per_pair = a.n_qt * a.n_split;
+  const int n_slices = a.view[0].n_split + a.view[1].n_split;
+  const int per_pair = a.n_qt * n_slices;
   int pair, inner;
   if (a.xcd_mapping) {                 // consecutive workgroup ids go to consecutive XCDs
     const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
@@ -128,20 +142,40 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     inner = blockIdx.x % per_pair;
   }
   const int b = pair / a.h_kv, g = pair % a.h_kv;
-  const int qt = inner % a.n_qt, split = inner / a.n_qt;
+  const int qt = inner % a.n_qt, slice = inner / a.n_qt;
+  const int vw = slice >= a.view[0].n_split ? 1 : 0;             // which view this slice belongs to
+  // field-wise select (not an indexed load): every kernel argument is then fetched in the first round trip
+  KeyView V;
+  {
+    const KeyView &v0 = a.view[0], &v1 = a.view[1];
+    V.q = vw ? v1.q : v0.q;
+    V.k_cache = vw ? v1.k_cache : v0.k_cache;
+    V.v_cache = vw ? v1.v_cache : v0.v_cache;
+    V.q_bs = vw ? v1.q_bs : v0.q_bs;
+    V.cache_bs_bytes = vw ? v1.cache_bs_bytes : v0.cache_bs_bytes;
+    V.tok_bytes = vw ? v1.tok_bytes : v0.tok_bytes;
+    V.i_end = vw ? v1.i_end : v0.i_end;
+    V.n_sel = vw ? v1.n_sel : v0.n_sel;
+    V.l_start = vw ? v1.l_start : v0.l_start;
+    V.n_fixed = vw ? v1.n_fixed : v0.n_fixed;
+    V.with_chunk = vw ? v1.with_chunk : v0.with_chunk;
+    V.n_split = vw ? v1.n_split : v0.n_split;
+    V.slot0 = vw ? v1.slot0 : v0.slot0;
+  }
+  const int split = slice - (vw ? a.view[0].n_split : 0);        // slice number inside the view
 
-  const char* kc = a.k_cache + (int64_t)b * a.cache_bs_bytes + (int64_t)g * kD * 2;
-  const char* vc = a.v_cache + (int64_t)b * a.cache_bs_bytes + (int64_t)g * kD * 2;
-  const char* ksl = a.k_sel + (a.n_sel ? (int64_t)b * a.sel_bs_bytes + (int64_t)g * kD * 2 : 0);
-  const char* vsl = a.v_sel + (a.n_sel ? (int64_t)b * a.sel_bs_bytes + (int64_t)g * kD * 2 : 0);
+  const char* kc = V.k_cache + (int64_t)b * V.cache_bs_bytes + (int64_t)g * kD * 2;
+  const char* vc = V.v_cache + (int64_t)b * V.cache_bs_bytes + (int64_t)g * kD * 2;
+  const char* ksl = a.k_sel + (V.n_sel ? (int64_t)b * a.sel_bs_bytes + (int64_t)g * kD * 2 : 0);
+  const char* vsl = a.v_sel + (V.n_sel ? (int64_t)b * a.sel_bs_bytes + (int64_t)g * kD * 2 : 0);
 
   // ---- this workgroup's rows and key slice
   const int q0 = qt * a.qpt;
   const int c_last = (q0 + a.qpt < a.l_c ? q0 + a.qpt : a.l_c) - 1;
-  const uint32_t n_vis = a.n_fixed + (a.with_chunk ? c_last + 1 : 0);   // keys the tile's last token sees
+  const uint32_t n_vis = V.n_fixed + (V.with_chunk ? c_last + 1 : 0);   // keys the tile's last token sees
   const uint32_t n_tiles = (n_vis + kKT - 1) / kKT;
-  const uint32_t tile_begin = (uint32_t)((uint64_t)n_tiles * split / a.n_split);
-  const uint32_t tile_end = (uint32_t)((uint64_t)n_tiles * (split + 1) / a.n_split);
+  const uint32_t tile_begin = (uint32_t)((uint64_t)n_tiles * split / V.n_split);
+  const uint32_t tile_end = (uint32_t)((uint64_t)n_tiles * (split + 1) / V.n_split);
   const uint32_t k_end = tile_end * kKT < n_vis ? tile_end * kKT : n_vis;
 
   // ---- this wave's 32 rows: one head, 32 consecutive current tokens, one per lane (both half-waves)
@@ -150,7 +184,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   const int c = q0 + (wave % tph) * 32 + r;
   const bool c_ok = c < a.l_c;
   const int cc = c_ok ? c : a.l_c - 1;                             // rows past the chunk repeat its last token
-  const uint32_t vis = a.n_fixed + (a.with_chunk ? cc + 1 : 0);
+  const uint32_t vis = V.n_fixed + (V.with_chunk ? cc + 1 : 0);
   const uint32_t lim = vis < k_end ? vis : k_end;                  // first virtual key this lane's query may NOT see
   const uint32_t lim_lo = __shfl(lim, 0, 64);                      // smallest limit in the wave (r = 0)
   bf16x8 qf[kD / 16];                                              // loaded below, behind the first tile's loads
@@ -174,28 +208,28 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     __builtin_amdgcn_global_load_lds((global_void*)src, (lds_void*)dst_wave_uniform, 16, 0, 0);
   };
   auto tile_load = [&](uint32_t j0, bf16_t* kt, bf16_t* vt) {
-    const uint32_t sel_end = a.i_end + a.n_sel;
+    const uint32_t sel_end = V.i_end + V.n_sel;
     int seg = -1;                                                  // 0: cache rows, 1: gathered rows
     uint32_t row0 = 0;
     // A tile whose 64 keys lie inside one segment of the virtual sequence (the usual case) is addressed
     // as uniform base + row * stride + column; tiles that straddle a segment boundary or the end of the
     // slice take the general per-row path.
-    if (j0 + kKT <= a.i_end) {
+    if (j0 + kKT <= V.i_end) {
       seg = 0;
       row0 = j0;
-    } else if (j0 >= a.i_end && j0 + kKT <= sel_end) {
+    } else if (j0 >= V.i_end && j0 + kKT <= sel_end) {
       seg = 1;
-      row0 = j0 - a.i_end;
+      row0 = j0 - V.i_end;
     } else if (j0 >= sel_end && j0 + kKT <= k_end) {
       seg = 0;
-      row0 = j0 - sel_end + a.l_start;
+      row0 = j0 - sel_end + V.l_start;
     }
     bf16_t* kd0 = kt + wave * 512;                                 // 1 KB per row group
     bf16_t* kd1 = kt + (wave + 8) * 512;
     bf16_t* vd0 = vt + wave * 512;
     bf16_t* vd1 = vt + (wave + 8) * 512;
     if (seg >= 0) {
-      const uint32_t stride = seg ? a.sel_bytes : a.tok_bytes;
+      const uint32_t stride = seg ? a.sel_bytes : V.tok_bytes;
       const char* kb = (seg ? ksl : kc) + (uint64_t)row0 * stride;
       const char* vbase = (seg ? vsl : vc) + (uint64_t)row0 * stride;
       dma16(kb + (st_row * stride + kcol), kd0);
@@ -206,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
       uint32_t ja = j0 + st_row, jb = j0 + st_row + 32;
       ja = ja < k_end ? ja : k_end - 1;                            // the tail repeats a key; masked below
       jb = jb < k_end ? jb : k_end - 1;
-      const RowRef ra = row_ref(a, ja), rb = row_ref(a, jb);
+      const RowRef ra = row_ref(V, a.sel_bytes, ja), rb = row_ref(V, a.sel_bytes, jb);
       dma16((ra.in_sel ? ksl : kc) + ra.off + kcol, kd0);
       dma16((rb.in_sel ? ksl : kc) + rb.off + kcol, kd1);
       dma16((ra.in_sel ? vsl : vc) + ra.off + vcol, vd0);
@@ -309,7 +343,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   // The first tile's loads go out before the query fragments' so that the two round trips overlap.
   if (tile_begin < tile_end) tile_load(tile_begin * kKT, k_st0, v_st0);
   {
-    const bf16_t* qp = a.q + (int64_t)b * a.q_bs + ((int64_t)cc * a.h + head) * kD + hi * 8;
+    const bf16_t* qp = V.q + (int64_t)b * V.q_bs + ((int64_t)cc * a.h + head) * kD + hi * 8;
 #pragma unroll
     for (int ks16 = 0; ks16 < kD / 16; ++ks16) qf[ks16] = *(const bf16x8*)(qp + ks16 * 16);
     // Pin the fragments as arrived values here: otherwise every use inside the tile loop carries a
@@ -339,7 +373,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   // results of a key slice are fp16 (normalised values are bounded by max |v|, and fp16's 11-bit
   // significand keeps their rounding well below that of the bf16 output) next to fp32 (maximum, sum).
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  const bool final_out = a.n_split == 1 && !a.to_slots;
+  const bool final_out = n_slices == 1 && !a.to_slots;
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   __syncthreads();                       // every wave is done with the last tile
   {
@@ -366,7 +400,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   if (final_out) {
     dst = (uint16_t*)a.out + (int64_t)b * a.out_bs + ((int64_t)c_wave * a.h + head) * kD;
   } else {
-    const int64_t prow0 = ((int64_t)(b * a.n_slot + a.slot0 + split) * a.l_c) * a.h;
+    const int64_t prow0 = ((int64_t)(b * a.n_slot + V.slot0 + split) * a.l_c) * a.h;
     dst = a.part_o + (prow0 + (int64_t)c_wave * a.h + head) * kD;
     if (hi == 0 && c_ok) {
       float2 ml = {m_run, l_tot};
@@ -490,6 +524,35 @@ size_t attend_mfma_workspace_bytes(int l_c, int h, int h_kv, int d, int batch) {
   return slots_bytes(n_slot, l_c, h, batch);
 }
 
+namespace {
+
+KeyView make_view(const void* q, int64_t q_bs, const void* k_cache, const void* v_cache, int64_t tok_stride,
+                  int64_t cache_bs, int64_t i_end, int n_sel, int64_t l_start, int64_t n_fixed, int with_chunk,
+                  int n_split, int slot0) {
+  KeyView v;
+  v.q = (const bf16_t*)q;
+  v.k_cache = (const char*)k_cache;
+  v.v_cache = (const char*)v_cache;
+  v.q_bs = q_bs;
+  v.cache_bs_bytes = cache_bs * 2;
+  v.tok_bytes = (uint32_t)(tok_stride * 2);
+  v.i_end = (uint32_t)i_end;
+  v.n_sel = (uint32_t)n_sel;
+  v.l_start = (uint32_t)l_start;
+  v.n_fixed = (uint32_t)n_fixed;
+  v.with_chunk = with_chunk;
+  v.n_split = n_split;
+  v.slot0 = slot0;
+  return v;
+}
+
+int clamp_splits(int ns, int64_t keys_of_first_tile) {
+  const int64_t tiles = (keys_of_first_tile + kKT - 1) / kKT;
+  return (int)(ns > tiles ? (tiles > 0 ? tiles : 1) : ns);
+}
+
+}  // namespace
+
 int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache,
                        const void* v_cache, int64_t tok_stride, int64_t t0, int64_t i_end, int64_t l_start,
                        const void* k_sel, const void* v_sel, int n_sel, float scale, void* out, float* lse, int batch,
@@ -499,14 +562,10 @@ int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h
   if (t0 + l_c >= ((int64_t)1 << 31) || tok_stride * 2 >= ((int64_t)1 << 32))
     ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend: positions beyond 2^31 are not supported by the matrix-core kernel");
   AttendArgs a;
-  a.q = (const bf16_t*)q;
   a.out = (bf16_t*)out;
   a.lse = lse;
-  a.k_cache = (const char*)k_cache;
-  a.v_cache = (const char*)v_cache;
   a.k_sel = (const char*)k_sel;
   a.v_sel = (const char*)v_sel;
-  a.tok_bytes = (uint32_t)(tok_stride * 2);
   a.sel_bytes = (uint32_t)((int64_t)h_kv * d * 2);
   a.l_c = l_c;
   a.h = h;
@@ -516,24 +575,18 @@ int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h
   a.n_qt = (l_c + a.qpt - 1) / a.qpt;
   a.batch = batch;
   a.c2 = scale * kLog2e;
-  a.q_bs = q_bs;
   a.out_bs = out_bs;
-  a.cache_bs_bytes = cache_bs * 2;
   a.sel_bs_bytes = sel_bs * 2;
   a.xcd_mapping = ((batch * h_kv) % 8 == 0) ? 1 : 0;
 
   const SplitPlan plan = plan_splits(l_c, a.group, h_kv, batch);
   const int first_rows = l_c < a.qpt ? l_c : a.qpt;
-  auto clamp = [](int ns, int64_t keys_of_first_tile) {
-    const int64_t tiles = (keys_of_first_tile + kKT - 1) / kKT;
-    return (int)(ns > tiles ? (tiles > 0 ? tiles : 1) : ns);
-  };
   // slices in use: one call -> `all`; two calls -> local in slots [0, ns_local), selected in [plan.local, +ns_sel)
-  const int ns_all = clamp(plan.all, i_end + n_sel + (t0 - l_start) + first_rows);
+  const int ns_all = clamp_splits(plan.all, i_end + n_sel + (t0 - l_start) + first_rows);
   // split == ESA_SPLIT_ALGORITHM1 moves the initial tokens from the early part to the late one
   const int64_t i_early = split == ESA_SPLIT_ALGORITHM1 ? 0 : i_end, i_late = i_end - i_early;
-  const int ns_local = clamp(plan.local, i_early + (t0 - l_start) + first_rows);
-  const int ns_sel = i_late + n_sel > 0 ? clamp(plan.sel, i_late + n_sel) : 0;
+  const int ns_local = clamp_splits(plan.local, i_early + (t0 - l_start) + first_rows);
+  const int ns_sel = i_late + n_sel > 0 ? clamp_splits(plan.sel, i_late + n_sel) : 0;
   const int n_slot = part == kAttendAll ? ns_all : plan.local + plan.sel;
 
   a.part_o = nullptr;
@@ -546,41 +599,27 @@ int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h
     a.part_ml = (float*)((char*)ws + align_up(rows * kD * sizeof(uint16_t), 256));
   }
   a.n_slot = n_slot;
+  a.view[1] = make_view(q, q_bs, k_cache, v_cache, tok_stride, cache_bs, 0, 0, 0, 0, 0, 0, 0);   // unused
   auto launch = [&](int64_t n_wg) { attend_mfma_bf16<<<dim3((unsigned)n_wg), kThreads, 0, st>>>(a); };
   const int64_t rows = (int64_t)l_c * h;
   const dim3 merge_grid((unsigned)((rows + 7) / 8), batch);
   if (part == kAttendAll) {
-    a.i_end = (uint32_t)i_end;
-    a.n_sel = (uint32_t)n_sel;
-    a.l_start = (uint32_t)l_start;
-    a.n_fixed = (uint32_t)(i_end + n_sel + (t0 - l_start));
-    a.with_chunk = 1;
-    a.n_split = ns_all;
-    a.slot0 = 0;
+    a.view[0] = make_view(q, q_bs, k_cache, v_cache, tok_stride, cache_bs, i_end, n_sel, l_start,
+                          i_end + n_sel + (t0 - l_start), 1, ns_all, 0);
     a.to_slots = 0;
     launch((int64_t)batch * h_kv * a.n_qt * ns_all);
     if (ns_all > 1)
       esa_attend_merge<<<merge_grid, 256, 0, st>>>(a.part_o, a.part_ml, n_slot, ns_all, 0, 0, rows, (bf16_t*)out, lse,
                                                    out_bs, rows);
   } else if (part == kAttendLocal) {
-    a.i_end = (uint32_t)i_early;
-    a.n_sel = 0;
-    a.l_start = (uint32_t)l_start;
-    a.n_fixed = (uint32_t)(i_early + (t0 - l_start));
-    a.with_chunk = 1;
-    a.n_split = ns_local;
-    a.slot0 = 0;
+    a.view[0] = make_view(q, q_bs, k_cache, v_cache, tok_stride, cache_bs, i_early, 0, l_start,
+                          i_early + (t0 - l_start), 1, ns_local, 0);
     a.to_slots = 1;
     launch((int64_t)batch * h_kv * a.n_qt * ns_local);
   } else {
     if (ns_sel > 0) {
-      a.i_end = (uint32_t)i_late;
-      a.n_sel = (uint32_t)n_sel;
-      a.l_start = 0;
-      a.n_fixed = (uint32_t)(i_late + n_sel);
-      a.with_chunk = 0;
-      a.n_split = ns_sel;
-      a.slot0 = plan.local;
+      a.view[0] = make_view(q, q_bs, k_cache, v_cache, tok_stride, cache_bs, i_late, n_sel, 0, i_late + n_sel, 0, ns_sel,
+                            plan.local);
       a.to_slots = 1;
       launch((int64_t)batch * h_kv * a.n_qt * ns_sel);
     }
@@ -588,6 +627,69 @@ int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h
                                                  (bf16_t*)out, lse, out_bs, rows);
   }
   ESA_LAUNCH_CHECK("attend_mfma");
+  return ESA_OK;
+}
+
+// Section 3.2 in one launch: the local keys (dense re-encoded copy, rows [0, n_loc + l_c), causal) with the
+// queries q_loc, and the initial and selected keys (caller's un-encoded cache and gathered rows, every key
+// visible) with the queries q_glob; the slices of both share the launch and the merge.
+int launch_attend_mfma_two_views(const void* q_loc, const void* q_glob, int64_t qw_bs, int l_c, int h, int h_kv, int d,
+                                 const void* k_loc, const void* v_loc, int64_t n_loc, int64_t loc_bs,
+                                 const void* k_cache, const void* v_cache, int64_t tok_stride, int64_t cache_bs,
+                                 int64_t i_end, const void* k_sel, const void* v_sel, int n_sel, int64_t sel_bs,
+                                 float scale, void* out, float* lse, int batch, int64_t out_bs, void* ws, size_t ws_bytes,
+                                 hipStream_t st) {
+  if (!(scale > 0.f)) ESA_FAIL(ESA_EINVAL, "esa_attend: scale must be positive");
+  if (n_loc + l_c >= ((int64_t)1 << 31) || tok_stride * 2 >= ((int64_t)1 << 32))
+    ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend: positions beyond 2^31 are not supported by the matrix-core kernel");
+  AttendArgs a;
+  a.out = (bf16_t*)out;
+  a.lse = lse;
+  a.k_sel = (const char*)k_sel;
+  a.v_sel = (const char*)v_sel;
+  a.sel_bytes = (uint32_t)((int64_t)h_kv * d * 2);
+  a.l_c = l_c;
+  a.h = h;
+  a.h_kv = h_kv;
+  a.group = h / h_kv;
+  a.qpt = kRows / a.group;
+  a.n_qt = (l_c + a.qpt - 1) / a.qpt;
+  a.batch = batch;
+  a.c2 = scale * kLog2e;
+  a.out_bs = out_bs;
+  a.sel_bs_bytes = sel_bs * 2;
+  a.xcd_mapping = ((batch * h_kv) % 8 == 0) ? 1 : 0;
+  // the planned number of slices is shared out in proportion to the two parts' lengths, at least one each
+  const SplitPlan plan = plan_splits(l_c, a.group, h_kv, batch);
+  const int first_rows = l_c < a.qpt ? l_c : a.qpt;
+  const int64_t keys_a = n_loc + (l_c + 1) / 2, keys_b = i_end + n_sel;
+  int ns_b = keys_b > 0 ? (int)((plan.all * keys_b + (keys_a + keys_b) / 2) / (keys_a + keys_b)) : 0;
+  if (keys_b > 0 && ns_b < 1) ns_b = 1;
+  int ns_a = plan.all - ns_b < 1 ? 1 : plan.all - ns_b;
+  ns_a = clamp_splits(ns_a, n_loc + first_rows);
+  if (ns_b > 0) ns_b = clamp_splits(ns_b, keys_b);
+  const int n_slot = ns_a + ns_b;
+  const size_t need = slots_bytes(n_slot, l_c, h, batch);
+  a.part_o = nullptr;
+  a.part_ml = nullptr;
+  if (n_slot > 1) {
+    if (!ws || ws_bytes < need) ESA_FAIL(ESA_EWORKSPACE, "esa_attend: workspace needs %zu bytes", need);
+    const size_t rows = (size_t)batch * n_slot * l_c * h;
+    a.part_o = (uint16_t*)ws;
+    a.part_ml = (float*)((char*)ws + align_up(rows * kD * sizeof(uint16_t), 256));
+  }
+  a.n_slot = n_slot;
+  a.to_slots = 0;
+  a.view[0] = make_view(q_loc, qw_bs, k_loc, v_loc, (int64_t)h_kv * d, loc_bs, 0, 0, 0, n_loc, 1, ns_a, 0);
+  a.view[1] = make_view(q_glob, qw_bs, k_cache, v_cache, tok_stride, cache_bs, i_end, n_sel, 0, keys_b, 0, ns_b, ns_a);
+  attend_mfma_bf16<<<dim3((unsigned)((int64_t)batch * h_kv * a.n_qt * n_slot)), kThreads, 0, st>>>(a);
+  const int64_t rows = (int64_t)l_c * h;
+  if (n_slot > 1) {
+    const dim3 merge_grid((unsigned)((rows + 7) / 8), batch);
+    esa_attend_merge<<<merge_grid, 256, 0, st>>>(a.part_o, a.part_ml, n_slot, n_slot, 0, 0, rows, (bf16_t*)out, lse, out_bs,
+                                                 rows);
+  }
+  ESA_LAUNCH_CHECK("attend_mfma (two views)");
   return ESA_OK;
 }
 
