@@ -418,7 +418,9 @@ def test_attend_with_the_position_encoding_of_section_3_2(esa, dtype, H, H_kv, d
     ("bf16", 1, 512, 32, 128, 2048.0, 1.0, 0),       # local queries behind a window of 2048
     ("bf16", 2, 96, 8, 128, 4096.0, 0.0, 64),        # global queries at w; padded rows; batched
     ("bf16", 1, 33, 3, 64, 130000.0, 1.0, 8),        # large absolute positions
+    ("bf16", 2, 20, 2, 64, 5.0, 1.0, 3),             # odd row stride: the element-wise path
     ("f32", 2, 100, 4, 64, 7.5, 1.0, 0),
+    ("f32", 1, 9, 3, 128, 300.0, 1.0, 1),
     ("f32", 1, 5, 2, 32, 0.0, 0.0, 0)])              # position 0: identity
 def test_rope_matches_the_fp64_definition_rounded_once(esa, dtype, B, n_tok, heads, d, pos0, step, pad):
     say(f"rope dtype={dtype} B={B} n_tok={n_tok} heads={heads} d={d} pos0={pos0} step={step} pad={pad}")
