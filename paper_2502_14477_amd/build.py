@@ -23,6 +23,13 @@ FLAGS = [
 ]
 
 
+# per-file additions
+EXTRA_FLAGS = {
+    # plain v_max_f32 for the running maxima of the score sweeps (no NaN handling needed there)
+    "score.hip": ["-mno-amdgpu-ieee", "-fno-honor-nans"],
+}
+
+
 def _hipcc() -> str:
     for c in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
         if c and (os.path.isabs(c) and os.path.exists(c) or not os.path.isabs(c)):
@@ -44,7 +51,7 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
 
     def compile_one(src):
         obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-        out = _run([hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+        out = _run([hipcc, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj])
         if verbose and out.strip():
             print(out)
         return obj
