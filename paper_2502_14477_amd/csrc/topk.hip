@@ -2,9 +2,14 @@
 // order-preserving 32-bit keys, then an ordered compaction.
 //
 // Three histogram passes (11 + 11 + 10 bits, most significant first) pin down the key T of the
-// k-th largest score and how many scores equal to T are still needed; a counting pass and a
-// writing pass then emit the positions of every score above T plus the first `need` scores
-// equal to T, in ascending position order (equal scores: the lower position wins).
+// k-th largest score and how many scores equal to T are still needed; a writing pass then emits
+// the positions of every score above T plus the first `need` scores equal to T, in ascending
+// position order (equal scores: the lower position wins).  For its output offsets a workgroup of
+// the writing pass needs the number of selected scores in the workgroups before it; the third
+// histogram pass leaves that per workgroup in two pieces: the count of scores above the 22-bit
+// prefix fixed so far (selected whatever the last digit of T turns out to be), and the list of the
+// last digits of the scores that share the prefix (usually a handful), which the writing pass
+// compares with T's last digit once it knows it.
 // All cross-block traffic is integer atomics and plain stores, so the result is deterministic.
 // No workgroup ever waits for another: what one pass leaves in global memory (a 2048-bin
 // histogram, or the per-block counts) is re-read and scanned by EVERY workgroup of the next
@@ -23,10 +28,30 @@ constexpr int kBins = 2048;
 // Workspace of one batch row, in uint32 words.
 struct TopkLayout {
   static constexpr int hist = 0;                         // [3][kBins]
-  static constexpr int blk = 3 * kBins;                  // [2][nblk]: above-T and equal-T counts per block
+  static constexpr int blk = 3 * kBins;                  // [2][nblk]: per block, scores above the 22-bit prefix / sharing it
+  // then [nblk][cap] uint16: last digits of the scores sharing the prefix, cap = scores per block
 };
 
-__host__ __device__ inline int64_t topk_row_words(int64_t nblk) { return TopkLayout::blk + 2 * nblk; }
+struct TopkPlan {
+  int64_t sub;      // tiles of kTile scores per workgroup
+  int64_t nblk;     // workgroups per row
+};
+// One tile of kTile scores per workgroup while that keeps the chip busy (a call is latency-bound
+// then); with many rows a workgroup takes several tiles, so that the fixed work per workgroup
+// (prefix resolution, histogram flush) is paid by fewer of them.
+__host__ inline TopkPlan topk_plan(int64_t n, int batch) {
+  const int64_t tiles = (n + kTile - 1) / kTile;
+  int64_t sub = (tiles * batch + 767) / 768;
+  sub = sub < 1 ? 1 : (sub > 8 ? 8 : sub);
+  TopkPlan p;
+  p.sub = sub;
+  p.nblk = (tiles + sub - 1) / sub;
+  return p;
+}
+__host__ inline int64_t topk_row_words(const TopkPlan& p) {
+  const int64_t cand_words = (p.nblk * p.sub * kTile + 1) / 2;
+  return TopkLayout::blk + 2 * p.nblk + cand_words;
+}
 
 // Exclusive prefix sum of one value per thread over the block; *total gets the block sum.
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* total, uint32_t* wave_sums) {
@@ -158,11 +183,12 @@ __device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t bin)
 // PASS 0: bits 31..21, PASS 1: bits 20..10, PASS 2: bits 9..0.
 template <int PASS>
 __global__ __launch_bounds__(kThreads) void topk_hist(const float* __restrict__ score, int64_t n, int64_t score_bs,
-                                                      uint32_t* __restrict__ ws, int64_t row_words, uint32_t k,
-                                                      int sub) {
+                                                      uint32_t* __restrict__ ws, int64_t row_words, int nblk,
+                                                      uint32_t k, int sub) {
   __shared__ uint32_t h[kBins];
   __shared__ uint32_t wave_sums[kThreads / 64];
   __shared__ uint32_t result[2];
+  __shared__ uint32_t n_above, n_cand;             // PASS 2: this workgroup's scores above / sharing the prefix
   const float* row = score + (int64_t)blockIdx.y * score_bs;
   uint32_t* w = ws + (int64_t)blockIdx.y * row_words;
   const int64_t first = (int64_t)blockIdx.x * kTile * sub + (int64_t)threadIdx.x * kItems;
@@ -170,9 +196,15 @@ __global__ __launch_bounds__(kThreads) void topk_hist(const float* __restrict__ 
   bool ok[kItems];
   load_keys(row, n, first, key, ok);
   for (int i = threadIdx.x; i < kBins; i += kThreads) h[i] = 0u;
+  if (threadIdx.x == 0) {
+    n_above = 0u;
+    n_cand = 0u;
+  }
   uint32_t prefix, k_rem;
   resolve_prefix<PASS>(w, k, wave_sums, result, &prefix, &k_rem);
   __syncthreads();
+  uint16_t* cand = (uint16_t*)(w + TopkLayout::blk + 2 * nblk) + (int64_t)blockIdx.x * kTile * sub;
+  uint32_t above = 0;
   for (int st = 0; st < sub; ++st) {               // `sub` tiles of kTile scores, one histogram
     if (st > 0) load_keys(row, n, first + (int64_t)st * kTile, key, ok);
 #pragma unroll
@@ -182,45 +214,24 @@ __global__ __launch_bounds__(kThreads) void topk_hist(const float* __restrict__ 
       } else if (PASS == 1) {
         hist_add(h, ok[e] && (key[e] >> 21) == (prefix >> 21), (key[e] >> 10) & 2047u);
       } else {
-        hist_add(h, ok[e] && (key[e] >> 10) == (prefix >> 10), key[e] & 1023u);
+        const bool shares = ok[e] && (key[e] >> 10) == (prefix >> 10);
+        hist_add(h, shares, key[e] & 1023u);
+        above += (ok[e] && (key[e] >> 10) > (prefix >> 10)) ? 1u : 0u;
+        if (shares) cand[atomicAdd(&n_cand, 1u)] = (uint16_t)(key[e] & 1023u);   // order does not matter: they are counted
       }
     }
+  }
+  if (PASS == 2) {
+    above = (uint32_t)wave_sum((float)above);      // at most 64 * 8 * 8 per wave: exact in fp32
+    if ((threadIdx.x & 63) == 0) atomicAdd(&n_above, above);
   }
   __syncthreads();
   uint32_t* gh = w + TopkLayout::hist + PASS * kBins;
   for (int i = threadIdx.x; i < kBins; i += kThreads)
     if (h[i]) atomicAdd(&gh[i], h[i]);
-}
-
-// Per block: how many scores lie above T and how many equal T.
-__global__ __launch_bounds__(kThreads) void topk_count(const float* __restrict__ score, int64_t n, int64_t score_bs,
-                                                       uint32_t* __restrict__ ws, int64_t row_words, int nblk,
-                                                       uint32_t k, int sub) {
-  __shared__ uint32_t wave_sums[kThreads / 64];
-  __shared__ uint32_t result[2];
-  const float* row = score + (int64_t)blockIdx.y * score_bs;
-  uint32_t* w = ws + (int64_t)blockIdx.y * row_words;
-  const int64_t first = (int64_t)blockIdx.x * kTile * sub + (int64_t)threadIdx.x * kItems;
-  uint32_t key[kItems];
-  bool ok[kItems];
-  load_keys(row, n, first, key, ok);
-  uint32_t T, need;
-  resolve_prefix<3>(w, k, wave_sums, result, &T, &need);
-  uint32_t gt = 0, eq = 0;
-  for (int st = 0; st < sub; ++st) {
-    if (st > 0) load_keys(row, n, first + (int64_t)st * kTile, key, ok);
-#pragma unroll
-    for (int e = 0; e < kItems; ++e) {
-      gt += (ok[e] && key[e] > T) ? 1u : 0u;
-      eq += (ok[e] && key[e] == T) ? 1u : 0u;
-    }
-  }
-  uint32_t tot_gt, tot_eq;
-  block_excl_scan(gt, &tot_gt, wave_sums);
-  block_excl_scan(eq, &tot_eq, wave_sums);
-  if (threadIdx.x == 0) {
-    w[TopkLayout::blk + blockIdx.x] = tot_gt;
-    w[TopkLayout::blk + nblk + blockIdx.x] = tot_eq;
+  if (PASS == 2 && threadIdx.x == 0) {
+    w[TopkLayout::blk + blockIdx.x] = n_above;
+    w[TopkLayout::blk + nblk + blockIdx.x] = n_cand;
   }
 }
 
@@ -237,17 +248,49 @@ __global__ __launch_bounds__(kThreads) void topk_write(const float* __restrict__
   uint32_t key[kItems];
   bool ok[kItems];
   load_keys(row, n, first0, key, ok);
-  // scores above / equal to T in the blocks before this one
+  // What the third histogram pass left about the first workgroup this thread looks at: requested
+  // before T is resolved, so that the two round trips overlap.
+  constexpr int kPeek = 4;
+  const uint16_t* cand_all = (const uint16_t*)(w + TopkLayout::blk + 2 * nblk);
+  const int64_t cap = (int64_t)kTile * sub;
+  uint32_t c0 = 0, above0 = 0, peek[kPeek];
+#pragma unroll
+  for (int j = 0; j < kPeek; ++j) peek[j] = 0u;
+  if ((int)threadIdx.x < (int)blockIdx.x) {
+    above0 = w[TopkLayout::blk + threadIdx.x];
+    c0 = w[TopkLayout::blk + nblk + threadIdx.x];
+#pragma unroll
+    for (int j = 0; j < kPeek; ++j)
+      if ((uint32_t)j < c0) peek[j] = cand_all[threadIdx.x * cap + j];
+  }
+  uint32_t T, need;                                      // need: equal-to-T scores to take, lowest positions first
+  resolve_prefix<3>(w, k, wave_sums, result, &T, &need);
+  // scores above / equal to T in the workgroups before this one: those above the 22-bit prefix, plus
+  // those sharing it whose last digit is above / equal to T's
+  const uint32_t t_digit = T & 1023u;
   uint32_t my_gt = 0, my_eq = 0;
   for (int i = threadIdx.x; i < (int)blockIdx.x; i += kThreads) {
-    my_gt += w[TopkLayout::blk + i];
-    my_eq += w[TopkLayout::blk + nblk + i];
+    const bool head = i == (int)threadIdx.x;
+    const uint32_t c = head ? c0 : w[TopkLayout::blk + nblk + i];
+    my_gt += head ? above0 : w[TopkLayout::blk + i];
+    uint32_t j0 = 0;
+    if (head) {
+#pragma unroll
+      for (int j = 0; j < kPeek; ++j) {
+        my_gt += ((uint32_t)j < c && peek[j] > t_digit) ? 1u : 0u;
+        my_eq += ((uint32_t)j < c && peek[j] == t_digit) ? 1u : 0u;
+      }
+      j0 = kPeek;
+    }
+    for (uint32_t j = j0; j < c; ++j) {
+      const uint32_t dgt = cand_all[i * cap + j];
+      my_gt += dgt > t_digit ? 1u : 0u;
+      my_eq += dgt == t_digit ? 1u : 0u;
+    }
   }
   uint32_t off_gt, off_eq;
   block_excl_scan(my_gt, &off_gt, wave_sums);
   block_excl_scan(my_eq, &off_eq, wave_sums);
-  uint32_t T, need;                                      // need: equal-to-T scores to take, lowest positions first
-  resolve_prefix<3>(w, k, wave_sums, result, &T, &need);
   for (int st = 0; st < sub; ++st) {                     // tiles in position order; the offsets run on
     const int64_t first = first0 + (int64_t)st * kTile;
     if (st > 0) load_keys(row, n, first, key, ok);
@@ -287,8 +330,7 @@ __global__ void topk_all(int64_t n, int64_t base, int32_t* idx, int64_t idx_bs) 
 
 size_t topk_workspace_bytes(int64_t n, int k, int batch) {
   if (n <= 0 || k <= 0 || batch <= 0 || k >= n) return 256;
-  const int64_t nblk = (n + kTile - 1) / kTile;
-  return align_up((size_t)topk_row_words(nblk) * sizeof(uint32_t), 256) * (size_t)batch;
+  return align_up((size_t)topk_row_words(topk_plan(n, batch)) * sizeof(uint32_t), 256) * (size_t)batch;
 }
 
 int launch_topk(const float* score, int64_t n, int k, int64_t base, int32_t* idx, int batch, int64_t score_bs,
@@ -299,22 +341,16 @@ int launch_topk(const float* score, int64_t n, int k, int64_t base, int32_t* idx
     ESA_LAUNCH_CHECK("topk_all");
     return ESA_OK;
   }
-  // One tile of kTile scores per workgroup while that keeps the chip busy (a call is latency-bound
-  // then); with many rows a workgroup takes several tiles, so that the fixed work per workgroup
-  // (prefix resolution, histogram flush) is paid by fewer of them.
-  const int64_t tiles = (n + kTile - 1) / kTile;
-  int64_t sub = (tiles * batch + 767) / 768;
-  sub = sub < 1 ? 1 : (sub > 8 ? 8 : sub);
-  const int nblk = (int)((tiles + sub - 1) / sub);
-  const int64_t row_words = (int64_t)(align_up((size_t)topk_row_words(nblk) * sizeof(uint32_t), 256) / sizeof(uint32_t));
+  const TopkPlan plan = topk_plan(n, batch);
+  const int sub = (int)plan.sub, nblk = (int)plan.nblk;
+  const int64_t row_words = (int64_t)(align_up((size_t)topk_row_words(plan) * sizeof(uint32_t), 256) / sizeof(uint32_t));
   uint32_t* w = (uint32_t*)ws;
   const dim3 grid(nblk, batch);
   topk_init<<<dim3(3, batch), 1024, 0, st>>>(w, row_words);
-  topk_hist<0><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, (uint32_t)k, (int)sub);
-  topk_hist<1><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, (uint32_t)k, (int)sub);
-  topk_hist<2><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, (uint32_t)k, (int)sub);
-  topk_count<<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, (uint32_t)k, (int)sub);
-  topk_write<<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, base, idx, idx_bs, (uint32_t)k, (int)sub);
+  topk_hist<0><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, (uint32_t)k, sub);
+  topk_hist<1><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, (uint32_t)k, sub);
+  topk_hist<2><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, (uint32_t)k, sub);
+  topk_write<<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, base, idx, idx_bs, (uint32_t)k, sub);
   ESA_LAUNCH_CHECK("topk");
   return ESA_OK;
 }
