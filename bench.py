@@ -155,11 +155,12 @@ def main():
                 esa.esa_compress(rows(K, t0, t0 + l_c), W_k, out=rows(kc, t0, t0 + l_c))
                 esa.esa_attend_local(Q, K, V, t0, cfg.l_I, cfg.l_L)
 
-        if args.single_stream:
-            esa.esa_compress(rows(K, t0, t0 + l_c), W_k, out=rows(kc, t0, t0 + l_c))
-        elif args.fork_after == "start":
-            fork()
-        qc = esa.esa_compress(Q, W_q)
+        if args.single_stream:       # queries and keys of the chunk compressed by one call (Eq. 5 has both)
+            qc, _ = esa.esa_compress_qk(Q, W_q, rows(K, t0, t0 + l_c), W_k, out_k=rows(kc, t0, t0 + l_c))
+        else:
+            if args.fork_after == "start":
+                fork()
+            qc = esa.esa_compress(Q, W_q)
         if n_mid > cfg.k:
             score = esa.esa_score(qc, kc, i_end, l_start)
         else:
@@ -233,8 +234,7 @@ def main():
     ks_s, vs_s = esa.esa_gather_kv(K, V, idx_s)
 
     def call_compress():
-        esa.esa_compress(Q, W_q, out=qc_s)
-        esa.esa_compress(rows(K, t0, t0 + l_c), W_k, out=rows(kc, t0, t0 + l_c))
+        esa.esa_compress_qk(Q, W_q, rows(K, t0, t0 + l_c), W_k, out_q=qc_s, out_k=rows(kc, t0, t0 + l_c))
 
     single = {
         "compress": call_compress,
@@ -360,11 +360,13 @@ def whole_prompt(args, cfg, esa, torch, np):
             t1 = min(t0 + cfg.l_C, cfg.S)
             i_end, l_start = segment_bounds(t0, cfg.l_I, cfg.l_L)
             n_mid = l_start - i_end
-            esa.esa_compress(K[t0:t1], W_k, out=kc[t0:t1])
+            if n_mid > cfg.k:
+                qc, _ = esa.esa_compress_qk(Q[t0:t1], W_q, K[t0:t1], W_k, out_k=kc[t0:t1])
+            else:
+                esa.esa_compress(K[t0:t1], W_k, out=kc[t0:t1])
             ks = vs = None
             if n_mid > 0:
                 if n_mid > cfg.k:
-                    qc = esa.esa_compress(Q[t0:t1], W_q)
                     score = esa.esa_score(qc, kc, i_end, l_start)
                 else:   # k covers the middle: every middle token is selected, no scores needed
                     score = torch.zeros(n_mid, dtype=torch.float32, device="cuda")

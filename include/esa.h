@@ -83,6 +83,18 @@ ESA_API int esa_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx
                  int dtype, int batch, int64_t x_bs, int64_t out_bs, void* stream);
 
 /*
+ * Eq. 5 for the chunk's queries and keys in one call: exactly what two esa_compress calls compute
+ * (queries: xq, Wq, bias_q -> out_q; keys: xk, Wk, bias_k -> out_k, e.g. rows t0.. of the compressed-key
+ * cache), over the same n_tok tokens, d_c, weight layout, dtype and batch.  With packed weights and bf16
+ * the two products share one launch.  Arguments as esa_compress, per tensor.
+ */
+ESA_API int esa_compress_qk(const void* xq, int64_t d_in_q, int64_t ldxq, const void* Wq, const void* bias_q,
+                 void* out_q, int64_t ldoq, int64_t xq_bs, int64_t outq_bs,
+                 const void* xk, int64_t d_in_k, int64_t ldxk, const void* Wk, const void* bias_k,
+                 void* out_k, int64_t ldok, int64_t xk_bs, int64_t outk_bs,
+                 int64_t n_tok, int d_c, int w_layout, int dtype, int batch, void* stream);
+
+/*
  * Eq. 6 inside Eq. 4 — importance of every middle token m in [m_lo, m_hi):
  *   S[c,m] = qc[c] . kc_cache[m];  mu[c] = max_m S[c,m];  score[m-m_lo] = max_c (S[c,m] - mu[c]).
  * Consequently score <= 0, its maximum is exactly 0, and every current token's best middle

@@ -46,6 +46,9 @@ def _load() -> ctypes.CDLL:
     L.esa_pack_weights.restype = i32
     L.esa_pack_weights.argtypes = [vp, i64, i32, i32, vp, vp]
     L.esa_compress.argtypes = [vp, i64, i64, i64, vp, i32, vp, i32, vp, i64, i32, i32, i64, i64, vp]
+    L.esa_compress_qk.restype = i32
+    L.esa_compress_qk.argtypes = [vp, i64, i64, vp, vp, vp, i64, i64, i64, vp, i64, i64, vp, vp, vp, i64, i64, i64,
+                                  i64, i32, i32, i32, i32, vp]
     L.esa_score_workspace_bytes.restype = sz
     L.esa_score_workspace_bytes.argtypes = [i32, i64, i32, i32]
     L.esa_score.restype = i32
@@ -89,7 +92,7 @@ EXPORTS = ("esa_version", "esa_last_error", "esa_segments", "esa_pack_weights", 
            "esa_score", "esa_select_topk_workspace_bytes", "esa_select_topk", "esa_gather_kv",
            "esa_attend_workspace_bytes", "esa_attend", "esa_attend_local", "esa_attend_finish",
            "esa_attend_indexed_workspace_bytes", "esa_attend_indexed", "esa_rope",
-           "esa_attend_reencoded_workspace_bytes", "esa_attend_reencoded")
+           "esa_attend_reencoded_workspace_bytes", "esa_attend_reencoded", "esa_compress_qk")
 
 
 def _check(code: int) -> None:
@@ -206,6 +209,41 @@ def esa_compress(x: torch.Tensor, W, bias: Optional[torch.Tensor] = None,
     _check(lib.esa_compress(_ptr(xb), n_tok, d_in, xb.stride(1), _ptr(W), layout, _ptr(bias), d_c, _ptr(ob), ob.stride(1),
                             _dtype(x), B, xb.stride(0), ob.stride(0), _stream()))
     return ob if had_batch else ob[0]
+
+
+def esa_compress_qk(xq: torch.Tensor, Wq, xk: torch.Tensor, Wk, bias_q: Optional[torch.Tensor] = None,
+                    bias_k: Optional[torch.Tensor] = None, out_q: Optional[torch.Tensor] = None,
+                    out_k: Optional[torch.Tensor] = None):
+    """Both compressions of Eq. 5 in one call (shapes per tensor as esa_compress; `out_k` is typically the rows
+    t0.. of the compressed-key cache).  Returns (q', k')."""
+    packed = isinstance(Wq, PackedWeights)
+    assert packed == isinstance(Wk, PackedWeights), "both weight matrices in the same layout"
+    if packed:
+        layout, (dq, dc, wq), (dk, dck, wk) = ESA_W_PACKED, (Wq.d_in, Wq.d_c, Wq.data), (Wk.d_in, Wk.d_c, Wk.data)
+    else:
+        layout, (dq, dc, wq), (dk, dck, wk) = ESA_W_ROWMAJOR, (*Wq.shape, Wq), (*Wk.shape, Wk)
+    assert dc == dck and wq.is_contiguous() and wk.is_contiguous()
+
+    def prep(x, d_in, out):
+        if x.shape[-1] != d_in:
+            x = x.flatten(-2)
+        xb, had_batch = _batched(x, 2)
+        assert xb.shape[2] == d_in and xb.stride(2) == 1
+        if out is None:
+            ob = torch.empty((xb.shape[0], xb.shape[1], dc), dtype=x.dtype, device=x.device)
+        else:
+            ob, _ = _batched(out, 2)
+            assert ob.shape == (xb.shape[0], xb.shape[1], dc) and ob.stride(2) == 1 and ob.dtype == x.dtype
+        return xb, ob, had_batch
+
+    xqb, oq, had_batch = prep(xq, dq, out_q)
+    xkb, ok, _ = prep(xk, dk, out_k)
+    assert xqb.shape[:2] == xkb.shape[:2] and xqb.dtype == xkb.dtype
+    B, n_tok = xqb.shape[0], xqb.shape[1]
+    _check(lib.esa_compress_qk(_ptr(xqb), dq, xqb.stride(1), _ptr(wq), _ptr(bias_q), _ptr(oq), oq.stride(1), xqb.stride(0),
+                               oq.stride(0), _ptr(xkb), dk, xkb.stride(1), _ptr(wk), _ptr(bias_k), _ptr(ok), ok.stride(1),
+                               xkb.stride(0), ok.stride(0), n_tok, dc, layout, _dtype(xq), B, _stream()))
+    return (oq, ok) if had_batch else (oq[0], ok[0])
 
 
 def esa_score(qc: torch.Tensor, kc_cache: torch.Tensor, m_lo: int, m_hi: int, eps: int = 0,

@@ -142,27 +142,46 @@ __global__ __launch_bounds__(256) void compress_mfma_bf16(const bf16_t* __restri
 // v_mfma_f32_16x16x32_bf16: lane l supplies A[l%16][8*(l/16) .. +7] and B[8*(l/16) .. +7][l%16] and owns
 // C[4*(l/16) .. +3][l%16].  A rows are tokens, B columns are outputs, so a lane reads eight consecutive
 // reduction elements of one token row of x and of one output row of the packed weights.
+// One launch serves up to two inputs ("jobs") that share the token count, d_c and the batch: the chunk's
+// queries and keys are compressed side by side (Eq. 5 has both).  The job is the slow index of the grid
+// (blockIdx.y = job * col_tiles + column tile), so that all workgroups of job 0 are dispatched before
+// those of job 1 and a compute unit gets one of each rather than two of the long ones.
+struct CompressJob {
+  const bf16_t* x;
+  const bf16_t* Wt;
+  const bf16_t* bias;
+  bf16_t* out;
+  int64_t d_in, ldx, ldo, x_bs, out_bs;
+};
+
 template <int NW>
-__global__ __launch_bounds__(64 * NW) void compress_mfma_packed_bf16(const bf16_t* __restrict__ x, int64_t n_tok,
-                                                                 int64_t d_in, int64_t ldx,
-                                                                 const bf16_t* __restrict__ Wt,
-                                                                 const bf16_t* __restrict__ bias, int d_c,
-                                                                 bf16_t* __restrict__ out, int64_t ldo, int64_t x_bs,
-                                                                 int64_t out_bs) {
+__global__ __launch_bounds__(64 * NW) void compress_mfma_packed_bf16(CompressJob j0, CompressJob j1, int64_t n_tok,
+                                                                 int col_tiles) {
   __shared__ float red[NW][256];
+  const bool second = (int)blockIdx.y >= col_tiles;
+  // field-wise select: every kernel argument is fetched in the first round trip
+  const bf16_t* x = second ? j1.x : j0.x;
+  const bf16_t* Wt = second ? j1.Wt : j0.Wt;
+  const bf16_t* bias = second ? j1.bias : j0.bias;
+  bf16_t* out = second ? j1.out : j0.out;
+  const int64_t d_in = second ? j1.d_in : j0.d_in, ldx = second ? j1.ldx : j0.ldx, ldo = second ? j1.ldo : j0.ldo;
+  const int64_t x_bs = second ? j1.x_bs : j0.x_bs, out_bs = second ? j1.out_bs : j0.out_bs;
   const bf16_t* xb = x + (int64_t)blockIdx.z * x_bs;
   bf16_t* ob = out + (int64_t)blockIdx.z * out_bs;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, q = lane >> 4;
   const int64_t tok0 = (int64_t)blockIdx.x * 16;
-  const int col0 = blockIdx.y * 16;
+  const int col0 = ((int)blockIdx.y - (second ? col_tiles : 0)) * 16;
   int64_t tok = tok0 + r;
   tok = tok < n_tok ? tok : n_tok - 1;               // keep the address valid; the row is discarded
   const int64_t kq = d_in / NW;                      // this wave's share of the reduction (multiple of 32)
   const bf16_t* xp = xb + tok * ldx + wave * kq + q * 8;
   const bf16_t* wp = Wt + (int64_t)(col0 + r) * d_in + wave * kq + q * 8;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
+  // One pair of loads in flight per wave is enough here: sixteen waves per workgroup and two workgroups
+  // per compute unit hide the latency, and what paces the kernel is L2 traffic (every workgroup reads
+  // its token rows and its weight rows for one 16 x 16 output tile).  Issuing eight steps' loads at
+  // once was measured slower (17.5 against 11.8 us for the chunk's queries and keys).
   for (int64_t ks = 0; ks < kq; ks += 32) {
     const bf16x8 a = *(const bf16x8*)(xp + ks);
     const bf16x8 b = *(const bf16x8*)(wp + ks);
@@ -217,13 +236,13 @@ int launch_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx, con
     const bool vec_ok = (ldx % 8 == 0) && (x_bs % 8 == 0) && (((uintptr_t)x | (uintptr_t)W) % 16 == 0);
     if (packed && vec_ok && d_c % 16 == 0 && d_in % 128 == 0) {
       // few tokens: the reduction is cut sixteen ways so that every lane's loads are all in flight at once
-      const dim3 grid((unsigned)((n_tok + 15) / 16), d_c / 16, batch);
+      const int tiles = (int)((n_tok + 15) / 16);
+      const dim3 grid((unsigned)tiles, d_c / 16, batch);
+      const CompressJob job{(const bf16_t*)x, (const bf16_t*)W, (const bf16_t*)bias, (bf16_t*)out, d_in, ldx, ldo, x_bs, out_bs};
       if (d_in % 512 == 0 && n_tok <= 4096)
-        compress_mfma_packed_bf16<16><<<grid, 1024, 0, st>>>((const bf16_t*)x, n_tok, d_in, ldx, (const bf16_t*)W,
-                                                             (const bf16_t*)bias, d_c, (bf16_t*)out, ldo, x_bs, out_bs);
+        compress_mfma_packed_bf16<16><<<grid, 1024, 0, st>>>(job, job, n_tok, d_c / 16);
       else
-        compress_mfma_packed_bf16<4><<<grid, 256, 0, st>>>((const bf16_t*)x, n_tok, d_in, ldx, (const bf16_t*)W,
-                                                           (const bf16_t*)bias, d_c, (bf16_t*)out, ldo, x_bs, out_bs);
+        compress_mfma_packed_bf16<4><<<grid, 256, 0, st>>>(job, job, n_tok, d_c / 16);
     } else if (!packed && vec_ok && (d_c % kMCols == 0) && (d_in % kMStep == 0)) {
       compress_mfma_bf16<<<dim3((unsigned)nblk, d_c / kMCols, batch), 256, 0, st>>>(
           (const bf16_t*)x, n_tok, d_in, ldx, (const bf16_t*)W, (const bf16_t*)bias, d_c, (bf16_t*)out, ldo, x_bs,
@@ -246,6 +265,28 @@ int launch_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx, con
   }
   ESA_LAUNCH_CHECK("compress");
   return ESA_OK;
+}
+
+// Two inputs in one launch when both take the short-reduction matrix-core kernel; otherwise one launch each.
+int launch_compress_pair(const void* x0, int64_t d_in0, int64_t ldx0, const void* W0, const void* bias0, void* out0,
+                         int64_t ldo0, int64_t x0_bs, int64_t out0_bs, const void* x1, int64_t d_in1, int64_t ldx1,
+                         const void* W1, const void* bias1, void* out1, int64_t ldo1, int64_t x1_bs, int64_t out1_bs,
+                         int64_t n_tok, int d_c, int w_layout, int dtype, int batch, hipStream_t st) {
+  auto fast = [&](const void* x, int64_t d_in, int64_t ldx, const void* W, int64_t x_bs) {
+    return (ldx % 8 == 0) && (x_bs % 8 == 0) && (((uintptr_t)x | (uintptr_t)W) % 16 == 0) && d_in % 512 == 0;
+  };
+  if (dtype == ESA_BF16 && w_layout == ESA_W_PACKED && d_c % 16 == 0 && n_tok <= 4096 && n_tok > 0 &&
+      fast(x0, d_in0, ldx0, W0, x0_bs) && fast(x1, d_in1, ldx1, W1, x1_bs)) {
+    const int tiles = (int)((n_tok + 15) / 16);
+    const CompressJob j0{(const bf16_t*)x0, (const bf16_t*)W0, (const bf16_t*)bias0, (bf16_t*)out0, d_in0, ldx0, ldo0, x0_bs, out0_bs};
+    const CompressJob j1{(const bf16_t*)x1, (const bf16_t*)W1, (const bf16_t*)bias1, (bf16_t*)out1, d_in1, ldx1, ldo1, x1_bs, out1_bs};
+    compress_mfma_packed_bf16<16><<<dim3(tiles, 2 * (d_c / 16), batch), 1024, 0, st>>>(j0, j1, n_tok, d_c / 16);
+    ESA_LAUNCH_CHECK("compress (pair)");
+    return ESA_OK;
+  }
+  const int rc = launch_compress(x0, n_tok, d_in0, ldx0, W0, w_layout, bias0, d_c, out0, ldo0, dtype, batch, x0_bs, out0_bs, st);
+  if (rc != ESA_OK) return rc;
+  return launch_compress(x1, n_tok, d_in1, ldx1, W1, w_layout, bias1, d_c, out1, ldo1, dtype, batch, x1_bs, out1_bs, st);
 }
 
 }  // namespace esa

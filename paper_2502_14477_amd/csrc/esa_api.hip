@@ -76,6 +76,29 @@ int esa_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx, const 
                          (hipStream_t)stream);
 }
 
+int esa_compress_qk(const void* xq, int64_t d_in_q, int64_t ldxq, const void* Wq, const void* bias_q, void* out_q,
+                    int64_t ldoq, int64_t xq_bs, int64_t outq_bs, const void* xk, int64_t d_in_k, int64_t ldxk,
+                    const void* Wk, const void* bias_k, void* out_k, int64_t ldok, int64_t xk_bs, int64_t outk_bs,
+                    int64_t n_tok, int d_c, int w_layout, int dtype, int batch, void* stream) {
+  if (!dtype_ok(dtype)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_compress_qk: dtype %d", dtype);
+  if (w_layout != ESA_W_ROWMAJOR && w_layout != ESA_W_PACKED)
+    ESA_FAIL(ESA_EINVAL, "esa_compress_qk: weight layout %d", w_layout);
+  if (n_tok < 0 || d_in_q <= 0 || d_in_k <= 0 || d_c <= 0 || batch <= 0 || batch > kMaxBatch || n_tok >= (int64_t)1 << 31)
+    ESA_FAIL(ESA_EINVAL, "esa_compress_qk: bad size (n_tok=%lld d_in=%lld/%lld d_c=%d batch=%d)", (long long)n_tok,
+             (long long)d_in_q, (long long)d_in_k, d_c, batch);
+  if (d_c % 16 != 0 || d_c > 256) ESA_FAIL(ESA_EUNSUPPORTED, "esa_compress_qk: d_c=%d (multiple of 16, <= 256)", d_c);
+  if (ldxq < d_in_q || ldxk < d_in_k || ldoq < d_c || ldok < d_c)
+    ESA_FAIL(ESA_EINVAL, "esa_compress_qk: row stride smaller than the row");
+  if (n_tok == 0) return ESA_OK;
+  if (!xq || !Wq || !out_q || !xk || !Wk || !out_k) ESA_FAIL(ESA_EINVAL, "esa_compress_qk: null pointer");
+  const size_t es = elem_size(dtype);
+  if (!aligned(xq, es) || !aligned(Wq, es) || !aligned(out_q, es) || !aligned(bias_q, es) || !aligned(xk, es) ||
+      !aligned(Wk, es) || !aligned(out_k, es) || !aligned(bias_k, es))
+    ESA_FAIL(ESA_EINVAL, "esa_compress_qk: misaligned pointer");
+  return launch_compress_pair(xq, d_in_q, ldxq, Wq, bias_q, out_q, ldoq, xq_bs, outq_bs, xk, d_in_k, ldxk, Wk, bias_k, out_k,
+                              ldok, xk_bs, outk_bs, n_tok, d_c, w_layout, dtype, batch, (hipStream_t)stream);
+}
+
 size_t esa_score_workspace_bytes(int l_c, int64_t n_mid, int eps, int batch) {
   return score_workspace_bytes(l_c, n_mid, eps, batch);
 }

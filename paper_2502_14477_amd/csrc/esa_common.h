@@ -88,6 +88,11 @@ int launch_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx, con
                     const void* bias, int d_c, void* out, int64_t ldo, int dtype, int batch, int64_t x_bs,
                     int64_t out_bs, hipStream_t st);
 
+int launch_compress_pair(const void* x0, int64_t d_in0, int64_t ldx0, const void* W0, const void* bias0, void* out0,
+                         int64_t ldo0, int64_t x0_bs, int64_t out0_bs, const void* x1, int64_t d_in1, int64_t ldx1,
+                         const void* W1, const void* bias1, void* out1, int64_t ldo1, int64_t x1_bs, int64_t out1_bs,
+                         int64_t n_tok, int d_c, int w_layout, int dtype, int batch, hipStream_t st);
+
 size_t score_workspace_bytes(int l_c, int64_t n_mid, int eps, int batch);
 int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, int64_t m_hi, int d_c, int eps,
                  float* score, int dtype, int batch, int64_t q_bs, int64_t kc_bs, int64_t score_bs,

@@ -17,7 +17,7 @@ def _declared():
 
 def test_every_declared_symbol_is_exported_and_bound():
     names = _declared()
-    assert len(names) == 19 and "esa_attend" in names and "esa_select_topk" in names
+    assert len(names) == 20 and "esa_attend" in names and "esa_select_topk" in names
     raw = ctypes.CDLL(esa.lib_path())
     for n in names:
         assert hasattr(raw, n), n
@@ -53,6 +53,10 @@ def test_argument_validation_returns_codes_without_a_gpu():
     assert L.esa_pack_weights(fake, 64, 32, 0, fake, None) == -1                                    # in place is refused
     assert L.esa_pack_weights(None, 64, 32, 0, fake, None) == -1
     assert b"esa_pack_weights" in L.esa_last_error()
+    qk = lambda ldxk, ptr=fake: L.esa_compress_qk(ptr, 64, 64, fake, None, fake, 32, 0, 0, fake, 32, ldxk, fake, None, fake, 32, 0, 0,
+                                                  4, 32, 1, 0, 1, None)
+    assert qk(16) == -1                                                                             # key row stride < d_in
+    assert qk(32, None) == -1
     # score: bad range, missing workspace
     assert L.esa_score(fake, 4, fake, 10, 5, 32, 0, fake, 0, 1, 0, 0, 0, fake, 1 << 20, None) == -1
     assert L.esa_score(fake, 4, fake, 0, 100, 32, 0, fake, 0, 1, 0, 0, 0, None, 0, None) == -3

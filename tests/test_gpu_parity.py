@@ -179,6 +179,43 @@ def test_compress_writes_rows_of_a_strided_cache_in_place(esa):
         assert np.max(np.abs(got[b, t0:t0 + l_c] - want)) <= 1e-5
 
 
+@pytest.mark.parametrize("dtype,B,n_tok,hq,hk,d,d_c,packed", [
+    ("bf16", 1, 512, 32, 8, 128, 128, True),      # the chunk of configuration 3: one launch for both
+    ("bf16", 2, 37, 8, 4, 128, 64, True),         # ragged token count, batched
+    ("bf16", 1, 1, 32, 8, 128, 128, True),        # decode
+    ("bf16", 1, 40, 4, 2, 64, 32, True),          # d_in not a multiple of 512: one launch each
+    ("bf16", 1, 40, 8, 4, 128, 64, False),        # row-major weights
+    ("f32", 2, 24, 4, 2, 64, 32, False)])
+def test_compress_qk_equals_two_compress_calls(esa, dtype, B, n_tok, hq, hk, d, d_c, packed):
+    say(f"compress_qk dtype={dtype} B={B} n_tok={n_tok} hq={hq} hk={hk} d={d} d_c={d_c} packed={packed}")
+    rng = np.random.default_rng(90 + n_tok + hq)
+    S, t0 = n_tok + 11, 5
+    q = orc.round_to_storage(rng.standard_normal((B, n_tok, hq, d)), dtype)
+    Kc = orc.round_to_storage(rng.standard_normal((B, S, hk, d)), dtype)
+    Wq = orc.round_to_storage(rng.standard_normal((hq * d, d_c)) / np.sqrt(hq * d), dtype)
+    Wk = orc.round_to_storage(rng.standard_normal((hk * d, d_c)) / np.sqrt(hk * d), dtype)
+    bq = orc.round_to_storage(rng.standard_normal(d_c) * 0.1, dtype)
+    qd, Kd, Wqd, Wkd, bqd = (f64_to_dev(a, dtype) for a in (q, Kc, Wq, Wk, bq))
+    if packed:
+        Wqd, Wkd = esa.esa_pack_weights(Wqd), esa.esa_pack_weights(Wkd)
+    cache = torch.full((B, S, d_c), 3.0, dtype=qd.dtype, device="cuda")
+    cache_ref = cache.clone()
+    got_q, got_k = esa.esa_compress_qk(qd, Wqd, Kd[:, t0:t0 + n_tok], Wkd, bias_q=bqd, out_k=cache[:, t0:t0 + n_tok])
+    ref_q = esa.esa_compress(qd, Wqd, bias=bqd)
+    esa.esa_compress(Kd[:, t0:t0 + n_tok], Wkd, out=cache_ref[:, t0:t0 + n_tok])
+    assert torch.equal(got_q, ref_q) and torch.equal(cache, cache_ref)     # the same arithmetic, bit for bit
+    assert got_k.data_ptr() == cache[:, t0:t0 + n_tok].data_ptr()
+    tol = 1e-5 if dtype == "f32" else None
+    for b in range(B):
+        want_q = orc.compress(q[b].reshape(n_tok, -1), Wq, bq, dtype)
+        want_k = orc.compress(Kc[b, t0:t0 + n_tok].reshape(n_tok, -1), Wk, None, dtype)
+        for got, want in ((to_f64(got_q[b]), want_q), (to_f64(cache[b, t0:t0 + n_tok]), want_k)):
+            if tol is not None:
+                assert np.max(np.abs(got - want)) <= tol
+            else:       # within one bf16 step (fp32 accumulation crossing a rounding midpoint)
+                assert np.all(np.abs(got - want) <= bf16_ulp(want) * 1.001)
+
+
 # ------------------------------------------------------------------------------------------ score
 @pytest.mark.parametrize("dtype,l_c,n,d_c,m_lo", [
     ("f32", 128, 1632, 32, 32), ("f32", 1, 999, 32, 0), ("f32", 5, 63, 16, 7),
