@@ -179,9 +179,9 @@ __global__ __launch_bounds__(64 * NW) void compress_mfma_packed_bf16(CompressJob
   const bf16_t* wp = Wt + (int64_t)(col0 + r) * d_in + wave * kq + q * 8;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   // One pair of loads in flight per wave is enough here: sixteen waves per workgroup and two workgroups
-  // per compute unit hide the latency, and what paces the kernel is L2 traffic (every workgroup reads
-  // its token rows and its weight rows for one 16 x 16 output tile).  Issuing eight steps' loads at
-  // once was measured slower (17.5 against 11.8 us for the chunk's queries and keys).
+  // per compute unit hide the latency.  Putting eight steps' loads in flight at once changed nothing
+  // (11.8 us for the chunk's queries and keys either way), and was slower when the short job had to issue
+  // surplus loads to fit the same unrolled loop (17.5 us).
   for (int64_t ks = 0; ks < kq; ks += 32) {
     const bf16x8 a = *(const bf16x8*)(xp + ks);
     const bf16x8 b = *(const bf16x8*)(wp + ks);
