@@ -208,9 +208,9 @@ ESA_API int esa_attend_finish(const void* q, int l_c, int h, int h_kv, int d,
  * esa_gather_kv and esa_attend in one call: the selected tokens' keys and values are read from the
  * caches through the index list (ascending absolute positions, as esa_select_topk writes them), so
  * no gathered copy is written and read back ("a small number of keys and values are loaded" per
- * step, Appendix B).  Computes exactly what esa_gather_kv followed by esa_attend computes.  Decode-
- * sized chunks and the plain kernel follow the indices directly; the matrix-core prefill kernel
- * works on tiles of consecutive rows and gathers into the workspace first.
+ * step, Appendix B).  Computes exactly what esa_gather_kv followed by esa_attend computes.  Every
+ * kernel follows the indices itself; the matrix-core prefill kernel looks the rows of a tile up one
+ * tile ahead of the tile's loads.
  *   idx  [batch][n_sel] int32, batch stride idx_bs; entries are positions of middle tokens (an entry
  *        outside [0, l_start) is clamped into it rather than followed)
  *   workspace esa_attend_indexed_workspace_bytes(...) bytes, 256-byte aligned

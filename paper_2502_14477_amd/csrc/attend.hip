@@ -115,10 +115,8 @@ size_t generic_parts_bytes(int l_c, int h, int d, int batch) {
 }  // namespace
 
 size_t attend_indexed_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch, int n_sel) {
-  size_t b = attend_workspace_bytes(l_c, h, h_kv, d, dtype, batch);
-  if (l_c > 0 && h > 0 && h_kv > 0 && d > 0 && batch > 0 && n_sel > 0 && attend_mfma_supported(l_c, h, h_kv, d, dtype))
-    b = align_up(b, 256) + 2 * align_up((size_t)n_sel * h_kv * d * 2, 256) * batch;
-  return b;
+  (void)n_sel;      // every kernel follows the indices itself: no room for gathered rows is needed
+  return attend_workspace_bytes(l_c, h, h_kv, d, dtype, batch);
 }
 
 size_t attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch) {
@@ -147,24 +145,11 @@ int launch_attend(int part, int split, const void* q, int l_c, int h, int h_kv, 
   // The two calls of a separately encoded attention must take the same kernel: no fallback between them.
   if (mfma_shape && !mfma_aligned && part != kAttendAll && split == ESA_SPLIT_ALGORITHM1)
     ESA_FAIL(ESA_EINVAL, "esa_attend (two calls, Algorithm 1 grouping): pointers and strides must be 16-byte aligned");
-  if (mfma_shape && mfma_aligned && sel_idx) {
-    // The matrix-core kernel addresses whole tiles of consecutive rows, so an index list is turned
-    // into gathered rows first (room for them follows the attention workspace proper).
-    const size_t own = attend_mfma_workspace_bytes(l_c, h, h_kv, d, batch);
-    const size_t rows_bytes = align_up((size_t)n_sel * h_kv * d * 2, 256);
-    if (!ws || ws_bytes < own + 2 * rows_bytes * batch) ESA_FAIL(ESA_EWORKSPACE, "esa_attend_indexed: workspace too small");
-    char* ks_tmp = (char*)ws + own;
-    char* vs_tmp = ks_tmp + rows_bytes * batch;
-    const int rc = launch_gather(k_cache, v_cache, tok_stride, sel_idx, n_sel, h_kv, d, ks_tmp, vs_tmp, dtype, batch,
-                                 cache_bs, idx_bs, (int64_t)(rows_bytes / 2), st);
-    if (rc != ESA_OK) return rc;
-    return launch_attend_mfma(part, split, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, sg.i_end, sg.l_start,
-                              ks_tmp, vs_tmp, n_sel, scale, out, lse, batch, q_bs, cache_bs, (int64_t)(rows_bytes / 2),
-                              out_bs, ws, own, st);
-  }
   if (mfma_shape && mfma_aligned) {
+    // an index list is followed by the kernel itself (index-driven tile loads): no gathered copy
     return launch_attend_mfma(part, split, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, sg.i_end, sg.l_start, k_sel,
-                              v_sel, n_sel, scale, out, lse, batch, q_bs, cache_bs, sel_bs, out_bs, ws, ws_bytes, st);
+                              v_sel, n_sel, sel_idx, idx_bs, scale, out, lse, batch, q_bs, cache_bs, sel_bs, out_bs, ws,
+                              ws_bytes, st);
   }
   // Every other shape.  With the initial tokens in the early part the finishing (or the only) call
   // computes everything; Algorithm 1's grouping (separately encoded parts) runs the plain kernel once

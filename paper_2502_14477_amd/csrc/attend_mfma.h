@@ -14,8 +14,9 @@ enum { kAttendAll = 0, kAttendLocal = 1, kAttendFinish = 2 };
 size_t attend_mfma_workspace_bytes(int l_c, int h, int h_kv, int d, int batch);
 int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache, const void* v_cache,
                        int64_t tok_stride, int64_t t0, int64_t i_end, int64_t l_start, const void* k_sel,
-                       const void* v_sel, int n_sel, float scale, void* out, float* lse, int batch, int64_t q_bs,
-                       int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes, hipStream_t st);
+                       const void* v_sel, int n_sel, const int32_t* sel_idx, int64_t idx_bs, float scale, void* out,
+                       float* lse, int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws,
+                       size_t ws_bytes, hipStream_t st);
 
 // Section 3.2's two differently encoded parts in one launch (see attend_mfma.hip).
 int launch_attend_mfma_two_views(const void* q_loc, const void* q_glob, int64_t qw_bs, int l_c, int h, int h_kv, int d,

@@ -71,6 +71,9 @@ struct KeyView {
   uint32_t tok_bytes;               // row stride of the cache
   uint32_t i_end, n_sel, l_start;
   uint32_t n_fixed;                 // keys every row sees
+  const int32_t* sel_idx;           // not null: the n_sel selected rows are cache rows sel_idx[0..n_sel), not a gathered buffer
+  int64_t idx_bs;                   // batch stride of the index list
+  uint32_t idx_limit;               // indices are clamped into [0, idx_limit)
   int with_chunk;     // 1: the virtual sequence ends with the current chunk (causal); 0: every key is visible to every row
   int n_split;        // slices of this view (view 0's slices come first)
   int slot0;          // partial results of slice s go to slot slot0 + s
@@ -109,13 +112,19 @@ struct RowRef {
   bool in_sel;
   uint64_t off;
 };
-__device__ __forceinline__ RowRef row_ref(const KeyView& V, uint32_t sel_bytes, uint32_t j) {
+__device__ __forceinline__ uint32_t clamped_index(const KeyView& V, const int32_t* sidx, uint32_t pos) {
+  const int32_t v = sidx[pos];      // a middle token's position; clamped so that a bad index cannot leave the cache
+  return v < 0 ? 0u : ((uint32_t)v < V.idx_limit ? (uint32_t)v : V.idx_limit - 1);
+}
+// sidx: this batch element's index list, or null when the selected rows come from the gathered buffer
+__device__ __forceinline__ RowRef row_ref(const KeyView& V, const int32_t* sidx, uint32_t sel_bytes, uint32_t j) {
   const bool in_i = j < V.i_end;
   const bool in_s = !in_i && (j < V.i_end + V.n_sel);
-  const uint32_t row = in_i ? j : (in_s ? j - V.i_end : j - V.i_end - V.n_sel + V.l_start);
+  uint32_t row = in_i ? j : (in_s ? j - V.i_end : j - V.i_end - V.n_sel + V.l_start);
   RowRef r;
-  r.in_sel = in_s;
-  r.off = (uint64_t)row * (in_s ? sel_bytes : V.tok_bytes);
+  r.in_sel = in_s && !sidx;
+  if (in_s && sidx) row = clamped_index(V, sidx, row);
+  r.off = (uint64_t)row * (r.in_sel ? sel_bytes : V.tok_bytes);
   return r;
 }
 
@@ -158,6 +167,9 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     V.n_sel = vw ? v1.n_sel : v0.n_sel;
     V.l_start = vw ? v1.l_start : v0.l_start;
     V.n_fixed = vw ? v1.n_fixed : v0.n_fixed;
+    V.sel_idx = vw ? v1.sel_idx : v0.sel_idx;
+    V.idx_bs = vw ? v1.idx_bs : v0.idx_bs;
+    V.idx_limit = vw ? v1.idx_limit : v0.idx_limit;
     V.with_chunk = vw ? v1.with_chunk : v0.with_chunk;
     V.n_split = vw ? v1.n_split : v0.n_split;
     V.slot0 = vw ? v1.slot0 : v0.slot0;
@@ -207,6 +219,18 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   auto dma16 = [&](const char* src, bf16_t* dst_wave_uniform) {
     __builtin_amdgcn_global_load_lds((global_void*)src, (lds_void*)dst_wave_uniform, 16, 0, 0);
   };
+  // Index-driven selected rows (the gather folded into this kernel): the two cache rows this lane fetches
+  // for a tile that lies inside the selected segment are looked up one tile ahead of the tile's loads,
+  // so that the look-up is not a dependent round trip in front of them.
+  const int32_t* sidx = V.sel_idx ? V.sel_idx + (int64_t)b * V.idx_bs : nullptr;
+  uint32_t idx_a = 0, idx_b = 0;
+  auto idx_prefetch = [&](uint32_t t) {
+    const uint32_t j0 = t * kKT;
+    if (sidx && t < tile_end && j0 >= V.i_end && j0 + kKT <= V.i_end + V.n_sel) {
+      idx_a = clamped_index(V, sidx, j0 - V.i_end + st_row);
+      idx_b = clamped_index(V, sidx, j0 - V.i_end + st_row + 32);
+    }
+  };
   auto tile_load = [&](uint32_t j0, bf16_t* kt, bf16_t* vt) {
     const uint32_t sel_end = V.i_end + V.n_sel;
     int seg = -1;                                                  // 0: cache rows, 1: gathered rows
@@ -228,7 +252,12 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     bf16_t* kd1 = kt + (wave + 8) * 512;
     bf16_t* vd0 = vt + wave * 512;
     bf16_t* vd1 = vt + (wave + 8) * 512;
-    if (seg >= 0) {
+    if (seg == 1 && sidx) {             // rows idx_a / idx_b of the cache, looked up by idx_prefetch for this tile
+      dma16(kc + ((uint64_t)idx_a * V.tok_bytes + kcol), kd0);
+      dma16(kc + ((uint64_t)idx_b * V.tok_bytes + kcol), kd1);
+      dma16(vc + ((uint64_t)idx_a * V.tok_bytes + vcol), vd0);
+      dma16(vc + ((uint64_t)idx_b * V.tok_bytes + vcol), vd1);
+    } else if (seg >= 0) {
       const uint32_t stride = seg ? a.sel_bytes : V.tok_bytes;
       const char* kb = (seg ? ksl : kc) + (uint64_t)row0 * stride;
       const char* vbase = (seg ? vsl : vc) + (uint64_t)row0 * stride;
@@ -240,7 +269,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
       uint32_t ja = j0 + st_row, jb = j0 + st_row + 32;
       ja = ja < k_end ? ja : k_end - 1;                            // the tail repeats a key; masked below
       jb = jb < k_end ? jb : k_end - 1;
-      const RowRef ra = row_ref(V, a.sel_bytes, ja), rb = row_ref(V, a.sel_bytes, jb);
+      const RowRef ra = row_ref(V, sidx, a.sel_bytes, ja), rb = row_ref(V, sidx, a.sel_bytes, jb);
       dma16((ra.in_sel ? ksl : kc) + ra.off + kcol, kd0);
       dma16((rb.in_sel ? ksl : kc) + rb.off + kcol, kd1);
       dma16((ra.in_sel ? vsl : vc) + ra.off + vcol, vd0);
@@ -341,7 +370,9 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   };
 
   // The first tile's loads go out before the query fragments' so that the two round trips overlap.
+  idx_prefetch(tile_begin);
   if (tile_begin < tile_end) tile_load(tile_begin * kKT, k_st0, v_st0);
+  idx_prefetch(tile_begin + 1);
   {
     const bf16_t* qp = V.q + (int64_t)b * V.q_bs + ((int64_t)cc * a.h + head) * kD + hi * 8;
 #pragma unroll
@@ -357,11 +388,13 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     loads_landed();
     __syncthreads();
     if (t + 1 < tile_end) tile_load((t + 1) * kKT, k_st1, v_st1);
+    idx_prefetch(t + 2);
     tile_math(t, k_st0, v_st0);
     if (t + 1 < tile_end) {
       loads_landed();
       __syncthreads();
       if (t + 2 < tile_end) tile_load((t + 2) * kKT, k_st0, v_st0);
+      idx_prefetch(t + 3);
       tile_math(t + 1, k_st1, v_st1);
     }
   }
@@ -528,8 +561,11 @@ namespace {
 
 KeyView make_view(const void* q, int64_t q_bs, const void* k_cache, const void* v_cache, int64_t tok_stride,
                   int64_t cache_bs, int64_t i_end, int n_sel, int64_t l_start, int64_t n_fixed, int with_chunk,
-                  int n_split, int slot0) {
+                  int n_split, int slot0, const int32_t* sel_idx = nullptr, int64_t idx_bs = 0, int64_t idx_limit = 1) {
   KeyView v;
+  v.sel_idx = n_sel > 0 ? sel_idx : nullptr;
+  v.idx_bs = idx_bs;
+  v.idx_limit = (uint32_t)(idx_limit > 0 ? idx_limit : 1);
   v.q = (const bf16_t*)q;
   v.k_cache = (const char*)k_cache;
   v.v_cache = (const char*)v_cache;
@@ -555,9 +591,9 @@ int clamp_splits(int ns, int64_t keys_of_first_tile) {
 
 int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache,
                        const void* v_cache, int64_t tok_stride, int64_t t0, int64_t i_end, int64_t l_start,
-                       const void* k_sel, const void* v_sel, int n_sel, float scale, void* out, float* lse, int batch,
-                       int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* ws, size_t ws_bytes,
-                       hipStream_t st) {
+                       const void* k_sel, const void* v_sel, int n_sel, const int32_t* sel_idx, int64_t idx_bs,
+                       float scale, void* out, float* lse, int batch, int64_t q_bs, int64_t cache_bs, int64_t sel_bs,
+                       int64_t out_bs, void* ws, size_t ws_bytes, hipStream_t st) {
   if (!(scale > 0.f)) ESA_FAIL(ESA_EINVAL, "esa_attend: scale must be positive");
   if (t0 + l_c >= ((int64_t)1 << 31) || tok_stride * 2 >= ((int64_t)1 << 32))
     ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend: positions beyond 2^31 are not supported by the matrix-core kernel");
@@ -605,7 +641,7 @@ int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h
   const dim3 merge_grid((unsigned)((rows + 7) / 8), batch);
   if (part == kAttendAll) {
     a.view[0] = make_view(q, q_bs, k_cache, v_cache, tok_stride, cache_bs, i_end, n_sel, l_start,
-                          i_end + n_sel + (t0 - l_start), 1, ns_all, 0);
+                          i_end + n_sel + (t0 - l_start), 1, ns_all, 0, sel_idx, idx_bs, l_start);
     a.to_slots = 0;
     launch((int64_t)batch * h_kv * a.n_qt * ns_all);
     if (ns_all > 1)
@@ -619,7 +655,7 @@ int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h
   } else {
     if (ns_sel > 0) {
       a.view[0] = make_view(q, q_bs, k_cache, v_cache, tok_stride, cache_bs, i_late, n_sel, 0, i_late + n_sel, 0, ns_sel,
-                            plan.local);
+                            plan.local, sel_idx, idx_bs, l_start);
       a.to_slots = 1;
       launch((int64_t)batch * h_kv * a.n_qt * ns_sel);
     }
