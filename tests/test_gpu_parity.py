@@ -691,3 +691,54 @@ def test_step_captured_as_a_graph_replays_identically(esa):
         other = gpu_step(esa, dev, cfg, 4608, kc_dev)          # eager work between replays
         torch.cuda.synchronize()
         assert other["O"].shape == want_O.shape
+
+
+def test_variant_calls_captured_as_a_graph_replay_identically(esa):
+    """The calls beside the five (both compressions at once, index-driven attention, the two-call form,
+    Section 3.2's re-encoding) captured in one graph: every replay reproduces the eager results."""
+    say("graph capture of the variant calls")
+    rng = np.random.default_rng(77)
+    H, H_kv, d, d_c, t0, l_C, l_I, l_L, n_sel = 8, 2, 128, 64, 1400, 96, 16, 300, 200
+    S = t0 + l_C
+    bf = torch.bfloat16
+    q = torch.from_numpy(rng.standard_normal((l_C, H, d)).astype(np.float32)).cuda().to(bf)
+    K = torch.from_numpy(rng.standard_normal((S, H_kv, d)).astype(np.float32)).cuda().to(bf)
+    V = torch.from_numpy(rng.standard_normal((S, H_kv, d)).astype(np.float32)).cuda().to(bf)
+    Wq = esa.esa_pack_weights((torch.randn(H * d, d_c, device="cuda") / 32).to(bf))
+    Wk = esa.esa_pack_weights((torch.randn(H_kv * d, d_c, device="cuda") / 16).to(bf))
+    i_end, l_start = segment_bounds(t0, l_I, l_L)
+    idx = torch.from_numpy(np.sort(rng.choice(np.arange(i_end, l_start), n_sel, replace=False)).astype(np.int32)).cuda()
+    kc = torch.zeros((S, d_c), dtype=bf, device="cuda")
+
+    def calls():
+        qc, _ = esa.esa_compress_qk(q, Wq, K[t0:], Wk, out_k=kc[t0:])
+        o_idx = esa.esa_attend_indexed(q, K, V, t0, l_I, l_L, idx)
+        ks, vs = esa.esa_gather_kv(K, V, idx)
+        esa.esa_attend_local(q, K, V, t0, l_I, l_L)
+        o_two = esa.esa_attend_finish(q, K, V, t0, l_I, l_L, ks, vs)
+        o_re = esa.esa_attend_reencoded(q, K, V, t0, l_I, l_L, ks, vs, 4096.0, 500000.0)
+        return qc, o_idx, o_two, o_re
+
+    want = [t.clone() for t in calls()]
+    want_kc = kc.clone()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        calls()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        got = calls()
+    for rep in range(3):
+        for t in got:
+            t.zero_()
+        kc.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for g, w in zip(got, want):
+            assert torch.equal(g, w), rep
+        assert torch.equal(kc, want_kc), rep
+        calls()                                              # eager work between replays
+        torch.cuda.synchronize()
