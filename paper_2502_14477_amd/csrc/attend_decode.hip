@@ -236,12 +236,23 @@ __global__ __launch_bounds__(256) void attend_decode_merge(const float* __restri
   const float l = wave_sum(__fmaf_rn(w0, a0.y, w1 * a1.y));
   float o0 = 0.f, o1 = 0.f;
   const float* po = part_o + row * stride * kD + lane * 2;
-#pragma unroll 4
-  for (int s = wave; s < splits; s += 4) {
-    const float w = s < 64 ? __shfl(w0, s, 64) : __shfl(w1, s - 64, 64);
-    const float2 o = *(const float2*)(po + (int64_t)s * kD);
-    o0 += w != 0.f ? w * o.x : 0.f;    // slices past the causal limit hold no output
-    o1 += w != 0.f ? w * o.y : 0.f;
+  // eight slices per trip, their loads issued together (a slice past the end re-reads slice 0 with weight 0)
+  for (int s0 = wave; s0 < splits; s0 += 4 * 8) {
+    float2 o[8];
+    float w[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int s = s0 + 4 * u;
+      const bool in = s < splits;
+      o[u] = *(const float2*)(po + (int64_t)(in ? s : 0) * kD);
+      const float ws = s < 64 ? __shfl(w0, s & 63, 64) : __shfl(w1, (s - 64) & 63, 64);
+      w[u] = in ? ws : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      o0 += w[u] != 0.f ? w[u] * o[u].x : 0.f;    // slices past the causal limit hold no output
+      o1 += w[u] != 0.f ? w[u] * o[u].y : 0.f;
+    }
   }
   red[wave][lane * 2] = o0;
   red[wave][lane * 2 + 1] = o1;
