@@ -317,7 +317,16 @@ __global__ __launch_bounds__(256) void score_rowmax_reduce(const float* __restri
   if (c >= l_c) return;
   const float* p = part_max + ((int64_t)b * l_c + c) * nblk;
   float m = -INFINITY;
-  for (int i = lane; i < nblk; i += 64) m = fmaxf(m, p[i]);
+  for (int i0 = lane; i0 < nblk; i0 += 4 * 64) {      // four loads in flight per lane (256 workgroups per trip)
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + 64 * u;
+      v[u] = p[i < nblk ? i : lane];
+      if (i >= nblk) v[u] = -INFINITY;
+    }
+    m = fmaxf(fmaxf(m, v[0]), fmaxf(fmaxf(v[1], v[2]), v[3]));
+  }
   m = wave_max(m);
   if (lane == 0) mu[(int64_t)b * l_c + c] = m;
 }
@@ -391,15 +400,36 @@ __global__ __launch_bounds__(256) void score_gemv_bf16(const bf16_t* __restrict_
 __global__ __launch_bounds__(256) void score_sub_mu(float* __restrict__ raw, int64_t n, const float* __restrict__ part,
                                                     int n_part, int64_t raw_bs) {
   __shared__ float red[4];
+  float* p = raw + (int64_t)blockIdx.y * raw_bs;
+  const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
+  // this thread's first four scores are requested together with the partial maxima: one round trip
+  float x[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int64_t i = first + u * stride;
+    x[u] = i < n ? p[i] : 0.f;
+  }
   float mu = -INFINITY;
-  for (int i = threadIdx.x; i < n_part; i += 256) mu = fmaxf(mu, part[(int64_t)blockIdx.y * n_part + i]);
+  for (int i0 = threadIdx.x; i0 < n_part; i0 += 4 * 256) {
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + 256 * u;
+      v[u] = part[(int64_t)blockIdx.y * n_part + (i < n_part ? i : 0)];
+      if (i >= n_part) v[u] = -INFINITY;
+    }
+    mu = fmaxf(fmaxf(mu, v[0]), fmaxf(fmaxf(v[1], v[2]), v[3]));
+  }
   mu = wave_max(mu);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mu;
   __syncthreads();
   mu = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-  float* p = raw + (int64_t)blockIdx.y * raw_bs;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
-    p[i] = p[i] - mu;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int64_t i = first + u * stride;
+    if (i < n) p[i] = x[u] - mu;
+  }
+  for (int64_t i = first + 4 * stride; i < n; i += stride) p[i] = p[i] - mu;
 }
 
 // Eq. 8: out[j] = max(in[max(j-eps,0) .. min(j+eps,n-1)]).
