@@ -28,7 +28,8 @@ constexpr int kBins = 2048;
 // Workspace of one batch row, in uint32 words.
 struct TopkLayout {
   static constexpr int hist = 0;                         // [3][kBins]
-  static constexpr int blk = 3 * kBins;                  // [2][nblk]: per block, scores above the 22-bit prefix / sharing it
+  static constexpr int pick = 3 * kBins;                 // [2][2]: (bin, remaining rank) chosen in the first / second histogram
+  static constexpr int blk = 3 * kBins + 4;              // [2][nblk]: per block, scores above the 22-bit prefix / sharing it
   // then [nblk][cap] uint16: last digits of the scores sharing the prefix, cap = scores per block
 };
 
@@ -135,28 +136,48 @@ __device__ __forceinline__ BinPick pick_bin(const BinSlice& sl, uint32_t k_rem, 
 
 // Key bits fixed by the passes before PASS, and the rank still to find below them.  All
 // histogram loads are issued before the first scan, so they cost one round trip together.
+// A pass picks one histogram itself (the one the pass before it filled) and reads what the earlier passes
+// picked from the workspace, where the pass that made the pick left it (every workgroup writes the same
+// two words).
 template <int PASS>
-__device__ __forceinline__ void resolve_prefix(const uint32_t* __restrict__ w, uint32_t k, uint32_t* wave_sums,
+__device__ __forceinline__ void resolve_prefix(uint32_t* __restrict__ w, uint32_t k, uint32_t* wave_sums,
                                                uint32_t* result, uint32_t* prefix, uint32_t* k_rem) {
-  BinSlice s0, s1, s2;
-  if (PASS >= 1) s0 = load_slice(w + TopkLayout::hist);
-  if (PASS >= 2) s1 = load_slice(w + TopkLayout::hist + kBins);
-  if (PASS >= 3) s2 = load_slice(w + TopkLayout::hist + 2 * kBins);
   uint32_t p = 0, kr = k;
-  if (PASS >= 1) {
-    const BinPick b0 = pick_bin(s0, kr, wave_sums, result);
-    p = b0.bin << 21;
-    kr = b0.k_rem;
+  if (PASS == 0) {
+    *prefix = 0;
+    *k_rem = k;
+    return;
   }
+  const BinSlice sl = load_slice(w + TopkLayout::hist + (PASS - 1) * kBins);
+  uint32_t b0 = 0, k0 = 0, b1 = 0, k1 = 0;
   if (PASS >= 2) {
-    const BinPick b1 = pick_bin(s1, kr, wave_sums, result);
-    p |= b1.bin << 10;
-    kr = b1.k_rem;
+    b0 = w[TopkLayout::pick + 0];
+    k0 = w[TopkLayout::pick + 1];
   }
   if (PASS >= 3) {
-    const BinPick b2 = pick_bin(s2, kr, wave_sums, result);
-    p |= b2.bin;
-    kr = b2.k_rem;
+    b1 = w[TopkLayout::pick + 2];
+    k1 = w[TopkLayout::pick + 3];
+  }
+  if (PASS == 1) {
+    const BinPick b = pick_bin(sl, k, wave_sums, result);
+    if (threadIdx.x == 0) {
+      w[TopkLayout::pick + 0] = b.bin;
+      w[TopkLayout::pick + 1] = b.k_rem;
+    }
+    p = b.bin << 21;
+    kr = b.k_rem;
+  } else if (PASS == 2) {
+    const BinPick b = pick_bin(sl, k0, wave_sums, result);
+    if (threadIdx.x == 0) {
+      w[TopkLayout::pick + 2] = b.bin;
+      w[TopkLayout::pick + 3] = b.k_rem;
+    }
+    p = (b0 << 21) | (b.bin << 10);
+    kr = b.k_rem;
+  } else {
+    const BinPick b = pick_bin(sl, k1, wave_sums, result);
+    p = (b0 << 21) | (b1 << 10) | b.bin;
+    kr = b.k_rem;
   }
   *prefix = p;
   *k_rem = kr;
@@ -236,13 +257,13 @@ __global__ __launch_bounds__(kThreads) void topk_hist(const float* __restrict__ 
 }
 
 __global__ __launch_bounds__(kThreads) void topk_write(const float* __restrict__ score, int64_t n, int64_t score_bs,
-                                                       const uint32_t* __restrict__ ws, int64_t row_words, int nblk,
+                                                       uint32_t* __restrict__ ws, int64_t row_words, int nblk,
                                                        int64_t base, int32_t* __restrict__ idx, int64_t idx_bs,
                                                        uint32_t k, int sub) {
   __shared__ uint32_t wave_sums[kThreads / 64];
   __shared__ uint32_t result[2];
   const float* row = score + (int64_t)blockIdx.y * score_bs;
-  const uint32_t* w = ws + (int64_t)blockIdx.y * row_words;
+  uint32_t* w = ws + (int64_t)blockIdx.y * row_words;
   int32_t* out = idx + (int64_t)blockIdx.y * idx_bs;
   const int64_t first0 = (int64_t)blockIdx.x * kTile * sub + (int64_t)threadIdx.x * kItems;
   uint32_t key[kItems];
