@@ -454,54 +454,60 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
 }
 
 // Algorithm 1's merge over partial results: weights 2^(m_s - M) with the maximum subtracted first.
-// The slots in use are [0, ns_a) and [slot_b, slot_b + ns_b) of n_slot.  32 lanes per row (four
-// head-dims each), eight rows per workgroup.
+// The slots in use are [0, ns_a) and [slot_b, slot_b + ns_b) of n_slot.  16 lanes per row (eight
+// head-dims, 16 bytes of fp16 partials, each), sixteen rows per workgroup.
 __global__ __launch_bounds__(256) void esa_attend_merge(const uint16_t* __restrict__ part_o,
                                                         const float* __restrict__ part_ml, int n_slot, int ns_a,
                                                         int slot_b, int ns_b, int64_t rows, bf16_t* __restrict__ out,
                                                         float* __restrict__ lse, int64_t out_bs, int64_t lse_bs) {
-  const int64_t row = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);
-  const int d4 = (threadIdx.x & 31) * 4;
+  const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int d8 = (threadIdx.x & 15) * 8;
   const int b = blockIdx.y;
   if (row >= rows) return;
   // Every load of the row goes out before the first use (one round trip): the slices' (maximum, sum)
   // pairs and their outputs.  A slice that saw no key of this row stored zeros and sum 0.
   float m[kMaxSlots], l[kMaxSlots];
-  uint2 po[kMaxSlots];
+  uint4 po[kMaxSlots];
 #pragma unroll
   for (int s = 0; s < kMaxSlots; ++s) {
     m[s] = -INFINITY;
     l[s] = 0.f;
-    po[s] = make_uint2(0u, 0u);
+    po[s] = make_uint4(0u, 0u, 0u, 0u);
     if (s < ns_a || (s >= slot_b && s < slot_b + ns_b)) {
       const int64_t prow = ((int64_t)b * n_slot + s) * rows + row;
       const float2 ml = *(const float2*)(part_ml + prow * 2);
       m[s] = ml.x;
       l[s] = ml.y;
-      po[s] = *(const uint2*)(part_o + prow * kD + d4);
+      po[s] = *(const uint4*)(part_o + prow * kD + d8);
     }
   }
   float M = -INFINITY;
 #pragma unroll
   for (int s = 0; s < kMaxSlots; ++s) M = fmaxf(M, m[s]);
   float L = 0.f;
-  float4 acc = {0.f, 0.f, 0.f, 0.f};
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
 #pragma unroll
   for (int s = 0; s < kMaxSlots; ++s) {
     const float w = m[s] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m[s] - M) * l[s];   // outputs are normalised by the slice's sum
-    const f16x2 p01 = *(const f16x2*)&po[s].x, p23 = *(const f16x2*)&po[s].y;
+    const uint32_t u[4] = {po[s].x, po[s].y, po[s].z, po[s].w};
     L += w;
-    acc.x += w * (float)p01[0];
-    acc.y += w * (float)p01[1];
-    acc.z += w * (float)p23[0];
-    acc.w += w * (float)p23[1];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const f16x2 p = *(const f16x2*)&u[i];
+      acc[2 * i] += w * (float)p[0];
+      acc[2 * i + 1] += w * (float)p[1];
+    }
   }
   const float inv = 1.f / L;
-  uint2 w2;
-  w2.x = pack_bf16x2(acc.x * inv, acc.y * inv);
-  w2.y = pack_bf16x2(acc.z * inv, acc.w * inv);
-  *(uint2*)(out + (int64_t)b * out_bs + row * kD + d4) = w2;
-  if (lse && d4 == 0) lse[(int64_t)b * lse_bs + row] = (M + __builtin_amdgcn_logf(L)) * kLn2;
+  uint4 w4;
+  w4.x = pack_bf16x2(acc[0] * inv, acc[1] * inv);
+  w4.y = pack_bf16x2(acc[2] * inv, acc[3] * inv);
+  w4.z = pack_bf16x2(acc[4] * inv, acc[5] * inv);
+  w4.w = pack_bf16x2(acc[6] * inv, acc[7] * inv);
+  *(uint4*)(out + (int64_t)b * out_bs + row * kD + d8) = w4;
+  if (lse && d8 == 0) lse[(int64_t)b * lse_bs + row] = (M + __builtin_amdgcn_logf(L)) * kLn2;
 }
 
 int choose_splits(int l_c, int group, int h_kv, int batch) {
@@ -638,7 +644,7 @@ int launch_attend_mfma(int part, int split, const void* q, int l_c, int h, int h
   a.view[1] = make_view(q, q_bs, k_cache, v_cache, tok_stride, cache_bs, 0, 0, 0, 0, 0, 0, 0);   // unused
   auto launch = [&](int64_t n_wg) { attend_mfma_bf16<<<dim3((unsigned)n_wg), kThreads, 0, st>>>(a); };
   const int64_t rows = (int64_t)l_c * h;
-  const dim3 merge_grid((unsigned)((rows + 7) / 8), batch);
+  const dim3 merge_grid((unsigned)((rows + 15) / 16), batch);
   if (part == kAttendAll) {
     a.view[0] = make_view(q, q_bs, k_cache, v_cache, tok_stride, cache_bs, i_end, n_sel, l_start,
                           i_end + n_sel + (t0 - l_start), 1, ns_all, 0, sel_idx, idx_bs, l_start);
@@ -721,7 +727,7 @@ int launch_attend_mfma_two_views(const void* q_loc, const void* q_glob, int64_t 
   attend_mfma_bf16<<<dim3((unsigned)((int64_t)batch * h_kv * a.n_qt * n_slot)), kThreads, 0, st>>>(a);
   const int64_t rows = (int64_t)l_c * h;
   if (n_slot > 1) {
-    const dim3 merge_grid((unsigned)((rows + 7) / 8), batch);
+    const dim3 merge_grid((unsigned)((rows + 15) / 16), batch);
     esa_attend_merge<<<merge_grid, 256, 0, st>>>(a.part_o, a.part_ml, n_slot, n_slot, 0, 0, rows, (bf16_t*)out, lse, out_bs,
                                                  rows);
   }
