@@ -21,7 +21,7 @@ namespace esa {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kItems = 8;                       // consecutive scores per thread
+constexpr int kItems = 4;                       // consecutive scores per thread
 constexpr int kTile = kThreads * kItems;        // scores per block
 constexpr int kBins = 2048;
 
