@@ -20,8 +20,8 @@
 namespace esa {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kItems = 4;                       // consecutive scores per thread
+constexpr int kThreads = 512;
+constexpr int kItems = 2;                       // consecutive scores per thread
 constexpr int kTile = kThreads * kItems;        // scores per block
 constexpr int kBins = 2048;
 
