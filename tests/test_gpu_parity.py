@@ -742,3 +742,41 @@ def test_variant_calls_captured_as_a_graph_replay_identically(esa):
         assert torch.equal(kc, want_kc), rep
         calls()                                              # eager work between replays
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("l_C,pad,n_sel", [(64, 64, 100),      # matrix-core kernel, token rows wider than h_kv*d
+                                           (64, 4, 100),       # rows not 16-byte aligned: the plain kernel
+                                           (1, 64, 100),       # decode kernel
+                                           (48, 64, 0)])
+def test_attend_reads_caches_with_padded_token_rows(esa, l_C, pad, n_sel):
+    """The caches as strided views (tok_stride > h_kv*d), for every attention form; the padding holds
+    huge values that must never be read."""
+    say(f"attend with padded token rows l_C={l_C} pad={pad} n_sel={n_sel}")
+    rng = np.random.default_rng(600 + l_C + pad)
+    H, H_kv, d, t0, l_I, l_L = 8, 2, 128, 900, 16, 200
+    S = t0 + l_C
+    q = orc.round_to_storage(rng.standard_normal((l_C, H, d)), "bf16")
+    K = orc.round_to_storage(rng.standard_normal((S, H_kv, d)), "bf16")
+    V = orc.round_to_storage(rng.standard_normal((S, H_kv, d)), "bf16")
+    i_end, l_start = segment_bounds(t0, l_I, l_L)
+    sel = np.sort(rng.choice(np.arange(i_end, l_start), n_sel, replace=False)).astype(np.int32) if n_sel else \
+        np.empty(0, np.int32)
+
+    def padded(x):
+        buf = torch.full((S, H_kv * d + pad), 3.0e38, dtype=torch.bfloat16, device="cuda")
+        view = buf[:, :H_kv * d].unflatten(1, (H_kv, d))
+        view.copy_(f64_to_dev(x, "bf16"))
+        return view
+
+    Kd, Vd, qd = padded(K), padded(V), f64_to_dev(q, "bf16")
+    assert Kd.stride(0) == H_kv * d + pad
+    idx = torch.from_numpy(sel).cuda()
+    ks, vs = esa.esa_gather_kv(Kd, Vd, idx) if n_sel else (None, None)
+    want, want_lse = orc.attend(q, K, V, t0, l_I, l_L, sel, 1.0 / np.sqrt(d))
+    O1, lse1 = esa.esa_attend(qd, Kd, Vd, t0, l_I, l_L, ks, vs, return_lse=True)
+    esa.esa_attend_local(qd, Kd, Vd, t0, l_I, l_L)
+    O2 = esa.esa_attend_finish(qd, Kd, Vd, t0, l_I, l_L, ks, vs)
+    O3 = esa.esa_attend_indexed(qd, Kd, Vd, t0, l_I, l_L, idx if n_sel else None)
+    for O in (O1, O2, O3):
+        assert np.max(np.abs(to_f64(O) - want)) <= O_TOL["bf16"]
+    assert np.max(np.abs(to_f64(lse1) - want_lse)) <= 1e-3
