@@ -780,3 +780,27 @@ def test_attend_reads_caches_with_padded_token_rows(esa, l_C, pad, n_sel):
     for O in (O1, O2, O3):
         assert np.max(np.abs(to_f64(O) - want)) <= O_TOL["bf16"]
     assert np.max(np.abs(to_f64(lse1) - want_lse)) <= 1e-3
+
+
+@pytest.mark.parametrize("dtype,n_tok,d_in,d_c,pad,packed", [("bf16", 70, 1024, 128, 64, True), ("bf16", 70, 1024, 128, 3, True),
+                                                              ("bf16", 33, 256, 64, 8, False), ("f32", 20, 128, 32, 5, False)])
+def test_compress_reads_rows_with_a_stride(esa, dtype, n_tok, d_in, d_c, pad, packed):
+    """x as a strided view (ldx > d_in): aligned padding keeps the matrix-core kernel, odd padding takes the
+    plain one; the padding holds huge values that must never be read."""
+    say(f"compress strided rows dtype={dtype} n_tok={n_tok} d_in={d_in} d_c={d_c} pad={pad} packed={packed}")
+    rng = np.random.default_rng(31 + n_tok + pad)
+    x = orc.round_to_storage(rng.standard_normal((n_tok, d_in)), dtype)
+    W = orc.round_to_storage(rng.standard_normal((d_in, d_c)) / np.sqrt(d_in), dtype)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    buf = torch.full((n_tok, d_in + pad), 3.0e38, dtype=tdt, device="cuda")
+    xd = buf[:, :d_in]
+    xd.copy_(f64_to_dev(x, dtype))
+    Wd = f64_to_dev(W, dtype)
+    if packed:
+        Wd = esa.esa_pack_weights(Wd)
+    got = to_f64(esa.esa_compress(xd, Wd))
+    want = orc.compress(x, W, None, dtype)
+    if dtype == "f32":
+        assert np.max(np.abs(got - want)) <= 1e-5
+    else:
+        assert np.all(np.abs(got - want) <= bf16_ulp(want) * 1.001)
