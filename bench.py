@@ -33,10 +33,10 @@ VARIANT_CALLS = ("attend_indexed", "attend_local", "attend_finish", "attend_reen
 # x2.0 for FETCH_SIZE, x1.0 for WRITE_SIZE), summed over the kernels of the call.  Counters cannot be
 # read from inside this script, so the figure is attached only to the workload it was measured on.
 MEASURED_TRAFFIC_BYTES = {
-    ("C3", 131072, "attend"): 1024.0 * (2.0 * (11635.5 + 8744.5) + (16896.0 + 4096.0)),
+    ("C3", 131072, "attend"): 1024.0 * (2.0 * (11645.5 + 8493.5) + (16896.0 + 4096.0)),
     ("C3", 131072, "score"): 1024.0 * (2.0 * (16668.0 + 16718.5 + 279.5) + (3986.0 + 501.5 + 4.0)),
-    ("C3", 131072, "select"): 1024.0 * (2.0 * (3.8 + 285.2 + 328.2 + 366.8 + 417.8)
-                                        + (24.0 + 4.8 + 106.3 + 4.2 + 9.7)),
+    ("C3", 131072, "select"): 1024.0 * (2.0 * (3.8 + 269.8 + 310.8 + 317.2 + 329.2)
+                                        + (24.0 + 7.9 + 121.5 + 8.2 + 11.5)),
     ("C3", 131072, "gather"): 1024.0 * (2.0 * 4137.1 + 8192.0),
 }
 
