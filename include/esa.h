@@ -153,6 +153,8 @@ ESA_API int esa_gather_kv(const void* k_cache, const void* v_cache, int64_t tok_
  *   out  [batch][l_c, h, d] contiguous, batch stride out_bs
  *   lse  [batch][l_c, h] fp32 natural-log normaliser, batch stride l_c*h; NULL to skip
  *   workspace esa_attend_workspace_bytes(...) bytes, 256-byte aligned
+ * Values may use the whole finite range of the storage type as long as the products and sums of Eq. 1
+ * stay finite in fp32; intermediate results that pass through the workspace carry their own scale.
  */
 ESA_API size_t esa_attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, int batch);
 ESA_API int esa_attend(const void* q, int l_c, int h, int h_kv, int d,
@@ -207,8 +209,8 @@ ESA_API int esa_attend_finish(const void* q, int l_c, int h, int h_kv, int d,
 /*
  * esa_gather_kv and esa_attend in one call: the selected tokens' keys and values are read from the
  * caches through the index list (ascending absolute positions, as esa_select_topk writes them), so
- * no gathered copy is written and read back ("a small number of keys and values are loaded" per
- * step, Appendix B).  Computes exactly what esa_gather_kv followed by esa_attend computes.  Every
+ * no gathered copy is written and read back: only the selected rows are read, once (Appendix B's
+ * per-step loading of the selected keys and values).  Computes exactly what esa_gather_kv followed by esa_attend computes.  Every
  * kernel follows the indices itself; the matrix-core prefill kernel looks the rows of a tile up one
  * tile ahead of the tile's loads.
  *   idx  [batch][n_sel] int32, batch stride idx_bs; entries are positions of middle tokens (an entry

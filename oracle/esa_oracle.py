@@ -190,8 +190,8 @@ def merge_partial_attention(outs, lses):
     lses = np.stack(lses)                        # [parts, l_C, H]
     top = lses.max(axis=0, keepdims=True)
     w = np.exp(lses - top)
-    fac = w / w.sum(axis=0, keepdims=True)
-    return sum(f[..., None] * o for f, o in zip(fac, outs))
+    share = w / w.sum(axis=0, keepdims=True)     # each part's share of the joint normaliser
+    return sum(s[..., None] * o for s, o in zip(share, outs))
 
 
 # ----------------------------------------------------------------------------- Section 3.2: position encoding

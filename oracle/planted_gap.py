@@ -17,8 +17,13 @@ from esa_inputs import push_keys_down, segment_bounds
 from . import esa_oracle as orc
 
 
-def plant_gap(layer, steps, tau: float, max_rounds: int = 30):
+def plant_gap(layer, steps, tau: float, max_rounds: int = 30, eps: int = 0):
     """Modify layer.K in place.  `steps` = chunk start positions to protect.
+
+    With eps > 0 the selection acts on the max-pooled score of Eq. 8: tokens that share a pooled value
+    (the same source token inside their windows) are tied exactly on any implementation and the tie
+    rule orders them, so the band to clear is the pooled values strictly between f_k - tau and
+    f_k + tau other than f_k itself, and what gets pushed is the source token of such a value.
 
     Returns (sorted array of modified positions, compressed keys K' as float64 [S, d_c]).
     Steps without a planted direction cannot be protected this way and raise.
@@ -41,6 +46,17 @@ def plant_gap(layer, steps, tau: float, max_rounds: int = 30):
             t1 = min(t0 + cfg.l_C, cfg.S)
             qc = orc.compress(orc.widen(layer.Q[t0 - q_lo:t1 - q_lo], cfg.dtype), W_q, None, cfg.dtype)
             F = orc.importance(qc, kc[i_end:l_start])
+            if eps > 0:
+                Fp = orc.proximity(F, eps)
+                f_k = Fp[np.argsort(-Fp, kind="stable")[cfg.k - 1]]
+                near = np.nonzero((np.abs(Fp - f_k) < tau) & (Fp != f_k))[0]
+                src = set()
+                for j in near.tolist():           # the tokens inside j's window that carry its pooled value
+                    lo, hi = max(j - eps, 0), min(j + eps, n_mid - 1)
+                    src.update((lo + np.nonzero(F[lo:hi + 1] == Fp[j])[0]).tolist())
+                for p in sorted(src):
+                    bad.setdefault(p + i_end, []).append(t0)
+                continue
             order = np.argsort(-F, kind="stable")
             f_k = F[order[cfg.k - 1]]
             below = order[cfg.k:]

@@ -135,7 +135,7 @@ def _cache_ptr(t: torch.Tensor) -> int:
     dptr = ctypes.c_void_p()
     err = _hip.hipHostGetDevicePointer(ctypes.byref(dptr), ctypes.c_void_p(t.data_ptr()), 0)
     if err != 0 or not dptr.value:
-        raise EsaError("hipHostGetDevicePointer failed (%d): the pinned cache is not mapped into the GPU" % err)
+        raise EsaError(-4, "hipHostGetDevicePointer failed (%d): the pinned cache is not mapped into the GPU" % err)
     return dptr.value
 
 

@@ -83,8 +83,8 @@ struct AttendArgs {
   KeyView view[2];
   bf16_t* out;
   float* lse;
-  uint16_t* part_o;   // [batch][n_slot][l_c][h][128] fp16 partial outputs, each normalised by its own sum
-  float* part_ml;     // [batch][n_slot][l_c][h][2]   running maximum (log2 domain) and sum
+  uint16_t* part_o;   // [batch][n_slot][l_c][h][128] fp16 partial outputs, un-normalised, scaled by 2^-E per row
+  float* part_ml;     // [batch][n_slot][l_c][h][2]   softmax reference (log2 domain) + E, and sum * 2^-E
   const char* k_sel;
   const char* v_sel;
   uint32_t sel_bytes;               // row stride of the gathered buffers
@@ -400,14 +400,31 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   }
 
   // ---- results.  Accumulator register v of tile md is head-dim 32*md + 8*(v/4) + 4*hi + v%4 of this
-  // lane's query, so a lane holds its whole output row in 8-byte pieces.  The rows are normalised,
-  // narrowed to 16 bits and turned into whole 256-byte rows in LDS (free by now), from where each wave
-  // writes its own 32 rows with fully coalesced 16-byte stores.  Final outputs are bf16; partial
-  // results of a key slice are fp16 (normalised values are bounded by max |v|, and fp16's 11-bit
-  // significand keeps their rounding well below that of the bf16 output) next to fp32 (maximum, sum).
+  // lane's query, so a lane holds its whole output row in 8-byte pieces.  The rows are narrowed to 16
+  // bits and turned into whole 256-byte rows in LDS (free by now), from where each wave writes its own
+  // 32 rows with fully coalesced 16-byte stores.  Final outputs are normalised and rounded to bf16.
+  // Partial results of a key slice stay un-normalised and are stored as fp16 with a per-row power-of-two
+  // scale 2^-E that brings the row's largest magnitude to about 2^13 (fp16's 11-bit significand keeps the
+  // rounding well below that of the bf16 output, and any magnitude bf16 inputs can produce fits); beside
+  // them go m + E and l * 2^-E, so that the merge's sums of 2^(m+E-M) * (O 2^-E) and 2^(m+E-M) * (l 2^-E)
+  // are the plain log-sum-exp combination of Algorithm 1 with no trace of E.
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const bool final_out = n_slices == 1 && !a.to_slots;
-  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  float m_store = m_run, l_store = l_tot;
+  if (!final_out) {
+    float amax = 0.f;
+#pragma unroll
+    for (int md = 0; md < 4; ++md)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) amax = fmaxf(amax, __builtin_fabsf(o[md][v]));
+    amax = fmaxf(amax, __shfl_xor(amax, 32, 64));
+    int s_exp = 267 - (int)((__float_as_uint(amax) >> 23) & 0xFFu);      // biased exponent of 2^-E
+    s_exp = s_exp < 17 ? 17 : (s_exp > 167 ? 167 : s_exp);              // 2^-110 .. 2^40
+    inv = __uint_as_float((uint32_t)s_exp << 23);
+    m_store = m_run - (float)(s_exp - 127);
+    l_store = l_tot * inv;
+  }
   __syncthreads();                       // every wave is done with the last tile
   {
     // wave w's 32 rows of 256 bytes go to half (w%2) of stage array w/2, 16-byte slots swizzled by row % 16
@@ -436,7 +453,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     const int64_t prow0 = ((int64_t)(b * a.n_slot + V.slot0 + split) * a.l_c) * a.h;
     dst = a.part_o + (prow0 + (int64_t)c_wave * a.h + head) * kD;
     if (hi == 0 && c_ok) {
-      float2 ml = {m_run, l_tot};
+      float2 ml = {m_store, l_store};
       *(float2*)(a.part_ml + (prow0 + (int64_t)c * a.h + head) * 2) = ml;
     }
   }
@@ -453,7 +470,8 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     a.lse[(int64_t)b * a.l_c * a.h + (int64_t)c * a.h + head] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2;
 }
 
-// Algorithm 1's merge over partial results: weights 2^(m_s - M) with the maximum subtracted first.
+// Algorithm 1's merge over partial results (un-normalised outputs and sums, both relative to the slice's
+// reference m_s): weights 2^(m_s - M) with the maximum subtracted first.
 // The slots in use are [0, ns_a) and [slot_b, slot_b + ns_b) of n_slot.  16 lanes per row (eight
 // head-dims, 16 bytes of fp16 partials, each), sixteen rows per workgroup.
 __global__ __launch_bounds__(256) void esa_attend_merge(const uint16_t* __restrict__ part_o,
@@ -490,9 +508,9 @@ __global__ __launch_bounds__(256) void esa_attend_merge(const uint16_t* __restri
   for (int i = 0; i < 8; ++i) acc[i] = 0.f;
 #pragma unroll
   for (int s = 0; s < kMaxSlots; ++s) {
-    const float w = m[s] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m[s] - M) * l[s];   // outputs are normalised by the slice's sum
+    const float w = m[s] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m[s] - M);
     const uint32_t u[4] = {po[s].x, po[s].y, po[s].z, po[s].w};
-    L += w;
+    L += w * l[s];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const f16x2 p = *(const f16x2*)&u[i];

@@ -163,9 +163,12 @@ size_t esa_attend_workspace_bytes(int l_c, int h, int h_kv, int d, int dtype, in
 // Argument checks shared by every form of the attention call (everything but the workspace size).
 static int attend_args_ok(int part, int split, const void* q, int l_c, int h, int h_kv, int d, const void* k_cache,
                           const void* v_cache, int64_t tok_stride, int64_t t0, int64_t l_i, int64_t l_l,
-                          const void* k_sel, const void* v_sel, int n_sel, const int32_t* sel_idx, const void* out,
-                          const float* lse, int dtype, int batch) {
+                          const void* k_sel, const void* v_sel, int n_sel, const int32_t* sel_idx, float scale,
+                          const void* out, const float* lse, int dtype, int batch) {
   if (!dtype_ok(dtype)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend: dtype %d", dtype);
+  if (!(scale > 0.f) || !(scale < 3.0e38f)) ESA_FAIL(ESA_EINVAL, "esa_attend: scale must be positive and finite");
+  if (t0 + l_c >= ((int64_t)1 << 31) || tok_stride >= ((int64_t)1 << 31))
+    ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend: positions or token strides beyond 2^31 are not supported");
   if (split != ESA_SPLIT_I_EARLY && split != ESA_SPLIT_ALGORITHM1) ESA_FAIL(ESA_EINVAL, "esa_attend: split %d", split);
   if (l_c <= 0 || h <= 0 || h_kv <= 0 || d <= 0 || batch <= 0 || batch > kMaxBatch || n_sel < 0 || t0 < 0 ||
       l_i < 0 || l_l < 0 || l_c > 65535 || h > 65535)
@@ -197,7 +200,7 @@ static int attend_checked(int part, int split, const void* q, int l_c, int h, in
                           float scale, void* out, float* lse, int dtype, int batch, int64_t q_bs, int64_t cache_bs,
                           int64_t sel_bs, int64_t out_bs, void* workspace, size_t ws_bytes, void* stream) {
   const int rc = attend_args_ok(part, split, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i, l_l, k_sel, v_sel,
-                                n_sel, sel_idx, out, lse, dtype, batch);
+                                n_sel, sel_idx, scale, out, lse, dtype, batch);
   if (rc != ESA_OK) return rc;
   const size_t need = sel_idx ? attend_indexed_workspace_bytes(l_c, h, h_kv, d, dtype, batch, n_sel)
                               : attend_workspace_bytes(l_c, h, h_kv, d, dtype, batch);
@@ -272,7 +275,7 @@ int esa_attend_reencoded(const void* q, int l_c, int h, int h_kv, int d, const v
                          int64_t q_bs, int64_t cache_bs, int64_t sel_bs, int64_t out_bs, void* workspace, size_t ws_bytes,
                          void* stream) {
   const int rc = attend_args_ok(kAttendAll, ESA_SPLIT_ALGORITHM1, q, l_c, h, h_kv, d, k_cache, v_cache, tok_stride, t0, l_i,
-                                l_l, k_sel, v_sel, n_sel, nullptr, out, lse, dtype, batch);
+                                l_l, k_sel, v_sel, n_sel, nullptr, scale, out, lse, dtype, batch);
   if (rc != ESA_OK) return rc;
   if (!rope_head_size_ok(d)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_attend_reencoded: head size %d", d);
   if (!(rope_base > 0.0) || !(w >= 0.0)) ESA_FAIL(ESA_EINVAL, "esa_attend_reencoded: base must be positive and w non-negative");

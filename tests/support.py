@@ -30,7 +30,7 @@ def bf16_ulp(x: np.ndarray) -> np.ndarray:
     return 2.0 ** (e - 7)
 
 
-def oracle_step(layer, kc64, t0):
+def oracle_step(layer, kc64, t0, eps=0):
     """Oracle result for the step at t0: (O, lse, selected, F, qc)."""
     cfg = layer.cfg
     q_lo = getattr(layer, "q_row0", 0)
@@ -39,11 +39,11 @@ def oracle_step(layer, kc64, t0):
     K = orc.widen(layer.K[:t1], cfg.dtype)
     V = orc.widen(layer.V[:t1], cfg.dtype)
     qc = orc.compress(q, orc.widen(layer.W_q, cfg.dtype), None, cfg.dtype)
-    O, lse, sel, F = orc.esa_step(q, K, V, kc64, qc, t0, cfg.l_I, cfg.l_L, cfg.k, 1.0 / np.sqrt(cfg.d))
+    O, lse, sel, F = orc.esa_step(q, K, V, kc64, qc, t0, cfg.l_I, cfg.l_L, cfg.k, 1.0 / np.sqrt(cfg.d), eps=eps)
     return O, lse, sel, F, qc
 
 
-def gpu_step(esa, dev, cfg, t0, kc_dev=None, two_calls=False):
+def gpu_step(esa, dev, cfg, t0, kc_dev=None, two_calls=False, eps=0):
     """The five library calls for the step at t0.  dev: dict of device tensors Q,K,V,W_q,W_k
     (Q may start at row dev['q_row0']).  kc_dev: compressed-key cache [S, d_c]; rows of the current
     tokens are (re)written by esa_compress.  Returns dict of device tensors."""
@@ -61,10 +61,11 @@ def gpu_step(esa, dev, cfg, t0, kc_dev=None, two_calls=False):
     out = {"qc": qc, "kc": kc_dev, "score": None}
     if n_mid > 0:
         if n_mid > cfg.k:
-            out["score"] = esa.esa_score(qc, kc_dev, i_end, l_start)
+            out["score"] = esa.esa_score(qc, kc_dev, i_end, l_start, eps=eps)
             idx = esa.esa_select_topk(out["score"], cfg.k, base=i_end)
         else:
-            idx = esa.esa_select_topk(torch.zeros(n_mid, dtype=torch.float32, device="cuda"), cfg.k, base=i_end)
+            # k covers the middle segment: every middle token is taken and the scores are never read
+            idx = esa.esa_select_topk(torch.empty(n_mid, dtype=torch.float32, device="cuda"), cfg.k, base=i_end)
         ks, vs = esa.esa_gather_kv(dev["K"], dev["V"], idx)
     else:
         idx = torch.empty(0, dtype=torch.int32, device="cuda")

@@ -24,8 +24,8 @@ O_TOL = {"f32": 1e-5, "bf16": 2e-2}
 # |F_gpu - F_oracle| for identical stored inputs: fp32 accumulation of d_c exact (bf16) or
 # once-rounded (fp32) products of magnitude <= ~600 -> a few 1e-4 absolute.
 F_TOL = {"f32": 2e-4, "bf16": 1e-3}
-# boundary gap planted for stage-wise / end-to-end index parity (8x the score deviation each mode sees)
-TAU_STAGE = {"f32": 2e-3, "bf16": 8e-3}
+# boundary gap planted for end-to-end index parity (the GPU chain scores its own K', Q', which differ from the
+# oracle's in a few last places: one bf16 step in a compressed component moves a score by up to ~0.1)
 TAU_E2E = {"f32": 2e-3, "bf16": 0.5}
 
 
@@ -250,6 +250,22 @@ def test_score_with_proximity_influence(esa, eps):
     assert np.max(np.abs(got - want)) <= F_TOL["f32"]
 
 
+@pytest.mark.parametrize("B,n,d_c,m_lo", [(4, 20000, 128, 128), (16, 9000, 128, 0), (3, 5003, 64, 7), (2, 4100, 256, 3)])
+def test_score_one_current_token_batched(esa, B, n, d_c, m_lo):
+    """The decode shape of the score call (one current token per sequence) with several independent
+    sequences in one call: every batch element against the oracle, and Eq. 4's invariants per row."""
+    say(f"score l_c=1 batch={B} n={n} d_c={d_c} m_lo={m_lo}")
+    rng = np.random.default_rng(B * 1009 + n)
+    qc = orc.round_to_storage(rng.standard_normal((B, 1, d_c)) * 1.5, "bf16")
+    kc = orc.round_to_storage(rng.standard_normal((B, m_lo + n + 5, d_c)), "bf16")
+    got = to_f64(esa.esa_score(f64_to_dev(qc, "bf16"), f64_to_dev(kc, "bf16"), m_lo, m_lo + n))
+    assert got.shape == (B, n)
+    for b in range(B):
+        want = orc.importance(qc[b], kc[b, m_lo:m_lo + n])
+        assert np.max(np.abs(got[b] - want)) <= F_TOL["bf16"], b
+        assert np.all(got[b] <= 0.0) and got[b].max() == 0.0
+
+
 def test_score_batched(esa):
     say("score batch=3")
     rng = np.random.default_rng(9)
@@ -369,6 +385,36 @@ def test_attend_random_shapes_all_three_forms(esa, seed):
         want, _ = orc.attend(Q[b], K[b], V[b], t0, l_I, l_L, sel[b], 1.0 / np.sqrt(d))
         for O in (O1, O2, O3):
             assert np.max(np.abs(to_f64(O[b]) - want)) <= O_TOL["bf16"]
+
+
+@pytest.mark.parametrize("vmax", [1.0e5, 1.0e29])
+def test_attend_with_values_beyond_the_fp16_range_on_the_multi_slice_path(esa, vmax):
+    """bf16 storage admits |v| far above 65504: key slices of the matrix-core kernel must hand such
+    rows to the merge without overflow (one dominant key per row makes the output as large as the value)."""
+    say(f"attend bf16 with |V| up to {vmax:g}, key slices merged")
+    rng = np.random.default_rng(8181)
+    H, H_kv, d, t0, l_C, l_I, l_L, n_sel = 8, 2, 128, 1400, 96, 16, 300, 200
+    S = t0 + l_C
+    Q = orc.round_to_storage(rng.standard_normal((l_C, H, d)), "bf16")
+    K = orc.round_to_storage(rng.standard_normal((S, H_kv, d)), "bf16")
+    V = rng.standard_normal((S, H_kv, d))
+    big = rng.choice(S, 40, replace=False)
+    V[big] *= vmax / 8.0                                         # some rows huge, most of unit scale
+    V = orc.round_to_storage(np.clip(V, -vmax, vmax), "bf16")
+    i_end, l_start = segment_bounds(t0, l_I, l_L)
+    sel = np.sort(rng.choice(np.arange(i_end, l_start), n_sel, replace=False)).astype(np.int32)
+    want, _ = orc.attend(Q, K, V, t0, l_I, l_L, sel, 1.0 / np.sqrt(d))
+    Qd, Kd, Vd = f64_to_dev(Q, "bf16"), f64_to_dev(K, "bf16"), f64_to_dev(V, "bf16")
+    ks, vs = esa.esa_gather_kv(Kd, Vd, torch.from_numpy(sel).cuda())
+    O1 = esa.esa_attend(Qd, Kd, Vd, t0, l_I, l_L, ks, vs)
+    esa.esa_attend_local(Qd, Kd, Vd, t0, l_I, l_L)
+    O2 = esa.esa_attend_finish(Qd, Kd, Vd, t0, l_I, l_L, ks, vs)
+    for O in (O1, O2):
+        got = to_f64(O)
+        assert np.all(np.isfinite(got))
+        # outputs of this size are judged relative to their own magnitude: bf16 keeps 8 significant bits
+        assert np.all(np.abs(got - want) <= O_TOL["bf16"] * np.maximum(1.0, np.abs(want)))
+    assert np.abs(want).max() > 70000.0
 
 
 def test_attend_batched(esa):
@@ -553,14 +599,18 @@ def test_attend_indexed_equals_gather_then_attend(esa, dtype, B, H, H_kv, d, t0,
 
 
 # ------------------------------------------------------------------------------------------ whole steps
-def _check_step(esa, layer, dev, kc64, kc_dev, t0, stagewise_too=True, two_calls=False):
+def _check_step(esa, layer, dev, kc64, kc_dev, t0, two_calls=False, eps=0):
     cfg = layer.cfg
-    O, lse, sel, F, qc = oracle_step(layer, kc64, t0)
-    g = gpu_step(esa, dev, cfg, t0, kc_dev, two_calls=two_calls)
+    O, lse, sel, F, qc = oracle_step(layer, kc64, t0, eps=eps)
+    g = gpu_step(esa, dev, cfg, t0, kc_dev, two_calls=two_calls, eps=eps)
     got_idx = g["idx"].cpu().numpy()
     assert np.array_equal(got_idx, sel), f"t0={t0}: selected sets differ in {np.sum(got_idx != sel)} slots"
     if g["score"] is not None:
-        assert np.max(np.abs(to_f64(g["score"]) - F)) <= TAU_E2E[cfg.dtype] / 4
+        # End to end the score inherits the last-place differences of the GPU's own K' and Q' (a quarter of
+        # the planted gap is the loose sanity bound here); the bar for the score call itself is F_TOL, held
+        # by the stage-wise tests above, which feed it the oracle's compressed vectors.
+        want_F = orc.proximity(F, eps) if eps > 0 else F
+        assert np.max(np.abs(to_f64(g["score"]) - want_F)) <= TAU_E2E[cfg.dtype] / 4
     assert np.max(np.abs(to_f64(g["O"]) - O)) <= O_TOL[cfg.dtype], f"t0={t0}"
     if g["k_sel"] is not None:
         assert torch.equal(g["k_sel"], dev["K"][torch.from_numpy(sel).long().cuda()])
@@ -629,6 +679,64 @@ def test_decode_step_equals_one_token_chunk_bf16(esa):
         g = _check_step(esa, layer, dev, kc64, kc_dev, t0)
         needles = np.setdiff1d(layer.plan.positions[t0], replaced)
         assert set(needles.tolist()) <= set(g["idx"].cpu().numpy().tolist())
+
+
+def test_decode_step_batched_call_chain_bf16(esa):
+    """Configuration 4's shape on shorter caches: four independent sequences stacked and taken through
+    the five calls as ONE batched call each (batch strides of every tensor in use), every sequence
+    compared with its own oracle step."""
+    cfg = get_config("C4").scaled(S=20000)
+    t0, B = cfg.S - 1, 4
+    layers, kc64s = [], []
+    for b in range(B):
+        layer = make_layer(cfg, batch=b)
+        replaced, kc64 = plant_gap(layer, [t0], TAU_E2E["bf16"])
+        say(f"batched decode S={cfg.S} batch element {b}, {replaced.shape[0]} rows replaced")
+        layers.append(layer)
+        kc64s.append(kc64)
+    Q = torch.stack([to_dev(l.Q[t0:t0 + 1], "bf16") for l in layers])          # [B, 1, H, d]
+    K = torch.stack([to_dev(l.K, "bf16") for l in layers])                      # [B, S, H_kv, d]
+    V = torch.stack([to_dev(l.V, "bf16") for l in layers])
+    Wq = esa.esa_pack_weights(to_dev(layers[0].W_q, "bf16"))
+    Wk = esa.esa_pack_weights(to_dev(layers[0].W_k, "bf16"))
+    kc = torch.zeros((B, cfg.S, cfg.d_c), dtype=torch.bfloat16, device="cuda")
+    esa.esa_compress(K[:, :t0], Wk, out=kc[:, :t0])                             # state left by the earlier steps
+    qc, _ = esa.esa_compress_qk(Q, Wq, K[:, t0:t0 + 1], Wk, out_k=kc[:, t0:t0 + 1])
+    i_end, l_start = esa.esa_segments(t0, cfg.l_I, cfg.l_L)
+    score = esa.esa_score(qc, kc, i_end, l_start)
+    idx = esa.esa_select_topk(score, cfg.k, base=i_end)
+    ks, vs = esa.esa_gather_kv(K, V, idx)
+    O, lse = esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks, vs, return_lse=True)
+    O_idx = esa.esa_attend_indexed(Q, K, V, t0, cfg.l_I, cfg.l_L, idx)
+    assert idx.shape == (B, cfg.k) and O.shape == (B, 1, cfg.H, cfg.d)
+    for b in range(B):
+        want_O, want_lse, sel, F, _ = oracle_step(layers[b], kc64s[b], t0)
+        got_idx = idx[b].cpu().numpy()
+        assert np.array_equal(got_idx, sel), f"batch element {b}: {np.sum(got_idx != sel)} slots differ"
+        assert np.max(np.abs(to_f64(score[b]) - F)) <= TAU_E2E["bf16"] / 4
+        assert torch.equal(ks[b], K[b][torch.from_numpy(sel).long().cuda()])
+        assert np.max(np.abs(to_f64(O[b]) - want_O)) <= O_TOL["bf16"], b
+        assert np.max(np.abs(to_f64(O_idx[b]) - want_O)) <= O_TOL["bf16"], b
+        assert np.max(np.abs(to_f64(lse[b]) - want_lse)) <= 1e-3, b
+
+
+@pytest.mark.parametrize("eps", [3])
+def test_whole_step_with_proximity_influence_selects_the_oracles_set(esa, eps):
+    """Eq. 8 between Eq. 4 and Eq. 2 in a whole step: pooling makes neighbouring tokens share a score
+    exactly, so the tie rule decides much of the selected set.  Configuration 1's shape, two steps."""
+    cfg = get_config("C1")
+    layer = make_layer(cfg)
+    steps = [1152, 1920]
+    replaced, kc64 = plant_gap(layer, steps, TAU_E2E["f32"], eps=eps)
+    say(f"C1 steps {steps} with eps={eps}, {replaced.shape[0]} rows replaced")
+    dev = layer_to_dev(layer)
+    kc_dev = esa.esa_compress(dev["K"], dev["W_k"])
+    for t0 in steps:
+        g = _check_step(esa, layer, dev, kc64, kc_dev, t0, eps=eps)
+        # the pooled scores are full of exact ties: fewer distinct values than tokens among the selected
+        pooled = to_f64(g["score"])
+        i_end, _ = segment_bounds(t0, cfg.l_I, cfg.l_L)
+        assert np.unique(pooled[g["idx"].cpu().numpy() - i_end]).size < cfg.k // 2
 
 
 @pytest.mark.parametrize("name", ["C2", "C3", "C5", "C4"])

@@ -106,3 +106,21 @@ def test_oracle_selects_every_needle_and_gap_planting_separates_the_boundary():
             # every needle outranks every token of this chunk's middle segment that was not planted
             others = np.setdiff1d(np.arange(i_end, l_start), planted)
             assert F[needles - i_end].min() > F[others - i_end].max()
+
+
+def test_gap_planting_on_pooled_scores_clears_both_sides_of_the_boundary_value():
+    """With Eq. 8's pooling the k-th pooled value may be shared by several tokens (ties, ordered by
+    position); every other pooled value must stay at least tau away from it."""
+    cfg = get_config("C1")
+    L = make_layer(cfg)
+    steps, tau, eps = [1152, 1920], 1.5, 3
+    replaced, kc = plant_gap(L, steps, tau, eps=eps)
+    assert 0 < replaced.shape[0] < 200
+    W_q = orc.widen(L.W_q, cfg.dtype)
+    for t0 in steps:
+        i_end, l_start = segment_bounds(t0, cfg.l_I, cfg.l_L)
+        qc = orc.compress(L.f64("Q", t0, t0 + cfg.l_C), W_q, None, cfg.dtype)
+        Fp = orc.proximity(orc.importance(qc, kc[i_end:l_start]), eps)
+        f_k = np.sort(Fp)[::-1][cfg.k - 1]
+        dist = np.abs(Fp - f_k)
+        assert dist[dist > 0].min() >= tau
