@@ -412,8 +412,10 @@ def test_attend_with_values_beyond_the_fp16_range_on_the_multi_slice_path(esa, v
     for O in (O1, O2):
         got = to_f64(O)
         assert np.all(np.isfinite(got))
-        # outputs of this size are judged relative to their own magnitude: bf16 keeps 8 significant bits
-        assert np.all(np.abs(got - want) <= O_TOL["bf16"] * np.maximum(1.0, np.abs(want)))
+        # bf16 probabilities (8 significant bits) times values of this size: the error of an output element
+        # scales with the values its row mixes, so rows are judged relative to their largest output
+        row_scale = np.maximum(1.0, np.abs(want).max(axis=2, keepdims=True))
+        assert np.all(np.abs(got - want) <= O_TOL["bf16"] * row_scale)
     assert np.abs(want).max() > 70000.0
 
 
