@@ -395,11 +395,15 @@ def test_attend_with_values_beyond_the_fp16_range_on_the_multi_slice_path(esa, v
     rng = np.random.default_rng(8181)
     H, H_kv, d, t0, l_C, l_I, l_L, n_sel = 8, 2, 128, 1400, 96, 16, 300, 200
     S = t0 + l_C
-    Q = orc.round_to_storage(rng.standard_normal((l_C, H, d)), "bf16")
-    K = orc.round_to_storage(rng.standard_normal((S, H_kv, d)), "bf16")
+    u = rng.standard_normal(d)
+    u /= np.linalg.norm(u)
+    Q = orc.round_to_storage(rng.standard_normal((l_C, H, d)) + 6.0 * u, "bf16")     # every query leans towards u
+    K = rng.standard_normal((S, H_kv, d))
+    K[3] = 8.0 * np.sqrt(d) * u                                  # an initial token every query attends to almost alone
+    K = orc.round_to_storage(K, "bf16")
     V = rng.standard_normal((S, H_kv, d))
-    big = rng.choice(S, 40, replace=False)
-    V[big] *= vmax / 8.0                                         # some rows huge, most of unit scale
+    big = np.concatenate([[3], rng.choice(S, 40, replace=False)])
+    V[big] *= vmax / 2.0                                         # some rows huge, most of unit scale
     V = orc.round_to_storage(np.clip(V, -vmax, vmax), "bf16")
     i_end, l_start = segment_bounds(t0, l_I, l_L)
     sel = np.sort(rng.choice(np.arange(i_end, l_start), n_sel, replace=False)).astype(np.int32)
