@@ -128,6 +128,28 @@ ESA_API int esa_select_topk(const float* score, int64_t n, int k, int64_t base,
                     void* workspace, size_t ws_bytes, void* stream);
 
 /*
+ * esa_select_topk for callers that cannot allocate device memory or pass a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation): the same kernels, with
+ * their scratch in an array that the library itself holds on every GPU it runs on, from load until
+ * the process ends.  No allocation of any kind happens in these calls.
+ *   esa_select_topk_static_capacity  bytes of scratch held per GPU; a call is accepted when
+ *                                    esa_select_topk_workspace_bytes(n, k, batch) does not exceed it
+ *                                    (e.g. 16 rows of 262144 scores), ESA_EWORKSPACE otherwise
+ *   esa_select_topk_static_prepare   optional: looks the array's device address up for the current
+ *                                    device now (otherwise the first call on a device does it); a
+ *                                    host-side query, nothing is enqueued
+ *   esa_select_topk_static           arguments and results exactly as esa_select_topk
+ * All calls on one GPU share the one array, which keeps the previous call's contents (what must start
+ * at zero is cleared by the call itself): calls that overlap in time on the same GPU, from any
+ * stream or thread, race.  Calls on different GPUs are independent.
+ */
+ESA_API size_t esa_select_topk_static_capacity(void);
+ESA_API int esa_select_topk_static_prepare(void);
+ESA_API int esa_select_topk_static(const float* score, int64_t n, int k, int64_t base,
+                    int32_t* idx,
+                    int batch, int64_t score_bs, int64_t idx_bs, void* stream);
+
+/*
  * Fetch the full-size keys and values of the selected tokens into dense buffers.
  *   k_cache, v_cache [batch][S, h_kv, d]  token stride tok_stride (>= h_kv*d), batch stride cache_bs
  *   idx              [batch][n_sel] token positions (each in [0, S); not checked on the device)

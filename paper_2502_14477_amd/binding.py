@@ -57,6 +57,12 @@ def _load() -> ctypes.CDLL:
     L.esa_select_topk_workspace_bytes.argtypes = [i64, i32, i32]
     L.esa_select_topk.restype = i32
     L.esa_select_topk.argtypes = [vp, i64, i32, i64, vp, i32, i64, i64, vp, sz, vp]
+    L.esa_select_topk_static_capacity.restype = sz
+    L.esa_select_topk_static_capacity.argtypes = []
+    L.esa_select_topk_static_prepare.restype = i32
+    L.esa_select_topk_static_prepare.argtypes = []
+    L.esa_select_topk_static.restype = i32
+    L.esa_select_topk_static.argtypes = [vp, i64, i32, i64, vp, i32, i64, i64, vp]
     L.esa_gather_kv.restype = i32
     L.esa_gather_kv.argtypes = [vp, vp, i64, vp, i32, i32, i32, vp, vp, i32, i32, i64, i64, i64, vp]
     L.esa_attend_workspace_bytes.restype = sz
@@ -92,7 +98,8 @@ EXPORTS = ("esa_version", "esa_last_error", "esa_segments", "esa_pack_weights", 
            "esa_score", "esa_select_topk_workspace_bytes", "esa_select_topk", "esa_gather_kv",
            "esa_attend_workspace_bytes", "esa_attend", "esa_attend_local", "esa_attend_finish",
            "esa_attend_indexed_workspace_bytes", "esa_attend_indexed", "esa_rope",
-           "esa_attend_reencoded_workspace_bytes", "esa_attend_reencoded", "esa_compress_qk")
+           "esa_attend_reencoded_workspace_bytes", "esa_attend_reencoded", "esa_compress_qk",
+           "esa_select_topk_static_capacity", "esa_select_topk_static_prepare", "esa_select_topk_static")
 
 
 def _check(code: int) -> None:
@@ -277,6 +284,31 @@ def esa_select_topk(score: torch.Tensor, k: int, base: int = 0) -> torch.Tensor:
     ws = _workspace(nbytes, score.device, "topk")
     _check(lib.esa_select_topk(_ptr(sb), n, k, base, _ptr(idx), B, sb.stride(0) if B > 1 else max(n, 1),
                                max(k_eff, 1), _ptr(ws), ws.numel(), _stream()))
+    return idx if had_batch else idx[0]
+
+
+def esa_select_topk_static_capacity() -> int:
+    return lib.esa_select_topk_static_capacity()
+
+
+def esa_select_topk_static_prepare() -> None:
+    _check(lib.esa_select_topk_static_prepare())
+
+
+def esa_select_topk_static(score: torch.Tensor, k: int, base: int = 0, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """esa_select_topk on the library's own scratch.  With `out` given ([B?, min(k, n)] int32) this
+    function allocates nothing either."""
+    sb, had_batch = _batched(score, 1)
+    B, n = sb.shape
+    assert sb.dtype == torch.float32 and (n == 0 or sb.stride(1) == 1)
+    k_eff = min(k, n)
+    if out is None:
+        idx = torch.empty((B, k_eff), dtype=torch.int32, device=score.device)
+    else:
+        idx, _ = _batched(out, 1)
+        assert idx.dtype == torch.int32 and idx.shape == (B, k_eff) and idx.is_contiguous()
+    _check(lib.esa_select_topk_static(_ptr(sb), n, k, base, _ptr(idx), B, sb.stride(0) if B > 1 else max(n, 1),
+                                      max(k_eff, 1), _stream()))
     return idx if had_batch else idx[0]
 
 

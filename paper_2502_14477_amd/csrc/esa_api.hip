@@ -140,6 +140,21 @@ int esa_select_topk(const float* score, int64_t n, int k, int64_t base, int32_t*
   return launch_topk(score, n, k, base, idx, batch, score_bs, idx_bs, workspace, ws_bytes, (hipStream_t)stream);
 }
 
+size_t esa_select_topk_static_capacity(void) { return topk_static_capacity(); }
+
+int esa_select_topk_static_prepare(void) { return topk_static_prepare(); }
+
+int esa_select_topk_static(const float* score, int64_t n, int k, int64_t base, int32_t* idx, int batch,
+                           int64_t score_bs, int64_t idx_bs, void* stream) {
+  if (n < 0 || k < 0 || batch <= 0 || batch > kMaxBatch)
+    ESA_FAIL(ESA_EINVAL, "esa_select_topk_static: bad size (n=%lld k=%d batch=%d)", (long long)n, k, batch);
+  if (base < 0 || base + n > (int64_t)INT32_MAX) ESA_FAIL(ESA_EINVAL, "esa_select_topk_static: positions exceed int32");
+  if (n == 0 || k == 0) return ESA_OK;
+  if (!score || !idx) ESA_FAIL(ESA_EINVAL, "esa_select_topk_static: null pointer");
+  if (!aligned(score, 4) || !aligned(idx, 4)) ESA_FAIL(ESA_EINVAL, "esa_select_topk_static: misaligned pointer");
+  return launch_topk_static(score, n, k, base, idx, batch, score_bs, idx_bs, (hipStream_t)stream);
+}
+
 int esa_gather_kv(const void* k_cache, const void* v_cache, int64_t tok_stride, const int32_t* idx, int n_sel,
                   int h_kv, int d, void* k_sel, void* v_sel, int dtype, int batch, int64_t cache_bs, int64_t idx_bs,
                   int64_t sel_bs, void* stream) {

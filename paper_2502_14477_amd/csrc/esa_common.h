@@ -102,6 +102,11 @@ size_t topk_workspace_bytes(int64_t n, int k, int batch);
 int launch_topk(const float* score, int64_t n, int k, int64_t base, int32_t* idx, int batch, int64_t score_bs,
                 int64_t idx_bs, void* ws, size_t ws_bytes, hipStream_t st);
 
+size_t topk_static_capacity();
+int topk_static_prepare();
+int launch_topk_static(const float* score, int64_t n, int k, int64_t base, int32_t* idx, int batch, int64_t score_bs,
+                       int64_t idx_bs, hipStream_t st);
+
 int launch_gather(const void* k_cache, const void* v_cache, int64_t tok_stride, const int32_t* idx, int n_sel,
                   int h_kv, int d, void* k_sel, void* v_sel, int dtype, int batch, int64_t cache_bs,
                   int64_t idx_bs, int64_t sel_bs, hipStream_t st);

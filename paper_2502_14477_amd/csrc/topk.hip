@@ -15,6 +15,8 @@
 // histogram, or the per-block counts) is re-read and scanned by EVERY workgroup of the next
 // launch, redundantly, instead of being finished by a last-arriving workgroup — a launch is then
 // one round trip to memory plus a little LDS work, which is what bounds this latency-bound call.
+#include <atomic>
+
 #include "esa_common.h"
 
 namespace esa {
@@ -348,6 +350,52 @@ __global__ void topk_all(int64_t n, int64_t base, int32_t* idx, int64_t idx_bs) 
 }
 
 }  // namespace
+
+// ---------------------------------------------------------------- library-owned scratch (no caller workspace)
+// For callers that cannot allocate.  One array per GPU, held until the process ends; every call on
+// a GPU shares it, so calls that overlap in time on one GPU race.  In host code the array's name is
+// only a handle: its device address is looked up once per device and that address is what the
+// kernels are given.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_addr[kMaxDevices];
+
+// Device address of `scratch` on the current device (looked up on first use).
+static int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_failed(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) ESA_FAIL(ESA_EUNSUPPORTED, "device ordinal %d beyond %d", dev, kMaxDevices - 1);
+  void* p = g_scratch_addr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return hip_failed(e, "hipGetSymbolAddress(scratch)");
+    g_scratch_addr[dev].store(p, std::memory_order_release);     // every thread finds the same address
+  }
+  *out = p;
+  return ESA_OK;
+}
+
+size_t topk_static_capacity() { return kStaticScratchBytes; }
+
+int topk_static_prepare() {
+  void* p;
+  return static_scratch(&p);
+}
+
+int launch_topk_static(const float* score, int64_t n, int k, int64_t base, int32_t* idx, int batch, int64_t score_bs,
+                       int64_t idx_bs, hipStream_t st) {
+  const size_t need = topk_workspace_bytes(n, k, batch);
+  if (need > kStaticScratchBytes)
+    ESA_FAIL(ESA_EWORKSPACE, "esa_select_topk_static: %lld scores x %d rows need %zu bytes of scratch, the library holds %zu",
+             (long long)n, batch, need, kStaticScratchBytes);
+  void* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != ESA_OK) return rc;
+  return launch_topk(score, n, k, base, idx, batch, score_bs, idx_bs, ws, kStaticScratchBytes, st);
+}
 
 size_t topk_workspace_bytes(int64_t n, int k, int batch) {
   if (n <= 0 || k <= 0 || batch <= 0 || k >= n) return 256;
