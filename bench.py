@@ -3,18 +3,21 @@
 
 A "step" is one pass of the whole hot path for one chunk of current tokens: compress the
 chunk's queries and keys, score every middle token, pick the top-k, gather their keys/values
-and attend over [I, M_k, L, C].  The default workload is the metric's: the Llama-3-8B-shaped
-layer at 128k context (configuration 3), steady-state last chunk (t0 = 130560, 128384 middle
-tokens).  Inputs (Q, K, V, the compressed-key cache of the preceding tokens, weights) are
-resident in HBM before the timed region.
+and attend over [I, M_k, L, C].  The default workload is the metric's first half: the
+Llama-3-8B-shaped layer at 128k context (configuration 3), steady-state last chunk
+(t0 = 130560, 128384 middle tokens).  The metric's second half, the decode step on a
+256k-token cache (configuration 4, batch 1 and 16), is timed in the same run and reported
+under `decode`.  Inputs (Q, K, V, the compressed-key cache of the preceding tokens, weights)
+are resident in HBM before the timed region.
 
 Prints ONE JSON line: the contract fields plus `roofline` (dominant call, from HIP events
-recorded live on the launch stream) and `cpu_baseline` (the float64 oracle timed on the host
-cores on the same step).
+recorded live on the launch stream), `decode`, and `cpu_baseline` (the float64 oracle timed
+on the host cores on the same step).
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -27,18 +30,28 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
+CALLS = ("compress", "score", "select", "gather", "attend")
 VARIANT_CALLS = ("attend_indexed", "attend_local", "attend_finish", "attend_reencoded")   # timed beside the step
+
 # HBM bytes per launch from the rocprofv3 counter passes summarised under profiles/ (FETCH_SIZE and
 # WRITE_SIZE per dispatch, each scaled by what the same counter reads for a plain 256 MiB device copy:
 # x2.0 for FETCH_SIZE, x1.0 for WRITE_SIZE), summed over the kernels of the call.  Counters cannot be
-# read from inside this script, so the figure is attached only to the workload it was measured on.
-MEASURED_TRAFFIC_BYTES = {
-    ("C3", 131072, "attend"): 1024.0 * (2.0 * (11645.5 + 8493.5) + (16896.0 + 4096.0)),
-    ("C3", 131072, "score"): 1024.0 * (2.0 * (16668.0 + 16718.5 + 279.5) + (3986.0 + 501.5 + 4.0)),
-    ("C3", 131072, "select"): 1024.0 * (2.0 * (3.8 + 269.8 + 310.8 + 317.2 + 329.2)
-                                        + (24.0 + 7.9 + 121.5 + 8.2 + 11.5)),
-    ("C3", 131072, "gather"): 1024.0 * (2.0 * 4137.1 + 8192.0),
-}
+# read from inside this script, so a figure is attached only to the workload it was measured on and only
+# while the kernel sources are the ones it was measured on (TRAFFIC_TREE, see csrc_tree_hash).
+TRAFFIC_TREE = "unmeasured"
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def csrc_tree_hash():
+    """Fingerprint of the kernel sources: the stored traffic figures belong to exactly one such tree."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2502_14477_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            with open(os.path.join(csrc, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()[:16]
 
 
 def algorithmic_work(cfg, t0, n_mid, k_eff, l_c):
@@ -58,89 +71,65 @@ def algorithmic_work(cfg, t0, n_mid, k_eff, l_c):
     }
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="C3", help="C2, C3 or C5 (prefill), C4 (decode)")
-    ap.add_argument("--seq", type=int, default=0, help="override the sequence length (debugging)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--eager", action="store_true",
-                    help="time eager launches instead of replaying the step as a captured HIP graph")
-    ap.add_argument("--two-branches", action="store_true",
-                    help="variant: the selection-independent part (key compression, attention over I, L, C) runs on a "
-                         "second stream beside select and gather and esa_attend_finish adds the selected keys; measured "
-                         "equal to the one-stream step at configuration 3, slower at configuration 5")
-    ap.add_argument("--fused-gather", action="store_true",
-                    help="variant: esa_attend_indexed follows the indices itself instead of esa_gather_kv + esa_attend "
-                         "(four calls; not the default step)")
-    ap.add_argument("--fork-after", choices=("start", "score"), default="score",
-                    help="where the second stream starts (the score sweeps want every CU for themselves)")
-    ap.add_argument("--batch", type=int, default=1,
-                    help="independent sequences per step (the decode configuration is also quoted at 16)")
-    ap.add_argument("--prompt", action="store_true",
-                    help="secondary metric: prefill the whole prompt chunk by chunk (S / total time) instead of "
-                         "timing the last chunk")
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="also run one plain device copy of the key cache (calibrates HBM traffic counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+class Workload:
+    """One configuration's last step, resident on the GPU: B independent sequences."""
 
-    import numpy as np
-    import torch
-    import paper_2502_14477_amd as esa
-    from esa_inputs import get_config, make_layer, segment_bounds, chunk_starts
+    def __init__(self, esa, torch, np, cfg, B):
+        from esa_inputs import make_layer, segment_bounds, chunk_starts
+        self.cfg, self.B = cfg, B
+        self.t0 = chunk_starts(cfg)[-1]
+        self.l_c = min(cfg.l_C, cfg.S - self.t0)
+        self.i_end, self.l_start = segment_bounds(self.t0, cfg.l_I, cfg.l_L)
+        self.n_mid = self.l_start - self.i_end
+        self.k_eff = min(cfg.k, self.n_mid)
+        t_gen = time.time()
+        t0, l_c = self.t0, self.l_c
+        layers = [make_layer(cfg, batch=b, q_rows=(t0, t0 + l_c)) for b in range(B)]
+        for layer in layers:
+            layer.q_row0 = t0
+        self.layer = layers[0]
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    cfg = get_config(args.config)
-    if args.seq:
-        cfg = cfg.scaled(S=args.seq)
-    if args.prompt:
-        return whole_prompt(args, cfg, esa, torch, np)
-    # One stream unless asked otherwise; always one stream under the profiler (one dispatch after the
-    # other) and for decode-sized chunks, where nothing of the attention can start early.
-    args.single_stream = not args.two_branches or args.eager or cfg.l_C < 16
-    t0 = chunk_starts(cfg)[-1]
-    l_c = min(cfg.l_C, cfg.S - t0)
-    i_end, l_start = segment_bounds(t0, cfg.l_I, cfg.l_L)
-    n_mid = l_start - i_end
-    k_eff = min(cfg.k, n_mid)
+        def dev(name):
+            a = np.stack([getattr(x, name) for x in layers]) if B > 1 else getattr(self.layer, name)
+            if cfg.dtype == "f32":
+                return torch.from_numpy(a).cuda()
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
 
-    t_gen = time.time()
-    B = args.batch
-    layers = [make_layer(cfg, batch=b, q_rows=(t0, t0 + l_c)) for b in range(B)]
-    for layer in layers:
-        layer.q_row0 = t0
-    layer = layers[0]
+        def weights(a):
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16) if cfg.dtype == "bf16" \
+                else torch.from_numpy(a).cuda()
 
-    def dev(name):
-        a = np.stack([getattr(x, name) for x in layers]) if B > 1 else getattr(layer, name)
-        if cfg.dtype == "f32":
-            return torch.from_numpy(a).cuda()
-        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        self.Q, self.K, self.V = dev("Q"), dev("K"), dev("V")
+        del layers
+        # weights are packed once per layer, at load time (batch elements share the layer's weights)
+        self.W_q = esa.esa_pack_weights(weights(self.layer.W_q))
+        self.W_k = esa.esa_pack_weights(weights(self.layer.W_k))
+        # state left by the preceding steps: compressed keys of every earlier token
+        self.kc = torch.zeros(((B,) if B > 1 else ()) + (cfg.S, cfg.d_c), dtype=self.K.dtype, device="cuda")
+        for r0 in range(0, t0, 16384):
+            r1 = min(r0 + 16384, t0)
+            esa.esa_compress(self.rows(self.K, r0, r1), self.W_k, out=self.rows(self.kc, r0, r1))
+        torch.cuda.synchronize()
+        self.setup_s = time.time() - t_gen
 
-    def rows(t, r0, r1):
-        return t[:, r0:r1] if B > 1 else t[r0:r1]
+    def rows(self, t, r0, r1):
+        return t[:, r0:r1] if self.B > 1 else t[r0:r1]
 
-    Q, K, V = dev("Q"), dev("K"), dev("V")
-    # weights are packed once per layer, at load time (batch elements share the layer's weights)
-    W_q = esa.esa_pack_weights(torch.from_numpy(layer.W_q.view(np.int16)).cuda().view(torch.bfloat16)
-                               if cfg.dtype == "bf16" else torch.from_numpy(layer.W_q).cuda())
-    W_k = esa.esa_pack_weights(torch.from_numpy(layer.W_k.view(np.int16)).cuda().view(torch.bfloat16)
-                               if cfg.dtype == "bf16" else torch.from_numpy(layer.W_k).cuda())
-    # state left by the preceding steps: compressed keys of every earlier token
-    kc = torch.zeros(((B,) if B > 1 else ()) + (cfg.S, cfg.d_c), dtype=K.dtype, device="cuda")
-    for r0 in range(0, t0, 16384):
-        r1 = min(r0 + 16384, t0)
-        esa.esa_compress(rows(K, r0, r1), W_k, out=rows(kc, r0, r1))
-    torch.cuda.synchronize()
-    t_gen = time.time() - t_gen
+    def cold_copy(self):
+        """The same step on its own copy of the caches (distinct memory: nothing of it is in any cache)."""
+        import copy
+        w = copy.copy(self)
+        w.K, w.V, w.kc = self.K.clone(), self.V.clone(), self.kc.clone()
+        return w
 
-    calls = ("compress", "score", "select", "gather", "attend")
 
-    side = torch.cuda.Stream()
+def make_step(esa, torch, w, args, side=None):
+    """The five calls for one step of workload w, as a function to call (and to capture)."""
+    cfg, t0, l_c, B = w.cfg, w.t0, w.l_c, w.B
+    i_end, l_start, n_mid = w.i_end, w.l_start, w.n_mid
+    Q, K, V, kc, W_q, W_k = w.Q, w.K, w.V, w.kc, w.W_q, w.W_k
+    no_scores = torch.empty(((B,) if B > 1 else ()) + (n_mid,), dtype=torch.float32, device="cuda")
+    single_stream = args.single_stream or l_c < 16
 
     def step():
         # The five calls on one stream.  With --two-branches (Algorithm 1's split of the key set) the key
@@ -152,89 +141,98 @@ def main():
         def fork():
             side.wait_stream(main)
             with torch.cuda.stream(side):
-                esa.esa_compress(rows(K, t0, t0 + l_c), W_k, out=rows(kc, t0, t0 + l_c))
+                esa.esa_compress(w.rows(K, t0, t0 + l_c), W_k, out=w.rows(kc, t0, t0 + l_c))
                 esa.esa_attend_local(Q, K, V, t0, cfg.l_I, cfg.l_L)
 
-        if args.single_stream:       # queries and keys of the chunk compressed by one call (Eq. 5 has both)
-            qc, _ = esa.esa_compress_qk(Q, W_q, rows(K, t0, t0 + l_c), W_k, out_k=rows(kc, t0, t0 + l_c))
+        if single_stream:            # queries and keys of the chunk compressed by one call (Eq. 5 has both)
+            qc, _ = esa.esa_compress_qk(Q, W_q, w.rows(K, t0, t0 + l_c), W_k, out_k=w.rows(kc, t0, t0 + l_c))
         else:
             if args.fork_after == "start":
                 fork()
             qc = esa.esa_compress(Q, W_q)
-        if n_mid > cfg.k:
-            score = esa.esa_score(qc, kc, i_end, l_start)
-        else:
-            score = torch.zeros(((B,) if B > 1 else ()) + (n_mid,), dtype=torch.float32, device="cuda")
-        if not args.single_stream and args.fork_after == "score":
+        # k covers the middle segment in early chunks: every middle token is taken, no scores are read
+        score = esa.esa_score(qc, kc, i_end, l_start) if n_mid > cfg.k else no_scores
+        if not single_stream and args.fork_after == "score":
             fork()
         idx = esa.esa_select_topk(score, cfg.k, base=i_end)
         if args.fused_gather:
-            if not args.single_stream:
+            if not single_stream:
                 main.wait_stream(side)
             return esa.esa_attend_indexed(Q, K, V, t0, cfg.l_I, cfg.l_L, idx)
         ks, vs = esa.esa_gather_kv(K, V, idx)
-        if not args.single_stream:
+        if not single_stream:
             main.wait_stream(side)
             return esa.esa_attend_finish(Q, K, V, t0, cfg.l_I, cfg.l_L, ks, vs)
         return esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks, vs)
 
-    def timed(fn, n):
-        torch.cuda.synchronize()
-        t_start = time.perf_counter()
-        for _ in range(n):
-            fn()
-        torch.cuda.synchronize()
-        return 1e3 * (time.perf_counter() - t_start) / n
+    return step
 
-    def time_step():
-        for _ in range(max(args.warmup, 1)):
-            step()
-        eager = timed(step, args.steps)
-        if args.eager:
-            return eager, eager, "eager launches"
-        # The step is launch-bound on the host (about twenty small kernels), so it is captured once
-        # as a HIP graph and replayed; every kernel of the step runs in every replay.
-        warm = torch.cuda.Stream()
-        warm.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(warm):
-            step()
-        torch.cuda.current_stream().wait_stream(warm)
-        # One graph holds `per_graph` consecutive steps (as a prefill issues its chunks one after the other),
-        # so that the start-up gap of a graph launch is not paid by every step.
-        per_graph = 5 if args.steps % 5 == 0 else 1
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            for _ in range(per_graph):
-                graph_out = step()
-        for _ in range(max(args.warmup // per_graph, 1)):
-            graph.replay()
-        replay = timed(graph.replay, args.steps // per_graph) / per_graph
-        ref = step()
-        torch.cuda.synchronize()
-        assert torch.equal(ref, graph_out), "graph replay and eager step disagree"
-        return eager, replay, "HIP graph replay (%d steps per graph)" % per_graph
 
-    try:
-        eager_ms, ms_per_step, mode = time_step()
-    except Exception as exc:                # a second graph branch is an optimisation, not a requirement
-        if args.single_stream:
-            raise
-        print("bench.py: two-branch step failed (%s); timing the one-stream step" % exc, file=sys.stderr)
-        torch.cuda.synchronize()
-        args.single_stream = True
-        eager_ms, ms_per_step, mode = time_step()
+def wall_ms(torch, fn, n):
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(n):
+        fn()
+    torch.cuda.synchronize()
+    return 1e3 * (time.perf_counter() - t_start) / n
 
-    # Per-call durations from HIP events on the launch stream (torch's current stream).  Each call is
-    # issued `reps` times back to back between two events, as one captured graph (as separate launches
-    # under --eager), so that the figure is the kernels' own duration and not the host's launch gaps.
+
+def time_steps(torch, steps_fns, n_steps, warmup, eager_only):
+    """Time the step functions in `steps_fns` issued one after the other (one function: the same step
+    again and again, its caches warm; several: a rotation over independent copies of the caches, so that
+    every step finds its compressed keys and KV rows cold).  Returns (eager ms, replay ms, mode)."""
+    n_fn = len(steps_fns)
+
+    def round_of_steps():
+        out = None
+        for fn in steps_fns:
+            out = fn()
+        return out
+
+    for _ in range(max(warmup // n_fn, 1)):
+        round_of_steps()
+    eager = wall_ms(torch, round_of_steps, max(n_steps // n_fn, 1)) / n_fn
+    if eager_only:
+        return eager, eager, "eager launches", None
+    # The step is launch-bound on the host, so it is captured once as a HIP graph and replayed; every
+    # kernel of the step runs in every replay.  One graph holds several consecutive steps (as a prefill
+    # issues its chunks one after the other), so that the start-up gap of a graph launch is not paid by
+    # every step.
+    warm = torch.cuda.Stream()
+    warm.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(warm):
+        round_of_steps()
+    torch.cuda.current_stream().wait_stream(warm)
+    rounds_per_graph = 1 if n_fn > 1 else (5 if n_steps % 5 == 0 else 1)
+    per_graph = rounds_per_graph * n_fn
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(rounds_per_graph):
+            graph_out = round_of_steps()
+    for _ in range(max(warmup // per_graph, 1)):
+        graph.replay()
+    replay = wall_ms(torch, graph.replay, max(n_steps // per_graph, 1)) / per_graph
+    ref = steps_fns[-1]()
+    torch.cuda.synchronize()
+    assert torch.equal(ref, graph_out), "graph replay and eager step disagree"
+    return eager, replay, "HIP graph replay (%d steps per graph)" % per_graph, graph
+
+
+def per_call_times(esa, torch, np, w, args, with_variants):
+    """Per-call durations from HIP events on the launch stream (torch's current stream).  Each call is
+    issued `reps` times back to back between two events, as one captured graph (as separate launches
+    under --eager), so that the figure is the kernels' own duration and not the host's launch gaps."""
+    cfg, t0, l_c = w.cfg, w.t0, w.l_c
+    Q, K, V, kc, W_q, W_k = w.Q, w.K, w.V, w.kc, w.W_q, w.W_k
+    i_end, l_start, n_mid, B = w.i_end, w.l_start, w.n_mid, w.B
     qc_s = esa.esa_compress(Q, W_q)
     score_s = esa.esa_score(qc_s, kc, i_end, l_start) if n_mid > cfg.k else \
-        torch.zeros(((B,) if B > 1 else ()) + (n_mid,), dtype=torch.float32, device="cuda")
+        torch.empty(((B,) if B > 1 else ()) + (n_mid,), dtype=torch.float32, device="cuda")
     idx_s = esa.esa_select_topk(score_s, cfg.k, base=i_end)
     ks_s, vs_s = esa.esa_gather_kv(K, V, idx_s)
 
     def call_compress():
-        esa.esa_compress_qk(Q, W_q, rows(K, t0, t0 + l_c), W_k, out_q=qc_s, out_k=rows(kc, t0, t0 + l_c))
+        esa.esa_compress_qk(Q, W_q, w.rows(K, t0, t0 + l_c), W_k, out_q=qc_s, out_k=w.rows(kc, t0, t0 + l_c))
 
     single = {
         "compress": call_compress,
@@ -242,15 +240,15 @@ def main():
         "select": lambda: esa.esa_select_topk(score_s, cfg.k, base=i_end),
         "gather": lambda: esa.esa_gather_kv(K, V, idx_s),
         "attend": lambda: esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s),
-        "attend_indexed": lambda: esa.esa_attend_indexed(Q, K, V, t0, cfg.l_I, cfg.l_L, idx_s),
-        "attend_local": lambda: esa.esa_attend_local(Q, K, V, t0, cfg.l_I, cfg.l_L),
-        "attend_finish": lambda: esa.esa_attend_finish(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s),
-        # Section 3.2 inside the library (the inputs stand in for un-encoded ones: same work)
-        "attend_reencoded": lambda: esa.esa_attend_reencoded(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s, 4096.0, 5e5),
     }
-    if args.eager:      # under the profiler: only the step's own launches, so that per-kernel averages are the step's
-        for c in VARIANT_CALLS:
-            del single[c]
+    if with_variants:
+        single.update({
+            "attend_indexed": lambda: esa.esa_attend_indexed(Q, K, V, t0, cfg.l_I, cfg.l_L, idx_s),
+            "attend_local": lambda: esa.esa_attend_local(Q, K, V, t0, cfg.l_I, cfg.l_L),
+            "attend_finish": lambda: esa.esa_attend_finish(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s),
+            # Section 3.2 inside the library (the inputs stand in for un-encoded ones: same work)
+            "attend_reencoded": lambda: esa.esa_attend_reencoded(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s, 4096.0, 5e5),
+        })
     reps, rounds = 10, max(3, min(args.steps, 10))
     call_ms = {}
     for c in single:
@@ -276,64 +274,207 @@ def main():
             samples.append(e0.elapsed_time(e1) / reps)
         call_ms[c] = float(np.mean(samples))
         del run
+    return call_ms
+
+
+def call_report(w, call_ms):
+    work = algorithmic_work(w.cfg, w.t0, w.n_mid, w.k_eff, w.l_c)
+    for x in work.values():   # batch elements are independent sequences
+        x["flops"] *= w.B
+        x["bytes"] *= w.B
+    rep = {}
+    for c in CALLS:
+        us = 1e3 * call_ms[c]
+        r = {"us": round(us, 2)}
+        if us > 0:
+            if work[c]["flops"]:
+                r["tflops"] = round(work[c]["flops"] / (us * 1e-6) / 1e12, 2)
+            r["gbs"] = round(work[c]["bytes"] / (us * 1e-6) / 1e9, 1)
+            r["hbm_frac"] = round(r["gbs"] / PEAK_HBM_GBS, 4)
+        rep[c] = r
+    for c in VARIANT_CALLS:   # variants: fused gather, the two-call form, Section 3.2's re-encoding
+        if c in call_ms:
+            rep[c] = {"us": round(1e3 * call_ms[c], 2)}
+    return work, rep
+
+
+def workload_text(w):
+    cfg = w.cfg
+    return ("%s: H=%d H_kv=%d d=%d, S=%d, chunk l_C=%d at t0=%d, l_I=%d l_L=%d k=%d d_c=%d, %d middle tokens; "
+            "one step = compress+score+select+gather+attend for one chunk"
+            % (cfg.name, cfg.H, cfg.H_kv, cfg.d, cfg.S, w.l_c, w.t0, cfg.l_I, cfg.l_L, cfg.k, cfg.d_c, w.n_mid))
+
+
+def decode_record(esa, torch, np, args):
+    """Configuration 4: one decode step (one new token per sequence) on 256k-token caches, batch 1 and 16."""
+    from esa_inputs import get_config
+    cfg = get_config("C4")
+    out = {"workload": None, "unit": "us/step"}
+    for B in (1, 16):
+        w = Workload(esa, torch, np, cfg, B)
+        out["workload"] = workload_text(w)
+        step = make_step(esa, torch, w, args)
+        n = max(args.steps, 10)
+        eager, replay, mode, graph = time_steps(torch, [step], n, args.warmup, args.eager)
+        call_ms = per_call_times(esa, torch, np, w, args, with_variants=False)
+        work, rep = call_report(w, call_ms)
+        step_bytes = sum(x["bytes"] for x in work.values())
+        rec = {"us_per_step": round(1e3 * replay, 2), "eager_us_per_step": round(1e3 * eager, 2),
+               "tokens_per_s": round(B / (replay * 1e-3), 1),
+               "step_gbs": round(step_bytes / (replay * 1e-3) / 1e9, 1),
+               "step_hbm_frac": round(step_bytes / (replay * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+               "algorithmic_bytes": round(step_bytes), "per_call": rep, "launch_mode": mode,
+               "setup_s": round(w.setup_s, 1)}
+        if B == 1:
+            # one sequence's step touches about 100 MB, which the 256 MB memory-side cache keeps between
+            # replays: rotate over independent copies of the caches so that every step reads from HBM
+            del graph
+            copies = [w] + [w.cold_copy() for _ in range(4)]       # 5 x (66 MB K' + 2 x 512 MB KV)
+            fns = [make_step(esa, torch, c, args) for c in copies]
+            _, cold, _, graph = time_steps(torch, fns, max(n, 20), args.warmup, args.eager)
+            rec["cold_us_per_step"] = round(1e3 * cold, 2)
+            rec["cold_note"] = "rotation over 5 independent copies of K', K and V (330 MB of K' alone per round)"
+            del copies, fns
+        out["batch_%d" % B] = rec
+        del graph, w, step
+        torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="C3", help="C2, C3, C5, C6 (prefill) or C4 (decode)")
+    ap.add_argument("--seq", type=int, default=0, help="override the sequence length (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode record (configuration 4, batch 1 and 16)")
+    ap.add_argument("--cold", action="store_true",
+                    help="also time the step on a rotation over independent copies of the caches (more than 256 MB of "
+                         "compressed keys per round), so that nothing is served from the memory-side cache")
+    ap.add_argument("--eager", action="store_true",
+                    help="time eager launches instead of replaying the step as a captured HIP graph")
+    ap.add_argument("--two-branches", action="store_true",
+                    help="variant: the selection-independent part (key compression, attention over I, L, C) runs on a "
+                         "second stream beside select and gather and esa_attend_finish adds the selected keys; measured "
+                         "equal to the one-stream step at configuration 3, slower at configuration 5")
+    ap.add_argument("--fused-gather", action="store_true",
+                    help="variant: esa_attend_indexed follows the indices itself instead of esa_gather_kv + esa_attend "
+                         "(four calls; not the default step)")
+    ap.add_argument("--fork-after", choices=("start", "score"), default="score",
+                    help="where the second stream starts (the score sweeps want every CU for themselves)")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="independent sequences per step (the decode configuration is also quoted at 16)")
+    ap.add_argument("--prompt", action="store_true",
+                    help="secondary metric: prefill the whole prompt chunk by chunk (S / total time) instead of "
+                         "timing the last chunk")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain device copy of the key cache (calibrates HBM traffic counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_2502_14477_amd as esa
+    from esa_inputs import get_config
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = get_config(args.config)
+    if args.seq:
+        cfg = cfg.scaled(S=args.seq)
+    if args.prompt:
+        return whole_prompt(args, cfg, esa, torch, np)
+    # One stream unless asked otherwise; always one stream under the profiler (one dispatch after the
+    # other) and for decode-sized chunks, where nothing of the attention can start early.
+    args.single_stream = not args.two_branches or args.eager or cfg.l_C < 16
+    B = args.batch
+    w = Workload(esa, torch, np, cfg, B)
+    side = torch.cuda.Stream()
+
+    try:
+        eager_ms, ms_per_step, mode, graph = time_steps(torch, [make_step(esa, torch, w, args, side)], args.steps, args.warmup,
+                                                        args.eager)
+    except Exception as exc:                # a second graph branch is an optimisation, not a requirement
+        if args.single_stream:
+            raise
+        print("bench.py: two-branch step failed (%s); timing the one-stream step" % exc, file=sys.stderr)
+        torch.cuda.synchronize()
+        args.single_stream = True
+        eager_ms, ms_per_step, mode, graph = time_steps(torch, [make_step(esa, torch, w, args, side)], args.steps,
+                                                        args.warmup, args.eager)
+    del graph
+
+    cold_ms = None
+    if args.cold:
+        per_copy = w.kc.numel() * w.kc.element_size()
+        n_copies = max(3, int(320e6 // per_copy) + 1)
+        copies = [w] + [w.cold_copy() for _ in range(n_copies - 1)]
+        fns = [make_step(esa, torch, c, args, side) for c in copies]
+        _, cold_ms, _, graph = time_steps(torch, fns, max(args.steps, 2 * n_copies), args.warmup, args.eager)
+        del graph, fns, copies
+        torch.cuda.empty_cache()
+
+    # under the profiler (--eager) only the step's own launches are issued, so that per-kernel averages are the step's
+    call_ms = per_call_times(esa, torch, np, w, args, with_variants=not args.eager)
 
     if args.copy_probe:
         # a plain copy of known size (2 x K bytes moved), the yardstick for the HBM traffic counters
-        torch.empty_like(K).copy_(K)
+        torch.empty_like(w.K).copy_(w.K)
         torch.cuda.synchronize()
 
-    work = algorithmic_work(cfg, t0, n_mid, k_eff, l_c)
-    for w in work.values():   # batch elements are independent sequences
-        w["flops"] *= B
-        w["bytes"] *= B
-    per_call_report = {}
-    for c in calls:
-        us = 1e3 * call_ms[c]
-        rep = {"us": round(us, 2)}
-        if work[c]["flops"]:
-            rep["tflops"] = round(work[c]["flops"] / (us * 1e-6) / 1e12, 2)
-        rep["gbs"] = round(work[c]["bytes"] / (us * 1e-6) / 1e9, 1)
-        per_call_report[c] = rep
-    for c in VARIANT_CALLS:   # variants: fused gather, the two-call form, Section 3.2's re-encoding
-        if c in call_ms:
-            per_call_report[c] = {"us": round(1e3 * call_ms[c], 2)}
-    dominant = max(calls, key=lambda c: call_ms[c])
+    work, per_call_report = call_report(w, call_ms)
+    dominant = max(CALLS, key=lambda c: call_ms[c])
     if work[dominant]["flops"]:
         achieved = work[dominant]["flops"] / (call_ms[dominant] * 1e-3) / 1e12
         roofline = {"kernel": "esa_" + dominant, "bound": "mfma", "achieved": round(achieved, 2),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                     "traffic": None}
+        roofline["algorithmic_flops"] = round(work[dominant]["flops"])
     else:
         achieved = work[dominant]["bytes"] / (call_ms[dominant] * 1e-3) / 1e9
         roofline = {"kernel": "esa_" + dominant, "bound": "hbm", "achieved": round(achieved, 1),
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4),
                     "traffic": None}
-    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.S, dominant)) if B == 1 else None
+    # `traffic` and `algorithmic_bytes` are both HBM bytes per launch of the dominant call
+    traffic = None
+    if B == 1 and csrc_tree_hash() == TRAFFIC_TREE:
+        traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.S, dominant))
     roofline["traffic"] = None if traffic is None else round(traffic)
-    roofline["algorithmic"] = round(work[dominant]["flops"] or work[dominant]["bytes"])
+    roofline["algorithmic_bytes"] = round(work[dominant]["bytes"])
+    roofline["traffic_measured_on_tree"] = TRAFFIC_TREE if traffic is not None else None
     roofline["per_call"] = per_call_report
-    step_flops = sum(w["flops"] for w in work.values())
+    step_flops = sum(x["flops"] for x in work.values())
     roofline["step_tflops"] = round(step_flops / (ms_per_step * 1e-3) / 1e12, 2)
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
-        cpu_baseline = cpu_oracle_baseline(layer, cfg, t0, l_c)
+        cpu_baseline = cpu_oracle_baseline(w.layer, cfg, w.t0, w.l_c)
+    workload = workload_text(w)
+    n_tok = B * w.l_c
 
-    unit = "tokens/s"
-    value = B * l_c / (ms_per_step * 1e-3)
+    decode = None
+    if not args.no_decode and not cfg.decode and B == 1 and not args.seq:
+        del w
+        torch.cuda.empty_cache()
+        decode = decode_record(esa, torch, np, args)
+
+    value = n_tok / (ms_per_step * 1e-3)
+    if cfg.decode:
+        metric = "ESA decode tokens/s per layer at %dk ctx" % (cfg.S // 1024)
+    else:
+        metric = "ESA prefill tokens/s per layer at %dk ctx" % (cfg.S // 1024)
     result = {
-        "metric": "ESA prefill tokens/s per layer at 128k ctx" if not cfg.decode else "ESA decode step",
-        "value": round(value, 1), "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "metric": metric,
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": "%s: H=%d H_kv=%d d=%d, S=%d, chunk l_C=%d at t0=%d, l_I=%d l_L=%d k=%d d_c=%d, "
-                               "%d middle tokens; one step = compress+score+select+gather+attend for one chunk"
-                               % (cfg.name, cfg.H, cfg.H_kv, cfg.d, cfg.S, l_c, t0, cfg.l_I, cfg.l_L, cfg.k,
-                                  cfg.d_c, n_mid),
-                   "global_batch": B, "seq_len": cfg.S, "parallelism": "single GPU"},
-        "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "config": {"workload": workload, "global_batch": B, "seq_len": cfg.S, "parallelism": "single GPU"},
+        "roofline": roofline, "decode": decode, "cpu_baseline": cpu_baseline,
         "launch_mode": mode + (", one stream" if args.single_stream else ", two branches")
-        + (", gather fused into attend" if args.fused_gather else ""), "eager_ms_per_step": round(eager_ms, 4), "setup_s": round(t_gen, 1),
+        + (", gather fused into attend" if args.fused_gather else ""), "eager_ms_per_step": round(eager_ms, 4),
+        "cold_ms_per_step": None if cold_ms is None else round(cold_ms, 4),
     }
     print(json.dumps(result))
 
@@ -353,6 +494,9 @@ def whole_prompt(args, cfg, esa, torch, np):
     W_q, W_k = esa.esa_pack_weights(dev(layer.W_q)), esa.esa_pack_weights(dev(layer.W_k))
     kc = torch.zeros((cfg.S, cfg.d_c), dtype=K.dtype, device="cuda")
     starts = chunk_starts(cfg)
+    # k covers the middle segment in early chunks: every middle token is taken and no scores are read; the
+    # buffer is allocated before the capture so that no fill is recorded into the graph
+    no_scores = torch.empty(max(cfg.k, 1), dtype=torch.float32, device="cuda")
 
     def prefill():
         out = None
@@ -366,25 +510,14 @@ def whole_prompt(args, cfg, esa, torch, np):
                 esa.esa_compress(K[t0:t1], W_k, out=kc[t0:t1])
             ks = vs = None
             if n_mid > 0:
-                if n_mid > cfg.k:
-                    score = esa.esa_score(qc, kc, i_end, l_start)
-                else:   # k covers the middle: every middle token is selected, no scores needed
-                    score = torch.zeros(n_mid, dtype=torch.float32, device="cuda")
+                score = esa.esa_score(qc, kc, i_end, l_start) if n_mid > cfg.k else no_scores[:n_mid]
                 idx = esa.esa_select_topk(score, cfg.k, base=i_end)
                 ks, vs = esa.esa_gather_kv(K, V, idx)
             out = esa.esa_attend(Q[t0:t1], K, V, t0, cfg.l_I, cfg.l_L, ks, vs)
         return out
 
-    def timed(fn, n):
-        torch.cuda.synchronize()
-        t_start = time.perf_counter()
-        for _ in range(n):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t_start) / n
-
     prefill()
-    eager_s = timed(prefill, 2)
+    eager_s = wall_ms(torch, prefill, 2) * 1e-3
     warm = torch.cuda.Stream()
     warm.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(warm):
@@ -394,7 +527,7 @@ def whole_prompt(args, cfg, esa, torch, np):
     with torch.cuda.graph(graph):
         graph_out = prefill()
     graph.replay()
-    graph_s = timed(graph.replay, 3)
+    graph_s = wall_ms(torch, graph.replay, 3) * 1e-3
     ref = prefill()
     torch.cuda.synchronize()
     assert torch.equal(ref, graph_out), "graph replay and eager prefill disagree"

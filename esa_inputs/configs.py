@@ -57,6 +57,10 @@ CONFIGS = {
     # 256k chunked prefill with clustered needles.
     "C5": EsaConfig("C5", "bf16", H=32, H_kv=8, d=128, S=262144, l_I=128, l_L=8192, l_C=1024,
                     k=8192, d_c=128, needles=8, needle_span=32, rope_base=500000.0, seed=5),
+    # Mistral-7B-shaped attention layer (the paper's second model: same head layout, its local length 4096,
+    # rotary base 1e6), 128k chunked prefill.
+    "C6": EsaConfig("C6", "bf16", H=32, H_kv=8, d=128, S=131072, l_I=128, l_L=4096, l_C=512,
+                    k=2048, d_c=128, needles=64, rope_base=1000000.0, seed=6),
 }
 
 

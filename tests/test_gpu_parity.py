@@ -745,7 +745,7 @@ def test_whole_step_with_proximity_influence_selects_the_oracles_set(esa, eps):
         assert np.unique(pooled[g["idx"].cpu().numpy() - i_end]).size < cfg.k // 2
 
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C5", "C4"])
+@pytest.mark.parametrize("name", ["C2", "C3", "C5", "C4", "C6"])
 def test_full_size_last_step_in_the_benchmark_launch_configuration(esa, name):
     """The configurations at their full sizes, last step (the one the benchmark times), launched the
     way the benchmark launches it: packed weights, compressed-key cache filled 16384 tokens at a time.

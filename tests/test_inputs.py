@@ -54,13 +54,16 @@ def test_shapes_and_distributions():
 
 def test_table_of_configurations():
     n_chunks = {n: len(chunk_starts(c)) for n, c in CONFIGS.items()}
-    assert n_chunks == {"C1": 16, "C2": 64, "C3": 256, "C4": 1, "C5": 256}
+    assert n_chunks == {"C1": 16, "C2": 64, "C3": 256, "C4": 1, "C5": 256, "C6": 256}
     c3 = get_config("C3")
     i_end, l_start = segment_bounds(chunk_starts(c3)[-1], c3.l_I, c3.l_L)
     assert l_start - i_end == 128384
     c4 = get_config("C4")
     i_end, l_start = segment_bounds(chunk_starts(c4)[-1], c4.l_I, c4.l_L)
     assert l_start - i_end == 259967 and chunk_starts(c4) == [262143]
+    c6 = get_config("C6")                     # the second model's shape: local length 4096 (Section 4.1, "Parameters")
+    i_end, l_start = segment_bounds(chunk_starts(c6)[-1], c6.l_I, c6.l_L)
+    assert (c6.l_L, c6.k, c6.l_I, c6.d_c) == (4096, 2048, 128, 128) and l_start - i_end == 126336
 
 
 def test_needles_lie_in_the_owning_chunks_middle_and_never_collide():
