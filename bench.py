@@ -31,7 +31,8 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 CALLS = ("compress", "score", "select", "gather", "attend")
-VARIANT_CALLS = ("attend_indexed", "attend_local", "attend_finish", "attend_reencoded")   # timed beside the step
+# timed beside the five calls: the fused form of score + select + gather that the default step uses, and variants
+VARIANT_CALLS = ("score_select_gather", "attend_indexed", "attend_local", "attend_finish", "attend_reencoded")
 
 # HBM bytes per launch from the rocprofv3 counter passes summarised under profiles/ (FETCH_SIZE and
 # WRITE_SIZE per dispatch, each scaled by what the same counter reads for a plain 256 MiB device copy:
@@ -150,6 +151,10 @@ def make_step(esa, torch, w, args, side=None):
             if args.fork_after == "start":
                 fork()
             qc = esa.esa_compress(Q, W_q)
+        if single_stream and not args.separate_calls and not args.fused_gather:
+            # score, select and gather as one call (the same results with three kernels fewer)
+            _, idx, ks, vs = esa.esa_score_select_gather(qc, kc, i_end, l_start, cfg.k, K, V)
+            return esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks, vs)
         # k covers the middle segment in early chunks: every middle token is taken, no scores are read
         score = esa.esa_score(qc, kc, i_end, l_start) if n_mid > cfg.k else no_scores
         if not single_stream and args.fork_after == "score":
@@ -241,6 +246,7 @@ def per_call_times(esa, torch, np, w, args, with_variants):
         "gather": lambda: esa.esa_gather_kv(K, V, idx_s),
         "attend": lambda: esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s),
     }
+    single["score_select_gather"] = lambda: esa.esa_score_select_gather(qc_s, kc, i_end, l_start, cfg.k, K, V)
     if with_variants:
         single.update({
             "attend_indexed": lambda: esa.esa_attend_indexed(Q, K, V, t0, cfg.l_I, cfg.l_L, idx_s),
@@ -301,7 +307,7 @@ def call_report(w, call_ms):
 def workload_text(w):
     cfg = w.cfg
     return ("%s: H=%d H_kv=%d d=%d, S=%d, chunk l_C=%d at t0=%d, l_I=%d l_L=%d k=%d d_c=%d, %d middle tokens; "
-            "one step = compress+score+select+gather+attend for one chunk"
+            "one step = compress, score, select, gather, attend for one chunk"
             % (cfg.name, cfg.H, cfg.H_kv, cfg.d, cfg.S, w.l_c, w.t0, cfg.l_I, cfg.l_L, cfg.k, cfg.d_c, w.n_mid))
 
 
@@ -359,6 +365,9 @@ def main():
                     help="variant: the selection-independent part (key compression, attention over I, L, C) runs on a "
                          "second stream beside select and gather and esa_attend_finish adds the selected keys; measured "
                          "equal to the one-stream step at configuration 3, slower at configuration 5")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="issue esa_score, esa_select_topk and esa_gather_kv as three calls instead of the one fused call "
+                         "esa_score_select_gather (same results, three kernels more)")
     ap.add_argument("--fused-gather", action="store_true",
                     help="variant: esa_attend_indexed follows the indices itself instead of esa_gather_kv + esa_attend "
                          "(four calls; not the default step)")
@@ -473,7 +482,9 @@ def main():
         "config": {"workload": workload, "global_batch": B, "seq_len": cfg.S, "parallelism": "single GPU"},
         "roofline": roofline, "decode": decode, "cpu_baseline": cpu_baseline,
         "launch_mode": mode + (", one stream" if args.single_stream else ", two branches")
-        + (", gather fused into attend" if args.fused_gather else ""), "eager_ms_per_step": round(eager_ms, 4),
+        + (", gather fused into attend" if args.fused_gather else "")
+        + (", five separate calls" if args.separate_calls or not args.single_stream else
+           ("" if args.fused_gather else ", score+select+gather as one call")), "eager_ms_per_step": round(eager_ms, 4),
         "cold_ms_per_step": None if cold_ms is None else round(cold_ms, 4),
     }
     print(json.dumps(result))

@@ -8,7 +8,7 @@ name without the built library raises ImportError.  The binding is loaded on fir
 _BINDING_NAMES = (
     "ESA_F32", "ESA_BF16", "ESA_W_ROWMAJOR", "ESA_W_PACKED", "ESA_SPLIT_I_EARLY", "ESA_SPLIT_ALGORITHM1", "EsaError", "PackedWeights", "EXPORTS", "lib", "lib_path",
     "esa_version", "esa_segments", "esa_pack_weights", "esa_compress", "esa_score", "esa_select_topk", "esa_gather_kv", "esa_attend", "esa_attend_local", "esa_attend_finish", "esa_attend_indexed", "esa_rope", "esa_attend_reencoded", "esa_compress_qk",
-    "esa_select_topk_static", "esa_select_topk_static_capacity", "esa_select_topk_static_prepare",
+    "esa_select_topk_static", "esa_select_topk_static_capacity", "esa_select_topk_static_prepare", "esa_score_select_gather",
 )
 __all__ = list(_BINDING_NAMES)
 

@@ -57,6 +57,11 @@ def _load() -> ctypes.CDLL:
     L.esa_select_topk_workspace_bytes.argtypes = [i64, i32, i32]
     L.esa_select_topk.restype = i32
     L.esa_select_topk.argtypes = [vp, i64, i32, i64, vp, i32, i64, i64, vp, sz, vp]
+    L.esa_score_select_gather_workspace_bytes.restype = sz
+    L.esa_score_select_gather_workspace_bytes.argtypes = [i32, i64, i32, i32]
+    L.esa_score_select_gather.restype = i32
+    L.esa_score_select_gather.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, vp, vp, vp, i64, i32, i32, vp, vp, i32, i32,
+                                          i64, i64, i64, i64, i64, i64, vp, sz, vp]
     L.esa_select_topk_static_capacity.restype = sz
     L.esa_select_topk_static_capacity.argtypes = []
     L.esa_select_topk_static_prepare.restype = i32
@@ -99,7 +104,8 @@ EXPORTS = ("esa_version", "esa_last_error", "esa_segments", "esa_pack_weights", 
            "esa_attend_workspace_bytes", "esa_attend", "esa_attend_local", "esa_attend_finish",
            "esa_attend_indexed_workspace_bytes", "esa_attend_indexed", "esa_rope",
            "esa_attend_reencoded_workspace_bytes", "esa_attend_reencoded", "esa_compress_qk",
-           "esa_select_topk_static_capacity", "esa_select_topk_static_prepare", "esa_select_topk_static")
+           "esa_select_topk_static_capacity", "esa_select_topk_static_prepare", "esa_select_topk_static",
+           "esa_score_select_gather_workspace_bytes", "esa_score_select_gather")
 
 
 def _check(code: int) -> None:
@@ -285,6 +291,43 @@ def esa_select_topk(score: torch.Tensor, k: int, base: int = 0) -> torch.Tensor:
     _check(lib.esa_select_topk(_ptr(sb), n, k, base, _ptr(idx), B, sb.stride(0) if B > 1 else max(n, 1),
                                max(k_eff, 1), _ptr(ws), ws.numel(), _stream()))
     return idx if had_batch else idx[0]
+
+
+def esa_score_select_gather(qc: torch.Tensor, kc_cache: torch.Tensor, m_lo: int, m_hi: int, k: int,
+                            k_cache: Optional[torch.Tensor] = None, v_cache: Optional[torch.Tensor] = None):
+    """esa_score + esa_select_topk (+ esa_gather_kv when the caches are given) in one call.
+    Returns (score or None, idx, k_sel, v_sel); k_sel / v_sel are None without caches."""
+    qb, had_batch = _batched(qc, 2)
+    kb, _ = _batched(kc_cache, 2)
+    B, l_c, d_c = qb.shape
+    assert kb.shape[0] == B and kb.shape[2] == d_c and qb.stride(2) == 1 and kb.stride(2) == 1
+    assert qb.stride(1) == d_c and kb.stride(1) == d_c and kb.dtype == qb.dtype
+    n = m_hi - m_lo
+    k_eff = min(k, max(n, 0))
+    score = torch.empty((B, max(n, 0)), dtype=torch.float32, device=qc.device) if n > k else None
+    idx = torch.empty((B, k_eff), dtype=torch.int32, device=qc.device)
+    ks = vs = kcb = vcb = None
+    tok_stride = h_kv = d = cache_bs = sel_bs = 0
+    if k_cache is not None:
+        kcb, _ = _batched(k_cache, 3)
+        vcb, _ = _batched(v_cache, 3)
+        _, S, h_kv, d = kcb.shape
+        assert vcb.shape == kcb.shape and vcb.stride() == kcb.stride() and kcb.stride(3) == 1 and kcb.stride(2) == d
+        assert kcb.shape[0] == B and kcb.is_cuda
+        ks = torch.empty((B, k_eff, h_kv, d), dtype=k_cache.dtype, device=qc.device)
+        vs = torch.empty_like(ks)
+        tok_stride, cache_bs, sel_bs = kcb.stride(1), kcb.stride(0), k_eff * h_kv * d
+    nbytes = lib.esa_score_select_gather_workspace_bytes(l_c, n, k, B)
+    ws = _workspace(nbytes, qc.device, "score_select")
+    _check(lib.esa_score_select_gather(_ptr(qb), l_c, _ptr(kb), m_lo, m_hi, d_c, k, _ptr(score), _ptr(idx), _ptr(kcb), _ptr(vcb),
+                                       tok_stride, h_kv, d, _ptr(ks), _ptr(vs), _dtype(qc), B, qb.stride(0), kb.stride(0),
+                                       max(n, 1), max(k_eff, 1), cache_bs, sel_bs, _ptr(ws), ws.numel(), _stream()))
+    if not had_batch:
+        score = None if score is None else score[0]
+        idx = idx[0]
+        ks = None if ks is None else ks[0]
+        vs = None if vs is None else vs[0]
+    return score, idx, ks, vs
 
 
 def esa_select_topk_static_capacity() -> int:

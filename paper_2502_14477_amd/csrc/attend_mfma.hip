@@ -292,13 +292,26 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
       for (int v = 0; v < 16; ++v) s[mt][v] = 0.f;
+    // The sixteen K fragments of the tile are requested eight ahead of the matrix instructions that use
+    // them (the order is pinned below): LDS latency is paid once per tile, not once per reduction step.
+    bf16x8 kf[kD / 16][2];
 #pragma unroll
     for (int ks16 = 0; ks16 < kD / 16; ++ks16)
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        const bf16x8 ka = *(const bf16x8*)&kt[(32 * mt + r) * kD + (((2 * ks16 + hi) ^ (r & 15)) << 3)];
-        s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks16], s[mt], 0, 0, 0);
-      }
+      for (int mt = 0; mt < 2; ++mt)
+        kf[ks16][mt] = *(const bf16x8*)&kt[(32 * mt + r) * kD + (((2 * ks16 + hi) ^ (r & 15)) << 3)];
+#pragma unroll
+    for (int ks16 = 0; ks16 < kD / 16; ++ks16)
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+        s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks16][mt], qf[ks16], s[mt], 0, 0, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
 
     // ---- mask keys beyond each query's limit (causal diagonal, end of the slice)
     if (j0 + kKT > lim_lo) {
@@ -367,6 +380,14 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
         const i16x8 both = __builtin_shufflevector(lo, up, 0, 1, 2, 3, 4, 5, 6, 7);
         o[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[kp], o[md], 0, 0, 0);
       }
+    // the V fragments of sixteen keys (eight reads) are requested ahead of the four matrix instructions that use them
+    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
   };
 
   // The first tile's loads go out before the query fragments' so that the two round trips overlap.

@@ -94,13 +94,19 @@ int launch_compress_pair(const void* x0, int64_t d_in0, int64_t ldx0, const void
                          int64_t n_tok, int d_c, int w_layout, int dtype, int batch, hipStream_t st);
 
 size_t score_workspace_bytes(int l_c, int64_t n_mid, int eps, int batch);
+// first_hist: null, or [batch] rows (stride first_hist_bs words) holding the three digit histograms of the
+// selection that follows; when the kernels in use can, they zero all three and fill the first with the
+// leading digits of the scores they write, and *first_hist_done is set.
 int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, int64_t m_hi, int d_c, int eps,
                  float* score, int dtype, int batch, int64_t q_bs, int64_t kc_bs, int64_t score_bs,
-                 void* ws, size_t ws_bytes, hipStream_t st);
+                 void* ws, size_t ws_bytes, hipStream_t st, uint32_t* first_hist = nullptr, int64_t first_hist_bs = 0,
+                 bool* first_hist_done = nullptr);
 
 size_t topk_workspace_bytes(int64_t n, int k, int batch);
+// first_hist_ready: the workspace's histograms are zeroed and the first one already holds the scores'
+// leading digits (left there by launch_score).
 int launch_topk(const float* score, int64_t n, int k, int64_t base, int32_t* idx, int batch, int64_t score_bs,
-                int64_t idx_bs, void* ws, size_t ws_bytes, hipStream_t st);
+                int64_t idx_bs, void* ws, size_t ws_bytes, hipStream_t st, bool first_hist_ready = false);
 
 size_t topk_static_capacity();
 int topk_static_prepare();

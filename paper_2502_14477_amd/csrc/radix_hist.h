@@ -1,0 +1,34 @@
+// First-digit histogram of the radix selection (Eq. 2), shared by the selection kernels and by the
+// score kernels that build it while the scores are still on chip.
+#pragma once
+#include "esa_common.h"
+
+namespace esa {
+
+constexpr int kRadixBins = 2048;        // 11-bit digits (the last pass uses 10 bits of them)
+
+// Workspace of one batch row of the selection, in uint32 words.
+struct TopkLayout {
+  static constexpr int hist = 0;                              // [3][kRadixBins]
+  static constexpr int pick = 3 * kRadixBins;                 // [2][2]: (bin, remaining rank) chosen in the first / second histogram
+  static constexpr int blk = 3 * kRadixBins + 4;              // [2][nblk]: per block, scores above the 22-bit prefix / sharing it
+  // then [nblk][cap] uint16: last digits of the scores sharing the prefix, cap = scores per block
+};
+
+// One LDS-histogram increment per lane, with the lanes of a wave that hit the leader's bin
+// folded into a single atomic (scores of one row share their exponent, so in the first pass
+// almost every lane hits the same bin).  Every lane of the wave must call it.
+__device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t bin) {
+  const uint64_t act = __ballot(active);
+  if (act == 0ull) return;
+  const int leader = __ffsll((long long)act) - 1;
+  const uint32_t lead_bin = __shfl(bin, leader, 64);
+  const uint64_t same = __ballot(active && bin == lead_bin);
+  if ((int)(threadIdx.x & 63) == leader) atomicAdd(&h[lead_bin], (uint32_t)__popcll(same));
+  if (active && bin != lead_bin) atomicAdd(&h[bin], 1u);
+}
+
+// Words of one batch row's selection workspace and the stride between rows (host side).
+int64_t topk_row_stride_words(int64_t n, int batch);
+
+}  // namespace esa

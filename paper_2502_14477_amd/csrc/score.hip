@@ -14,6 +14,7 @@
 // "canonicalises" each operand it cannot prove free of signalling NaNs (a max of the value with
 // itself).  No NaN occurs here (inputs are finite by contract; -inf is only ever compared).
 #include "esa_common.h"
+#include "radix_hist.h"
 
 namespace esa {
 namespace {
@@ -122,22 +123,27 @@ __host__ __device__ inline int64_t mfma_blocks(int64_t n) {
   const int64_t per = mfma_tiles_per_block(n);
   return ((n + 31) / 32 + per - 1) / per;
 }
-__host__ __device__ inline size_t mfma_lds_bytes(int64_t per) {
-  return (size_t)per * 32 * kTileLd * sizeof(bf16_t) + (size_t)per * 32 * sizeof(uint32_t);
+__host__ __device__ inline size_t mfma_lds_bytes(int64_t per) {       // K' share, column maxima, digit histogram
+  return (size_t)per * 32 * kTileLd * sizeof(bf16_t) + (size_t)per * 32 * sizeof(uint32_t) +
+         (size_t)kRadixBins * sizeof(uint32_t);
 }
 
-// PASS 0: partial row maxima into part_max[l_c][blocks].  PASS 1: F into score, using mu[l_c].
+// PASS 0: partial row maxima into part_max[l_c][blocks].  PASS 1: F into score, using mu[l_c]; with
+// first_hist given, also the histogram of the scores' leading 11 key bits (the first digit of the radix
+// selection that follows: the scores are in LDS here, so the selection need not read them for it).
 template <int PASS>
 __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __restrict__ qc, int l_c,
                                                             const bf16_t* __restrict__ kc, int64_t m_lo, int64_t n,
                                                             float* __restrict__ part_max,
                                                             const float* __restrict__ mu_all,
                                                             float* __restrict__ score, int64_t q_bs, int64_t kc_bs,
-                                                            int64_t score_bs, int tiles_per_block) {
+                                                            int64_t score_bs, int tiles_per_block,
+                                                            uint32_t* __restrict__ first_hist, int64_t first_hist_bs) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   const int span = tiles_per_block * 32;                               // tokens of this workgroup
   bf16_t* ktile = (bf16_t*)lds_raw;                                    // [span][kTileLd]
   uint32_t* colmax = (uint32_t*)(lds_raw + (size_t)span * kTileLd * sizeof(bf16_t));   // PASS 1: [span] keys
+  uint32_t* digit_hist = colmax + span;                                // PASS 1: [kRadixBins]
   const int b = blockIdx.y;
   const bf16_t* q = qc + (int64_t)b * q_bs;
   const bf16_t* kmid = kc + (int64_t)b * kc_bs + m_lo * (int64_t)kDc;
@@ -260,8 +266,11 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
   const uint4 p4 = *piece_src(4), p5 = *piece_src(5), p6 = *piece_src(6), p7 = *piece_src(7);
   const uint4 p8 = *piece_src(8), p9 = *piece_src(9), p10 = *piece_src(10), p11 = *piece_src(11);
   const uint4 p12 = *piece_src(12), p13 = *piece_src(13), p14 = *piece_src(14), p15 = *piece_src(15);
-  if (PASS == 1)
+  if (PASS == 1) {
     for (int i = tid; i < span; i += kThreads) colmax[i] = kOrderedKeyOfMinusInf;
+    if (first_hist)
+      for (int i = tid; i < kRadixBins; i += kThreads) digit_hist[i] = 0u;
+  }
   {
     int n_mt = (l_c - wave * kQPerWave + 31) / 32;       // 32-query tiles of this wave that hold a query
     n_mt = n_mt < 0 ? 0 : (n_mt > kMT ? kMT : n_mt);
@@ -301,19 +310,34 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
 
   if (PASS == 1) {
     __syncthreads();
-    for (int i = tid; i < span; i += kThreads) {
+    for (int i0 = 0; i0 < span; i0 += kThreads) {          // whole waves stay in step for hist_add
+      const int i = i0 + tid;
       const int64_t m = tok_base + i;
-      if (m < n) score[(int64_t)b * score_bs + m] = ordered_key_to_f32(colmax[i]);
+      const bool ok = i < span && m < n;
+      const uint32_t key = ok ? colmax[i] : 0u;
+      if (ok) score[(int64_t)b * score_bs + m] = ordered_key_to_f32(key);
+      if (first_hist) hist_add(digit_hist, ok, key >> 21);
+    }
+    if (first_hist) {
+      __syncthreads();
+      uint32_t* gh = first_hist + (int64_t)b * first_hist_bs;
+      for (int i = tid; i < kRadixBins; i += kThreads)
+        if (digit_hist[i]) atomicAdd(&gh[i], digit_hist[i]);
     }
   }
 }
 
 // mu[c] = max over workgroups of their partial row maxima ([l_c][blocks] layout): one wave per query.
+// Running between the two sweeps, it also zeroes the selection's three digit histograms when given them.
 __global__ __launch_bounds__(256) void score_rowmax_reduce(const float* __restrict__ part_max, int nblk, int l_c,
-                                                           float* __restrict__ mu) {
+                                                           float* __restrict__ mu, uint32_t* __restrict__ hists,
+                                                           int64_t hists_bs) {
   const int lane = threadIdx.x & 63;
   const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int b = blockIdx.y;
+  if (hists)
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < 3 * kRadixBins; i += gridDim.x * 256)
+      hists[(int64_t)b * hists_bs + i] = 0u;
   if (c >= l_c) return;
   const float* p = part_max + ((int64_t)b * l_c + c) * nblk;
   float m = -INFINITY;
@@ -354,11 +378,14 @@ template <int LPR>
 __global__ __launch_bounds__(256) void score_gemv_bf16(const bf16_t* __restrict__ qc, const bf16_t* __restrict__ kc,
                                                        int64_t m_lo, int64_t n, float* __restrict__ part,
                                                        float* __restrict__ raw, int64_t q_bs, int64_t kc_bs,
-                                                       int64_t raw_bs) {
+                                                       int64_t raw_bs, uint32_t* __restrict__ hists, int64_t hists_bs) {
   constexpr int kDcv = LPR * 8;
   constexpr int kRowsPerStep = 256 / LPR;
   __shared__ float red[4];
   const int b = blockIdx.y;
+  if (hists)       // the selection's digit histograms, zeroed here for the pass that follows
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < 3 * kRadixBins; i += gridDim.x * 256)
+      hists[(int64_t)b * hists_bs + i] = 0u;
   const bf16_t* kmid = kc + (int64_t)b * kc_bs + m_lo * (int64_t)kDcv;
   const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
   float qv[8];
@@ -398,8 +425,12 @@ __global__ __launch_bounds__(256) void score_gemv_bf16(const bf16_t* __restrict_
 }
 
 __global__ __launch_bounds__(256) void score_sub_mu(float* __restrict__ raw, int64_t n, const float* __restrict__ part,
-                                                    int n_part, int64_t raw_bs) {
+                                                    int n_part, int64_t raw_bs, uint32_t* __restrict__ first_hist,
+                                                    int64_t first_hist_bs) {
   __shared__ float red[4];
+  __shared__ uint32_t digit_hist[kRadixBins];
+  if (first_hist)
+    for (int i = threadIdx.x; i < kRadixBins; i += 256) digit_hist[i] = 0u;
   float* p = raw + (int64_t)blockIdx.y * raw_bs;
   const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
   // this thread's first four scores are requested together with the partial maxima: one round trip
@@ -427,9 +458,26 @@ __global__ __launch_bounds__(256) void score_sub_mu(float* __restrict__ raw, int
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
     const int64_t i = first + u * stride;
-    if (i < n) p[i] = x[u] - mu;
+    const float f = x[u] - mu;
+    if (i < n) p[i] = f;
+    if (first_hist) hist_add(digit_hist, i < n, ordered_key(f) >> 21);
   }
-  for (int64_t i = first + 4 * stride; i < n; i += stride) p[i] = p[i] - mu;
+  // whole waves stay in the loop together (hist_add is a wave-wide operation)
+  for (int64_t i0 = (int64_t)blockIdx.x * blockDim.x + (threadIdx.x & ~63) + 4 * stride; i0 < n; i0 += stride) {
+    const int64_t i = i0 + (threadIdx.x & 63);
+    float f = 0.f;
+    if (i < n) {
+      f = p[i] - mu;
+      p[i] = f;
+    }
+    if (first_hist) hist_add(digit_hist, i < n, ordered_key(f) >> 21);
+  }
+  if (first_hist) {
+    __syncthreads();
+    uint32_t* gh = first_hist + (int64_t)blockIdx.y * first_hist_bs;
+    for (int i = threadIdx.x; i < kRadixBins; i += 256)
+      if (digit_hist[i]) atomicAdd(&gh[i], digit_hist[i]);
+  }
 }
 
 // Eq. 8: out[j] = max(in[max(j-eps,0) .. min(j+eps,n-1)]).
@@ -465,8 +513,10 @@ size_t score_workspace_bytes(int l_c, int64_t n_mid, int eps, int batch) {
 
 int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, int64_t m_hi, int d_c, int eps,
                  float* score, int dtype, int batch, int64_t q_bs, int64_t kc_bs, int64_t score_bs, void* ws,
-                 size_t ws_bytes, hipStream_t st) {
+                 size_t ws_bytes, hipStream_t st, uint32_t* first_hist, int64_t first_hist_bs, bool* first_hist_done) {
   const int64_t n = m_hi - m_lo;
+  if (eps > 0) first_hist = nullptr;      // the pooled scores are written by a later pass
+  if (first_hist_done) *first_hist_done = false;
   uint32_t* mu = (uint32_t*)ws;
   float* raw = score;
   int64_t raw_bs = score_bs;
@@ -484,11 +534,14 @@ int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, in
     const bf16_t* q = (const bf16_t*)qc;
     const bf16_t* k = (const bf16_t*)kc_cache;
     float* part = (float*)((char*)ws + mu_bytes(l_c, batch));
-    if (lpr == 8) score_gemv_bf16<8><<<grid, 256, 0, st>>>(q, k, m_lo, n, part, raw, q_bs, kc_bs, raw_bs);
-    else if (lpr == 16) score_gemv_bf16<16><<<grid, 256, 0, st>>>(q, k, m_lo, n, part, raw, q_bs, kc_bs, raw_bs);
-    else score_gemv_bf16<32><<<grid, 256, 0, st>>>(q, k, m_lo, n, part, raw, q_bs, kc_bs, raw_bs);
+    uint32_t* fh = first_hist;
+    const int64_t fbs = first_hist_bs;
+    if (lpr == 8) score_gemv_bf16<8><<<grid, 256, 0, st>>>(q, k, m_lo, n, part, raw, q_bs, kc_bs, raw_bs, fh, fbs);
+    else if (lpr == 16) score_gemv_bf16<16><<<grid, 256, 0, st>>>(q, k, m_lo, n, part, raw, q_bs, kc_bs, raw_bs, fh, fbs);
+    else score_gemv_bf16<32><<<grid, 256, 0, st>>>(q, k, m_lo, n, part, raw, q_bs, kc_bs, raw_bs, fh, fbs);
     const int blocks = (int)((n + 1023) / 1024 < 2048 ? (n + 1023) / 1024 : 2048);
-    score_sub_mu<<<dim3(blocks, batch), 256, 0, st>>>(raw, n, part, nblk, raw_bs);
+    score_sub_mu<<<dim3(blocks, batch), 256, 0, st>>>(raw, n, part, nblk, raw_bs, fh, fbs);
+    if (fh && first_hist_done) *first_hist_done = true;
   } else if (vec_ok && d_c == kDc) {
     const int per = (int)mfma_tiles_per_block(n);
     const int nblk = (int)mfma_blocks(n);
@@ -507,10 +560,11 @@ int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, in
       lds_limit_raised = true;
     }
     score_mfma_bf16<0><<<grid, kThreads, lds0, st>>>((const bf16_t*)qc, l_c, (const bf16_t*)kc_cache, m_lo, n, part, muf,
-                                                raw, q_bs, kc_bs, raw_bs, per);
-    score_rowmax_reduce<<<dim3((l_c + 3) / 4, batch), 256, 0, st>>>(part, nblk, l_c, muf);
+                                                raw, q_bs, kc_bs, raw_bs, per, nullptr, 0);
+    score_rowmax_reduce<<<dim3((l_c + 3) / 4, batch), 256, 0, st>>>(part, nblk, l_c, muf, first_hist, first_hist_bs);
     score_mfma_bf16<1><<<grid, kThreads, lds1, st>>>((const bf16_t*)qc, l_c, (const bf16_t*)kc_cache, m_lo, n, part, muf,
-                                                raw, q_bs, kc_bs, raw_bs, per);
+                                                raw, q_bs, kc_bs, raw_bs, per, first_hist, first_hist_bs);
+    if (first_hist && first_hist_done) *first_hist_done = true;
   } else {
     fill_u32<<<(l_c * batch + 255) / 256, 256, 0, st>>>(mu, (int64_t)l_c * batch, kOrderedKeyOfMinusInf);
     const dim3 grid((unsigned)((n + kGTok - 1) / kGTok), batch);

@@ -18,6 +18,7 @@
 #include <atomic>
 
 #include "esa_common.h"
+#include "radix_hist.h"
 
 namespace esa {
 namespace {
@@ -25,15 +26,7 @@ namespace {
 constexpr int kThreads = 512;
 constexpr int kItems = 2;                       // consecutive scores per thread
 constexpr int kTile = kThreads * kItems;        // scores per block
-constexpr int kBins = 2048;
-
-// Workspace of one batch row, in uint32 words.
-struct TopkLayout {
-  static constexpr int hist = 0;                         // [3][kBins]
-  static constexpr int pick = 3 * kBins;                 // [2][2]: (bin, remaining rank) chosen in the first / second histogram
-  static constexpr int blk = 3 * kBins + 4;              // [2][nblk]: per block, scores above the 22-bit prefix / sharing it
-  // then [nblk][cap] uint16: last digits of the scores sharing the prefix, cap = scores per block
-};
+constexpr int kBins = kRadixBins;
 
 struct TopkPlan {
   int64_t sub;      // tiles of kTile scores per workgroup
@@ -188,19 +181,6 @@ __device__ __forceinline__ void resolve_prefix(uint32_t* __restrict__ w, uint32_
 __global__ void topk_init(uint32_t* ws, int64_t row_words) {
   uint32_t* w = ws + (int64_t)blockIdx.y * row_words;
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < 3 * kBins; i += gridDim.x * blockDim.x) w[i] = 0u;
-}
-
-// One LDS-histogram increment per lane, with the lanes of a wave that hit the leader's bin
-// folded into a single atomic (scores of one row share their exponent, so in the first pass
-// almost every lane hits the same bin).
-__device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t bin) {
-  const uint64_t act = __ballot(active);
-  if (act == 0ull) return;
-  const int leader = __ffsll((long long)act) - 1;
-  const uint32_t lead_bin = __shfl(bin, leader, 64);
-  const uint64_t same = __ballot(active && bin == lead_bin);
-  if ((int)(threadIdx.x & 63) == leader) atomicAdd(&h[lead_bin], (uint32_t)__popcll(same));
-  if (active && bin != lead_bin) atomicAdd(&h[bin], 1u);
 }
 
 // PASS 0: bits 31..21, PASS 1: bits 20..10, PASS 2: bits 9..0.
@@ -394,7 +374,7 @@ int launch_topk_static(const float* score, int64_t n, int k, int64_t base, int32
   void* ws = nullptr;
   const int rc = static_scratch(&ws);
   if (rc != ESA_OK) return rc;
-  return launch_topk(score, n, k, base, idx, batch, score_bs, idx_bs, ws, kStaticScratchBytes, st);
+  return launch_topk(score, n, k, base, idx, batch, score_bs, idx_bs, ws, kStaticScratchBytes, st, false);
 }
 
 size_t topk_workspace_bytes(int64_t n, int k, int batch) {
@@ -402,8 +382,12 @@ size_t topk_workspace_bytes(int64_t n, int k, int batch) {
   return align_up((size_t)topk_row_words(topk_plan(n, batch)) * sizeof(uint32_t), 256) * (size_t)batch;
 }
 
+int64_t topk_row_stride_words(int64_t n, int batch) {
+  return (int64_t)(align_up((size_t)topk_row_words(topk_plan(n, batch)) * sizeof(uint32_t), 256) / sizeof(uint32_t));
+}
+
 int launch_topk(const float* score, int64_t n, int k, int64_t base, int32_t* idx, int batch, int64_t score_bs,
-                int64_t idx_bs, void* ws, size_t ws_bytes, hipStream_t st) {
+                int64_t idx_bs, void* ws, size_t ws_bytes, hipStream_t st, bool first_hist_ready) {
   if (k >= n) {
     const int blocks = (int)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
     topk_all<<<dim3(blocks, batch), 256, 0, st>>>(n, base, idx, idx_bs);
@@ -412,11 +396,13 @@ int launch_topk(const float* score, int64_t n, int k, int64_t base, int32_t* idx
   }
   const TopkPlan plan = topk_plan(n, batch);
   const int sub = (int)plan.sub, nblk = (int)plan.nblk;
-  const int64_t row_words = (int64_t)(align_up((size_t)topk_row_words(plan) * sizeof(uint32_t), 256) / sizeof(uint32_t));
+  const int64_t row_words = topk_row_stride_words(n, batch);
   uint32_t* w = (uint32_t*)ws;
   const dim3 grid(nblk, batch);
-  topk_init<<<dim3(3, batch), 1024, 0, st>>>(w, row_words);
-  topk_hist<0><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, (uint32_t)k, sub);
+  if (!first_hist_ready) {     // otherwise the score call has zeroed the histograms and filled the first one
+    topk_init<<<dim3(3, batch), 1024, 0, st>>>(w, row_words);
+    topk_hist<0><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, (uint32_t)k, sub);
+  }
   topk_hist<1><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, (uint32_t)k, sub);
   topk_hist<2><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, (uint32_t)k, sub);
   topk_write<<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, base, idx, idx_bs, (uint32_t)k, sub);

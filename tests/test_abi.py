@@ -17,7 +17,7 @@ def _declared():
 
 def test_every_declared_symbol_is_exported_and_bound():
     names = _declared()
-    assert len(names) == 23 and "esa_attend" in names and "esa_select_topk" in names
+    assert len(names) == 25 and "esa_attend" in names and "esa_select_topk" in names
     raw = ctypes.CDLL(esa.lib_path())
     for n in names:
         assert hasattr(raw, n), n

@@ -307,6 +307,72 @@ def test_score_batched_on_the_matrix_core_path_with_proximity_influence(esa):
         assert np.max(np.abs(pooled[b] - orc.proximity(F, eps))) <= F_TOL["bf16"]
 
 
+# ------------------------------------------------------------------------------------------ score + select + gather fused
+@pytest.mark.parametrize("dtype,B,l_c,n,d_c,m_lo,k,h_kv,d,pad", [
+    ("bf16", 1, 512, 30080, 128, 128, 2048, 8, 128, 0),     # matrix-core sweeps, histogram left by the second one
+    ("bf16", 2, 100, 5003, 128, 7, 300, 2, 128, 64),        # batched, ragged share of the last workgroup, padded cache rows
+    ("bf16", 1, 1, 20000, 128, 128, 2048, 8, 128, 0),       # decode: histogram left by the subtract pass
+    ("bf16", 4, 1, 9000, 128, 0, 500, 2, 64, 0),            # decode, batched
+    ("bf16", 1, 700, 70000, 128, 3, 2048, 2, 128, 0),       # more than one block of queries
+    ("bf16", 1, 33, 4097, 64, 0, 64, 2, 64, 4),             # plain score kernel; cache rows not 16-byte aligned
+    ("f32", 2, 16, 3000, 32, 10, 256, 2, 64, 0),            # fp32: plain kernels throughout
+    ("bf16", 1, 64, 900, 128, 5, 2048, 2, 128, 0),          # k covers the middle: nothing is scored
+    ("bf16", 1, 512, 2049, 128, 128, 2048, 8, 128, 0)])     # all but one selected
+def test_score_select_gather_equals_the_three_calls(esa, dtype, B, l_c, n, d_c, m_lo, k, h_kv, d, pad):
+    say(f"fused score+select+gather dtype={dtype} B={B} l_c={l_c} n={n} d_c={d_c} m_lo={m_lo} k={k} h_kv={h_kv} d={d} pad={pad}")
+    rng = np.random.default_rng(l_c * 7 + n + k)
+    S = m_lo + n + 9
+    qc = orc.round_to_storage(rng.standard_normal((B, l_c, d_c)) * 1.5, dtype)
+    kc = orc.round_to_storage(rng.standard_normal((B, S, d_c)), dtype)
+    qd, kd = f64_to_dev(qc, dtype), f64_to_dev(kc, dtype)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    Kbuf = torch.randn((B, S, h_kv * d + pad), generator=torch.Generator().manual_seed(3)).to(tdt).cuda()
+    Vbuf = torch.randn((B, S, h_kv * d + pad), generator=torch.Generator().manual_seed(4)).to(tdt).cuda()
+    Kc, Vc = Kbuf[:, :, :h_kv * d].unflatten(2, (h_kv, d)), Vbuf[:, :, :h_kv * d].unflatten(2, (h_kv, d))
+    if B == 1:
+        qd, kd, Kc, Vc = qd[0], kd[0], Kc[0], Vc[0]
+    score, idx, ks, vs = esa.esa_score_select_gather(qd, kd, m_lo, m_lo + n, k, Kc, Vc)
+    want_score = esa.esa_score(qd, kd, m_lo, m_lo + n)
+    want_idx = esa.esa_select_topk(want_score, k, base=m_lo)
+    want_ks, want_vs = esa.esa_gather_kv(Kc, Vc, want_idx)
+    assert torch.equal(idx, want_idx)
+    assert torch.equal(ks, want_ks) and torch.equal(vs, want_vs)
+    if k < n:
+        assert torch.equal(score, want_score)
+    else:
+        assert score is None
+    # without the gather
+    score2, idx2, ks2, vs2 = esa.esa_score_select_gather(qd, kd, m_lo, m_lo + n, k)
+    assert torch.equal(idx2, want_idx) and ks2 is None and vs2 is None
+    # and against the oracle (first batch element)
+    F = orc.importance(qc[0], kc[0, m_lo:m_lo + n])
+    if k < n:
+        got_F = to_f64(score if B == 1 else score[0])
+        assert np.max(np.abs(got_F - F)) <= F_TOL[dtype]
+        srt = np.sort(F)[::-1]
+        if srt[k - 1] - srt[k] > 4 * F_TOL[dtype]:          # the boundary is clear of rounding: the set is the oracle's
+            assert np.array_equal((idx if B == 1 else idx[0]).cpu().numpy(), orc.select_topk(F, k, base=m_lo))
+
+
+def test_score_select_gather_with_massive_ties(esa):
+    """Identical compressed keys give identical scores: the tie rule (lower position first) decides the
+    whole selection, and the gathering write pass copies long runs of consecutive rows."""
+    say("fused score+select+gather, tied scores")
+    rng = np.random.default_rng(99)
+    l_c, n, d_c, m_lo, k, h_kv, d = 64, 6000, 128, 11, 1500, 2, 128
+    qc = orc.round_to_storage(rng.standard_normal((l_c, d_c)), "bf16")
+    # four distinct compressed keys, each repeated over a quarter of the cache
+    kc = np.repeat(orc.round_to_storage(rng.standard_normal((4, d_c)), "bf16"), (m_lo + n + 3) // 4 + 1, axis=0)[:m_lo + n + 3]
+    Kc = torch.randn((m_lo + n + 3, h_kv, d), generator=torch.Generator().manual_seed(5)).to(torch.bfloat16).cuda()
+    Vc = torch.randn((m_lo + n + 3, h_kv, d), generator=torch.Generator().manual_seed(6)).to(torch.bfloat16).cuda()
+    score, idx, ks, vs = esa.esa_score_select_gather(f64_to_dev(qc, "bf16"), f64_to_dev(kc, "bf16"), m_lo, m_lo + n, k, Kc, Vc)
+    F = orc.importance(qc, kc[m_lo:m_lo + n])
+    assert np.unique(F).size <= 4
+    want = orc.select_topk(to_f64(score), k, base=m_lo)       # ties are exact on both sides: the GPU's own scores decide
+    assert np.array_equal(idx.cpu().numpy(), want)
+    assert torch.equal(ks, Kc[idx.long()]) and torch.equal(vs, Vc[idx.long()])
+
+
 # ------------------------------------------------------------------------------------------ attend
 @pytest.mark.parametrize("dtype,H,H_kv,d,S,t0,l_C,l_I,l_L,n_sel", [
     ("f32", 4, 2, 64, 2048, 1920, 128, 32, 256, 256),
@@ -635,6 +701,8 @@ def test_tiny_layer_full_prefill_fp32(esa):
     n_selecting = 0
     for t0 in steps:
         g = _check_step(esa, layer, dev, kc64, kc_dev, t0)
+        fused = gpu_step(esa, dev, cfg, t0, kc_dev, fused=True)      # one call for score + select + gather
+        assert torch.equal(fused["idx"], g["idx"]) and torch.equal(fused["O"], g["O"])
         n_selecting += g["score"] is not None
         # needles of this chunk (those still in place) are all selected
         if t0 in layer.plan.positions and g["score"] is not None:
@@ -770,31 +838,37 @@ def test_full_size_last_step_in_the_benchmark_launch_configuration(esa, name):
     one = gpu_step(esa, dev, cfg, t0, kc_dev)     # esa_attend in one call: same selection, same output to rounding
     assert torch.equal(one["idx"], g["idx"])
     assert float((one["O"].float() - g["O"].float()).abs().max()) <= O_TOL["bf16"]
+    # score, select and gather as one call (the benchmark's default step): identical to the separate calls
+    fused = gpu_step(esa, dev, cfg, t0, kc_dev, fused=True)
+    assert torch.equal(fused["idx"], one["idx"]) and torch.equal(fused["score"], one["score"])
+    assert torch.equal(fused["k_sel"], one["k_sel"]) and torch.equal(fused["v_sel"], one["v_sel"])
+    assert torch.equal(fused["O"], one["O"])
     needles = np.setdiff1d(layer.plan.positions[t0], replaced)
     assert needles.size and set(needles.tolist()) <= set(g["idx"].cpu().numpy().tolist())
 
 
-def test_step_captured_as_a_graph_replays_identically(esa):
+@pytest.mark.parametrize("fused", [False, True])
+def test_step_captured_as_a_graph_replays_identically(esa, fused):
     """The five calls captured once and replayed, with eager work and synchronisations between the
     replays: every replay must reproduce the eager result bit for bit (nothing in the library
     records a memset node, and no call keeps state between launches)."""
     cfg = get_config("C2").scaled(S=8192)
     layer = make_layer(cfg)
-    say("graph capture of one step, C2-shaped S=8192")
+    say(f"graph capture of one step, C2-shaped S=8192, fused={fused}")
     dev = pack_layer_weights(esa, layer_to_dev(layer))
     t0 = 7680
     kc_dev = esa.esa_compress(dev["K"], dev["W_k"])
-    eager = gpu_step(esa, dev, cfg, t0, kc_dev)
+    eager = gpu_step(esa, dev, cfg, t0, kc_dev, fused=fused)
     torch.cuda.synchronize()
     want_O, want_idx = eager["O"].clone(), eager["idx"].clone()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        gpu_step(esa, dev, cfg, t0, kc_dev)
+        gpu_step(esa, dev, cfg, t0, kc_dev, fused=fused)
     torch.cuda.current_stream().wait_stream(side)
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        g = gpu_step(esa, dev, cfg, t0, kc_dev)
+        g = gpu_step(esa, dev, cfg, t0, kc_dev, fused=fused)
     for rep in range(4):
         g["O"].zero_()
         g["idx"].zero_()
