@@ -128,23 +128,24 @@ ESA_API int esa_select_topk(const float* score, int64_t n, int k, int64_t base,
                     void* workspace, size_t ws_bytes, void* stream);
 
 /*
- * esa_score (eps = 0), esa_select_topk (base = m_lo) and, if wanted, esa_gather_kv in one call, with
- * two kernels fewer than the three calls: the kernel that writes the scores (Eq. 4) also leaves the
- * first digit histogram of the radix selection (Eq. 2) while the scores are still on chip, and the
- * zero-fill of the histograms rides on an earlier kernel of the score call.
+ * esa_score, esa_select_topk (base = m_lo) and, if wanted, esa_gather_kv in one call, with two
+ * kernels fewer than the three calls: the kernel that writes the scores (Eq. 4, or Eq. 8's pooling
+ * pass when eps > 0) also leaves the first digit histogram of the radix selection (Eq. 2) while the
+ * scores are still on chip, and the zero-fill of the histograms rides on an earlier kernel of the
+ * score call.
  * Results are those of the separate calls, bit for bit.
  *   score    [batch][m_hi-m_lo] fp32, written as by esa_score; if k >= m_hi-m_lo every middle token is
  *            selected, nothing is scored and `score` is left untouched (it may then be NULL)
  *   idx      [batch][min(k, m_hi-m_lo)] int32, ascending absolute positions
  *   k_cache, v_cache, k_sel, v_sel, tok_stride, h_kv, d, cache_bs, sel_bs as in esa_gather_kv; pass all
  *            four pointers as NULL to skip the gather
- *   workspace esa_score_select_gather_workspace_bytes(l_c, m_hi-m_lo, k, batch) bytes, 256-byte aligned
+ *   workspace esa_score_select_gather_workspace_bytes(l_c, m_hi-m_lo, eps, k, batch) bytes, 256-byte aligned
  * Shapes outside the fused kernels (fp32, d_c other than 64/128/256) run the kernels of the three
  * calls in sequence.  m_hi == m_lo or k == 0 is a no-op.
  */
-ESA_API size_t esa_score_select_gather_workspace_bytes(int l_c, int64_t n_mid, int k, int batch);
+ESA_API size_t esa_score_select_gather_workspace_bytes(int l_c, int64_t n_mid, int eps, int k, int batch);
 ESA_API int esa_score_select_gather(const void* qc, int l_c,
-                    const void* kc_cache, int64_t m_lo, int64_t m_hi, int d_c, int k,
+                    const void* kc_cache, int64_t m_lo, int64_t m_hi, int d_c, int eps, int k,
                     float* score, int32_t* idx,
                     const void* k_cache, const void* v_cache, int64_t tok_stride, int h_kv, int d,
                     void* k_sel, void* v_sel,

@@ -58,9 +58,9 @@ def _load() -> ctypes.CDLL:
     L.esa_select_topk.restype = i32
     L.esa_select_topk.argtypes = [vp, i64, i32, i64, vp, i32, i64, i64, vp, sz, vp]
     L.esa_score_select_gather_workspace_bytes.restype = sz
-    L.esa_score_select_gather_workspace_bytes.argtypes = [i32, i64, i32, i32]
+    L.esa_score_select_gather_workspace_bytes.argtypes = [i32, i64, i32, i32, i32]
     L.esa_score_select_gather.restype = i32
-    L.esa_score_select_gather.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, vp, vp, vp, i64, i32, i32, vp, vp, i32, i32,
+    L.esa_score_select_gather.argtypes = [vp, i32, vp, i64, i64, i32, i32, i32, vp, vp, vp, vp, i64, i32, i32, vp, vp, i32, i32,
                                           i64, i64, i64, i64, i64, i64, vp, sz, vp]
     L.esa_select_topk_static_capacity.restype = sz
     L.esa_select_topk_static_capacity.argtypes = []
@@ -294,7 +294,7 @@ def esa_select_topk(score: torch.Tensor, k: int, base: int = 0) -> torch.Tensor:
 
 
 def esa_score_select_gather(qc: torch.Tensor, kc_cache: torch.Tensor, m_lo: int, m_hi: int, k: int,
-                            k_cache: Optional[torch.Tensor] = None, v_cache: Optional[torch.Tensor] = None):
+                            k_cache: Optional[torch.Tensor] = None, v_cache: Optional[torch.Tensor] = None, eps: int = 0):
     """esa_score + esa_select_topk (+ esa_gather_kv when the caches are given) in one call.
     Returns (score or None, idx, k_sel, v_sel); k_sel / v_sel are None without caches."""
     qb, had_batch = _batched(qc, 2)
@@ -317,9 +317,9 @@ def esa_score_select_gather(qc: torch.Tensor, kc_cache: torch.Tensor, m_lo: int,
         ks = torch.empty((B, k_eff, h_kv, d), dtype=k_cache.dtype, device=qc.device)
         vs = torch.empty_like(ks)
         tok_stride, cache_bs, sel_bs = kcb.stride(1), kcb.stride(0), k_eff * h_kv * d
-    nbytes = lib.esa_score_select_gather_workspace_bytes(l_c, n, k, B)
+    nbytes = lib.esa_score_select_gather_workspace_bytes(l_c, n, eps, k, B)
     ws = _workspace(nbytes, qc.device, "score_select")
-    _check(lib.esa_score_select_gather(_ptr(qb), l_c, _ptr(kb), m_lo, m_hi, d_c, k, _ptr(score), _ptr(idx), _ptr(kcb), _ptr(vcb),
+    _check(lib.esa_score_select_gather(_ptr(qb), l_c, _ptr(kb), m_lo, m_hi, d_c, eps, k, _ptr(score), _ptr(idx), _ptr(kcb), _ptr(vcb),
                                        tok_stride, h_kv, d, _ptr(ks), _ptr(vs), _dtype(qc), B, qb.stride(0), kb.stride(0),
                                        max(n, 1), max(k_eff, 1), cache_bs, sel_bs, _ptr(ws), ws.numel(), _stream()))
     if not had_batch:

@@ -141,19 +141,19 @@ int esa_select_topk(const float* score, int64_t n, int k, int64_t base, int32_t*
   return launch_topk(score, n, k, base, idx, batch, score_bs, idx_bs, workspace, ws_bytes, (hipStream_t)stream);
 }
 
-size_t esa_score_select_gather_workspace_bytes(int l_c, int64_t n_mid, int k, int batch) {
-  return align_up(score_workspace_bytes(l_c, n_mid, 0, batch), 256) + topk_workspace_bytes(n_mid, k, batch);
+size_t esa_score_select_gather_workspace_bytes(int l_c, int64_t n_mid, int eps, int k, int batch) {
+  return align_up(score_workspace_bytes(l_c, n_mid, eps, batch), 256) + topk_workspace_bytes(n_mid, k, batch);
 }
 
-int esa_score_select_gather(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, int64_t m_hi, int d_c, int k,
-                            float* score, int32_t* idx, const void* k_cache, const void* v_cache, int64_t tok_stride,
+int esa_score_select_gather(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, int64_t m_hi, int d_c, int eps,
+                            int k, float* score, int32_t* idx, const void* k_cache, const void* v_cache, int64_t tok_stride,
                             int h_kv, int d, void* k_sel, void* v_sel, int dtype, int batch, int64_t q_bs,
                             int64_t kc_bs, int64_t score_bs, int64_t idx_bs, int64_t cache_bs, int64_t sel_bs,
                             void* workspace, size_t ws_bytes, void* stream) {
   if (!dtype_ok(dtype)) ESA_FAIL(ESA_EUNSUPPORTED, "esa_score_select_gather: dtype %d", dtype);
-  if (l_c <= 0 || d_c <= 0 || batch <= 0 || batch > kMaxBatch || k < 0 || m_lo < 0 || m_hi < m_lo)
-    ESA_FAIL(ESA_EINVAL, "esa_score_select_gather: bad size (l_c=%d d_c=%d batch=%d k=%d m=[%lld,%lld))", l_c, d_c, batch, k,
-             (long long)m_lo, (long long)m_hi);
+  if (l_c <= 0 || d_c <= 0 || batch <= 0 || batch > kMaxBatch || k < 0 || eps < 0 || m_lo < 0 || m_hi < m_lo)
+    ESA_FAIL(ESA_EINVAL, "esa_score_select_gather: bad size (l_c=%d d_c=%d batch=%d k=%d eps=%d m=[%lld,%lld))", l_c, d_c, batch,
+             k, eps, (long long)m_lo, (long long)m_hi);
   if (d_c % 16 != 0 || d_c > 256) ESA_FAIL(ESA_EUNSUPPORTED, "esa_score_select_gather: d_c=%d (multiple of 16, <= 256)", d_c);
   if (m_hi > (int64_t)INT32_MAX) ESA_FAIL(ESA_EINVAL, "esa_score_select_gather: positions exceed int32");
   const int64_t n = m_hi - m_lo;
@@ -170,18 +170,18 @@ int esa_score_select_gather(const void* qc, int l_c, const void* kc_cache, int64
     if (!aligned(k_cache, es) || !aligned(v_cache, es) || !aligned(k_sel, es) || !aligned(v_sel, es))
       ESA_FAIL(ESA_EINVAL, "esa_score_select_gather: misaligned pointer");
   }
-  const size_t need = esa_score_select_gather_workspace_bytes(l_c, n, k, batch);
+  const size_t need = esa_score_select_gather_workspace_bytes(l_c, n, eps, k, batch);
   if (!workspace || !aligned(workspace, 256) || ws_bytes < need)
     ESA_FAIL(ESA_EWORKSPACE, "esa_score_select_gather: workspace needs %zu bytes, 256-byte aligned", need);
   hipStream_t st = (hipStream_t)stream;
   const int k_eff = (int)(k < n ? k : n);
-  const size_t score_ws = align_up(score_workspace_bytes(l_c, n, 0, batch), 256);
+  const size_t score_ws = align_up(score_workspace_bytes(l_c, n, eps, batch), 256);
   char* topk_ws = (char*)workspace + score_ws;
   bool hist_done = false;
   int rc = ESA_OK;
   if (k < n) {     // otherwise every middle token is taken and no score is needed
     uint32_t* hists = (uint32_t*)topk_ws + TopkLayout::hist;
-    rc = launch_score(qc, l_c, kc_cache, m_lo, m_hi, d_c, 0, score, dtype, batch, q_bs, kc_bs, score_bs, workspace, score_ws,
+    rc = launch_score(qc, l_c, kc_cache, m_lo, m_hi, d_c, eps, score, dtype, batch, q_bs, kc_bs, score_bs, workspace, score_ws,
                       st, hists, topk_row_stride_words(n, batch), &hist_done);
     if (rc != ESA_OK) return rc;
   }

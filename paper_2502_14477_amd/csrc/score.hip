@@ -358,10 +358,10 @@ __global__ __launch_bounds__(256) void score_rowmax_reduce(const float* __restri
 // ------------------------------------------------------------------------------------------ decode (l_c = 1)
 // One current token: S is a matrix-vector product over the whole compressed-key cache, pure HBM
 // streaming.  LPR lanes share a K' row (16 bytes each), so a wave reads 64*16 contiguous bytes per
-// step, eight steps in flight.  Writes S and the workgroup's maximum of it (no atomics: thousands of
+// step; a workgroup covers 256 rows with all its steps' loads in flight.  Writes S and the workgroup's maximum of it (no atomics: thousands of
 // workgroups folding into one word serialise in L2); score_sub_mu then reduces those maxima to mu,
 // every workgroup for itself, and forms F = S - mu.
-constexpr int kGemvSteps = 32;
+constexpr int kGemvRows = 256;           // rows per workgroup
 
 // Sum over groups of LPR consecutive lanes (LPR = 8, 16, 32) with DPP moves; every lane gets the total.
 template <int LPR>
@@ -381,6 +381,7 @@ __global__ __launch_bounds__(256) void score_gemv_bf16(const bf16_t* __restrict_
                                                        int64_t raw_bs, uint32_t* __restrict__ hists, int64_t hists_bs) {
   constexpr int kDcv = LPR * 8;
   constexpr int kRowsPerStep = 256 / LPR;
+  constexpr int kGemvSteps = kGemvRows / kRowsPerStep;
   __shared__ float red[4];
   const int b = blockIdx.y;
   if (hists)       // the selection's digit histograms, zeroed here for the pass that follows
@@ -397,8 +398,8 @@ __global__ __launch_bounds__(256) void score_gemv_bf16(const bf16_t* __restrict_
     qv[6] = __uint_as_float(u.w << 16); qv[7] = __uint_as_float(u.w & 0xFFFF0000u);
   }
   float best = -INFINITY;
-  const int64_t row0 = (int64_t)blockIdx.x * (kRowsPerStep * kGemvSteps);
-#pragma unroll 8
+  const int64_t row0 = (int64_t)blockIdx.x * kGemvRows;
+#pragma unroll
   for (int it = 0; it < kGemvSteps; ++it) {
     const int64_t row = row0 + it * kRowsPerStep + grp;
     uint4 u = make_uint4(0u, 0u, 0u, 0u);
@@ -462,15 +463,21 @@ __global__ __launch_bounds__(256) void score_sub_mu(float* __restrict__ raw, int
     if (i < n) p[i] = f;
     if (first_hist) hist_add(digit_hist, i < n, ordered_key(f) >> 21);
   }
-  // whole waves stay in the loop together (hist_add is a wave-wide operation)
-  for (int64_t i0 = (int64_t)blockIdx.x * blockDim.x + (threadIdx.x & ~63) + 4 * stride; i0 < n; i0 += stride) {
-    const int64_t i = i0 + (threadIdx.x & 63);
-    float f = 0.f;
-    if (i < n) {
-      f = p[i] - mu;
-      p[i] = f;
+  // whole waves stay in the loop together (hist_add is a wave-wide operation); four scores in flight per lane
+  for (int64_t i0 = (int64_t)blockIdx.x * blockDim.x + (threadIdx.x & ~63) + 4 * stride; i0 < n; i0 += 4 * stride) {
+    float y[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t i = i0 + u * stride + (threadIdx.x & 63);
+      y[u] = i < n ? p[i] : 0.f;
     }
-    if (first_hist) hist_add(digit_hist, i < n, ordered_key(f) >> 21);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t i = i0 + u * stride + (threadIdx.x & 63);
+      const float f = y[u] - mu;
+      if (i < n) p[i] = f;
+      if (first_hist) hist_add(digit_hist, i < n, ordered_key(f) >> 21);
+    }
   }
   if (first_hist) {
     __syncthreads();
@@ -480,16 +487,34 @@ __global__ __launch_bounds__(256) void score_sub_mu(float* __restrict__ raw, int
   }
 }
 
-// Eq. 8: out[j] = max(in[max(j-eps,0) .. min(j+eps,n-1)]).
-__global__ void proximity_maxpool(const float* __restrict__ in, float* __restrict__ out, int64_t n, int eps,
-                                  int64_t in_bs, int64_t out_bs) {
+// Eq. 8: out[j] = max(in[max(j-eps,0) .. min(j+eps,n-1)]).  With first_hist given, also the histogram of the
+// pooled scores' leading 11 key bits (this is the kernel that writes the scores the selection reads).
+__global__ __launch_bounds__(256) void proximity_maxpool(const float* __restrict__ in, float* __restrict__ out, int64_t n,
+                                                         int eps, int64_t in_bs, int64_t out_bs,
+                                                         uint32_t* __restrict__ first_hist, int64_t first_hist_bs) {
+  __shared__ uint32_t digit_hist[kRadixBins];
+  if (first_hist)
+    for (int i = threadIdx.x; i < kRadixBins; i += 256) digit_hist[i] = 0u;
+  __syncthreads();
   const float* src = in + (int64_t)blockIdx.y * in_bs;
   float* dst = out + (int64_t)blockIdx.y * out_bs;
-  for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += (int64_t)gridDim.x * blockDim.x) {
-    const int64_t lo = j - eps > 0 ? j - eps : 0, hi = j + eps < n - 1 ? j + eps : n - 1;
-    float m = src[lo];
-    for (int64_t w = lo + 1; w <= hi; ++w) m = fmaxf(m, src[w]);
-    dst[j] = m;
+  // whole waves stay in the loop together (hist_add is a wave-wide operation)
+  for (int64_t j0 = (int64_t)blockIdx.x * 256 + (threadIdx.x & ~63); j0 < n; j0 += (int64_t)gridDim.x * 256) {
+    const int64_t j = j0 + (threadIdx.x & 63);
+    float m = 0.f;
+    if (j < n) {
+      const int64_t lo = j - eps > 0 ? j - eps : 0, hi = j + eps < n - 1 ? j + eps : n - 1;
+      m = src[lo];
+      for (int64_t w = lo + 1; w <= hi; ++w) m = fmaxf(m, src[w]);
+      dst[j] = m;
+    }
+    if (first_hist) hist_add(digit_hist, j < n, ordered_key(m) >> 21);
+  }
+  if (first_hist) {
+    __syncthreads();
+    uint32_t* gh = first_hist + (int64_t)blockIdx.y * first_hist_bs;
+    for (int i = threadIdx.x; i < kRadixBins; i += 256)
+      if (digit_hist[i]) atomicAdd(&gh[i], digit_hist[i]);
   }
 }
 
@@ -515,7 +540,10 @@ int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, in
                  float* score, int dtype, int batch, int64_t q_bs, int64_t kc_bs, int64_t score_bs, void* ws,
                  size_t ws_bytes, hipStream_t st, uint32_t* first_hist, int64_t first_hist_bs, bool* first_hist_done) {
   const int64_t n = m_hi - m_lo;
-  if (eps > 0) first_hist = nullptr;      // the pooled scores are written by a later pass
+  // With pooling the kernel that writes the final scores is the pooling pass: the kernels before it only zero
+  // the histograms (pool_hist), it fills the first one.
+  uint32_t* pool_hist = eps > 0 ? first_hist : nullptr;
+  bool zeroed = false;
   if (first_hist_done) *first_hist_done = false;
   uint32_t* mu = (uint32_t*)ws;
   float* raw = score;
@@ -528,20 +556,20 @@ int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, in
                       kc_bs % 8 == 0;
   if (vec_ok && l_c == 1 && (d_c == 64 || d_c == 128 || d_c == 256)) {
     const int lpr = d_c / 8;
-    const int rows_per_block = (256 / lpr) * kGemvSteps;
-    const int nblk = (int)((n + rows_per_block - 1) / rows_per_block);
+    const int nblk = (int)((n + kGemvRows - 1) / kGemvRows);
     const dim3 grid((unsigned)nblk, batch);
     const bf16_t* q = (const bf16_t*)qc;
     const bf16_t* k = (const bf16_t*)kc_cache;
     float* part = (float*)((char*)ws + mu_bytes(l_c, batch));
     uint32_t* fh = first_hist;
     const int64_t fbs = first_hist_bs;
+    zeroed = fh != nullptr;
     if (lpr == 8) score_gemv_bf16<8><<<grid, 256, 0, st>>>(q, k, m_lo, n, part, raw, q_bs, kc_bs, raw_bs, fh, fbs);
     else if (lpr == 16) score_gemv_bf16<16><<<grid, 256, 0, st>>>(q, k, m_lo, n, part, raw, q_bs, kc_bs, raw_bs, fh, fbs);
     else score_gemv_bf16<32><<<grid, 256, 0, st>>>(q, k, m_lo, n, part, raw, q_bs, kc_bs, raw_bs, fh, fbs);
     const int blocks = (int)((n + 1023) / 1024 < 2048 ? (n + 1023) / 1024 : 2048);
-    score_sub_mu<<<dim3(blocks, batch), 256, 0, st>>>(raw, n, part, nblk, raw_bs, fh, fbs);
-    if (fh && first_hist_done) *first_hist_done = true;
+    score_sub_mu<<<dim3(blocks, batch), 256, 0, st>>>(raw, n, part, nblk, raw_bs, pool_hist ? nullptr : fh, fbs);
+    if (fh && !pool_hist && first_hist_done) *first_hist_done = true;
   } else if (vec_ok && d_c == kDc) {
     const int per = (int)mfma_tiles_per_block(n);
     const int nblk = (int)mfma_blocks(n);
@@ -563,8 +591,10 @@ int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, in
                                                 raw, q_bs, kc_bs, raw_bs, per, nullptr, 0);
     score_rowmax_reduce<<<dim3((l_c + 3) / 4, batch), 256, 0, st>>>(part, nblk, l_c, muf, first_hist, first_hist_bs);
     score_mfma_bf16<1><<<grid, kThreads, lds1, st>>>((const bf16_t*)qc, l_c, (const bf16_t*)kc_cache, m_lo, n, part, muf,
-                                                raw, q_bs, kc_bs, raw_bs, per, first_hist, first_hist_bs);
-    if (first_hist && first_hist_done) *first_hist_done = true;
+                                                raw, q_bs, kc_bs, raw_bs, per, pool_hist ? nullptr : first_hist,
+                                                first_hist_bs);
+    zeroed = first_hist != nullptr;
+    if (first_hist && !pool_hist && first_hist_done) *first_hist_done = true;
   } else {
     fill_u32<<<(l_c * batch + 255) / 256, 256, 0, st>>>(mu, (int64_t)l_c * batch, kOrderedKeyOfMinusInf);
     const dim3 grid((unsigned)((n + kGTok - 1) / kGTok), batch);
@@ -591,7 +621,9 @@ int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, in
   }
   if (eps > 0) {
     const int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
-    proximity_maxpool<<<dim3(blocks, batch), 256, 0, st>>>(raw, score, n, eps, raw_bs, score_bs);
+    uint32_t* ph = zeroed ? pool_hist : nullptr;       // only behind kernels that have zeroed the histograms
+    proximity_maxpool<<<dim3(blocks, batch), 256, 0, st>>>(raw, score, n, eps, raw_bs, score_bs, ph, first_hist_bs);
+    if (ph && first_hist_done) *first_hist_done = true;
   }
   ESA_LAUNCH_CHECK("score");
   return ESA_OK;

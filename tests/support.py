@@ -60,7 +60,7 @@ def gpu_step(esa, dev, cfg, t0, kc_dev=None, two_calls=False, eps=0, fused=False
     n_mid = l_start - i_end
     out = {"qc": qc, "kc": kc_dev, "score": None}
     if n_mid > 0 and fused:
-        out["score"], idx, ks, vs = esa.esa_score_select_gather(qc, kc_dev, i_end, l_start, cfg.k, dev["K"], dev["V"])
+        out["score"], idx, ks, vs = esa.esa_score_select_gather(qc, kc_dev, i_end, l_start, cfg.k, dev["K"], dev["V"], eps=eps)
     elif n_mid > 0:
         if n_mid > cfg.k:
             out["score"] = esa.esa_score(qc, kc_dev, i_end, l_start, eps=eps)

@@ -354,6 +354,30 @@ def test_score_select_gather_equals_the_three_calls(esa, dtype, B, l_c, n, d_c, 
             assert np.array_equal((idx if B == 1 else idx[0]).cpu().numpy(), orc.select_topk(F, k, base=m_lo))
 
 
+@pytest.mark.parametrize("B,l_c,n,d_c,eps", [(1, 512, 30080, 128, 3), (2, 1, 20000, 128, 2), (1, 33, 4097, 64, 1), (1, 16, 3000, 32, 5)])
+def test_score_select_gather_with_proximity_influence_equals_the_three_calls(esa, B, l_c, n, d_c, eps):
+    """Eq. 8 inside the fused call: the pooling pass leaves the selection's first histogram."""
+    say(f"fused score+select+gather with eps={eps}: B={B} l_c={l_c} n={n} d_c={d_c}")
+    rng = np.random.default_rng(n + eps)
+    dtype = "f32" if d_c == 32 else "bf16"
+    m_lo, k, h_kv, d = 9, 700, 2, 128
+    qc = orc.round_to_storage(rng.standard_normal((B, l_c, d_c)) * 1.5, dtype)
+    kc = orc.round_to_storage(rng.standard_normal((B, m_lo + n + 4, d_c)), dtype)
+    qd, kd = f64_to_dev(qc, dtype), f64_to_dev(kc, dtype)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    Kc = torch.randn((B, m_lo + n + 4, h_kv, d), generator=torch.Generator().manual_seed(7)).to(tdt).cuda()
+    Vc = torch.randn((B, m_lo + n + 4, h_kv, d), generator=torch.Generator().manual_seed(8)).to(tdt).cuda()
+    score, idx, ks, vs = esa.esa_score_select_gather(qd, kd, m_lo, m_lo + n, k, Kc, Vc, eps=eps)
+    want_score = esa.esa_score(qd, kd, m_lo, m_lo + n, eps=eps)
+    want_idx = esa.esa_select_topk(want_score, k, base=m_lo)
+    want_ks, want_vs = esa.esa_gather_kv(Kc, Vc, want_idx)
+    assert torch.equal(score, want_score) and torch.equal(idx, want_idx)
+    assert torch.equal(ks, want_ks) and torch.equal(vs, want_vs)
+    for b in range(B):
+        F = orc.proximity(orc.importance(qc[b], kc[b, m_lo:m_lo + n]), eps)
+        assert np.max(np.abs(to_f64(score[b]) - F)) <= F_TOL[dtype]
+
+
 def test_score_select_gather_with_massive_ties(esa):
     """Identical compressed keys give identical scores: the tie rule (lower position first) decides the
     whole selection, and the gathering write pass copies long runs of consecutive rows."""
@@ -807,6 +831,8 @@ def test_whole_step_with_proximity_influence_selects_the_oracles_set(esa, eps):
     kc_dev = esa.esa_compress(dev["K"], dev["W_k"])
     for t0 in steps:
         g = _check_step(esa, layer, dev, kc64, kc_dev, t0, eps=eps)
+        fused = gpu_step(esa, dev, cfg, t0, kc_dev, eps=eps, fused=True)      # pooling inside the fused call
+        assert torch.equal(fused["idx"], g["idx"]) and torch.equal(fused["score"], g["score"])
         # the pooled scores are full of exact ties: fewer distinct values than tokens among the selected
         pooled = to_f64(g["score"])
         i_end, _ = segment_bounds(t0, cfg.l_I, cfg.l_L)
