@@ -14,6 +14,7 @@
 // "canonicalises" each operand it cannot prove free of signalling NaNs (a max of the value with
 // itself).  No NaN occurs here (inputs are finite by contract; -inf is only ever compared).
 #include "esa_common.h"
+#include <type_traits>
 #include "radix_hist.h"
 
 namespace esa {
@@ -21,7 +22,9 @@ namespace {
 
 // Workspace: [batch][l_c] row maxima (uint32 keys or fp32), [batch][blocks][l_c] fp32 partial row maxima of the
 // matrix-core kernel, then (eps > 0) [batch][n] fp32 unpooled scores.
-__host__ __device__ inline size_t mu_bytes(int l_c, int batch) { return align_up((size_t)l_c * batch * 4, 256); }
+__host__ __device__ inline size_t mu_bytes(int l_c, int batch) {      // rows padded to whole groups of 64
+  return align_up((size_t)((l_c + 63) / 64 * 64) * batch * 4, 256);
+}
 
 __global__ void fill_u32(uint32_t* p, int64_t n, uint32_t v) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
@@ -85,24 +88,45 @@ __global__ __launch_bounds__(256) void score_fma(const T* __restrict__ qc, int l
 // ------------------------------------------------------------------------------------------ MFMA (bf16, d_c = 128)
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 // v_mfma_f32_32x32x16_bf16 computes D[32x32] += A[32x16] B[16x32].  Lane l supplies eight
 // consecutive reduction elements of A row l%32 and of B column l%32 (which eight depends only on
 // l/32, identically for A and B), and owns D[8*(v/4) + 4*(l/32) + v%4][l%32] in register v.
 //
 // Here A rows are current tokens (queries), B columns are middle tokens.  A workgroup of eight
-// waves (two per SIMD, so one wave's maximum/subtract work overlaps the other's matrix
-// instructions) owns up to 512 consecutive middle tokens.  Its whole share of K' (at most 128 KB)
-// is brought into LDS in ONE round trip — sixteen 16-byte loads per thread issued back to back,
-// full 256-byte rows per 16 lanes — and stays there; after a single barrier the kernel runs
-// without further global loads or barriers.  Queries are the register-resident operand (64 per
-// wave as A fragments for the whole d_c = 128; chunks longer than 512 loop over query blocks
-// against the same LDS tile), so K' is read from memory once per sweep.  With a token per lane,
-// the column maximum of Eq. 4 is an in-lane reduction over the accumulator registers plus one
-// exchange between the two half-waves, folded across waves with an LDS integer maximum on
-// order-preserving keys; the row maximum is kept per register across all tiles and reduced
-// across lanes once, then written as this workgroup's partial row maxima (no atomics across
-// workgroups) for score_rowmax_reduce.
+// waves (two per SIMD) owns up to 512 consecutive middle tokens.  Its whole share of K' (at most
+// 128 KB) goes from memory straight into LDS, without passing through registers: sixteen
+// global_load_lds_dwordx4 per thread, issued back to back at the start of the kernel, each wave
+// instruction bringing four 256-byte rows.  Which 16 bytes of its row a lane fetches is chosen such
+// that the rows land XOR-swizzled (piece p of row R in slot p ^ R%16), which makes the fragment
+// reads free of bank conflicts without padding.  Loads complete in order, so tile t (32 tokens,
+// instruction t of every wave) is usable once every wave has waited for its own instruction t and
+// a barrier has passed; the tiles are consumed as they land, two per barrier.  Queries are the
+// register-resident operand (64 per wave as A fragments for the whole d_c = 128; chunks longer than
+// 512 loop over query blocks against the same LDS tile), so K' is read from memory once per sweep.
+//
+// Inside a wave the tiles are software-pipelined: right after the matrix instructions of reduction
+// step ks of tile t have issued, fragment ks of tile t+1 is read from LDS into the registers they
+// have just released, and the maximum / subtract work on tile t-1's accumulators (a second
+// accumulator set) sits between the matrix instructions, so that one wave alone keeps the matrix
+// pipe fed.  With a token per lane, the column maximum of Eq. 4 is an in-lane reduction over the
+// accumulator registers plus one exchange between the two half-waves, folded across waves with an
+// LDS integer maximum on order-preserving keys; the row maximum is kept per register across all
+// tiles and reduced across lanes once, then written as this workgroup's partial row maxima (no
+// atomics across workgroups) for score_rowmax_reduce.
+//
+// While the share is landing, every LDS access of the tile loop is written as an instruction of its
+// own with its own counter waits: an LDS access the compiler generates is preceded by a wait for ALL
+// outstanding loads into LDS (it cannot tell which rows they fill), which would turn the stream into
+// one round trip followed by the arithmetic.  LDS operations complete in order, which the waits
+// below rely on: "at most 7 outstanding" before the use of fragment ks means that fragment has
+// arrived, because exactly seven fragment reads were issued after it (the rest of this tile's and the
+// first ks of the next tile's).  Operations the compiler adds on the same counter are newer still
+// and only make these waits stricter.
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+typedef __attribute__((address_space(1))) const void global_void;
 constexpr int kDc = 128;
 constexpr int kKSteps = kDc / 16;        // MFMA reduction steps per tile
 constexpr int kWaves = 8;
@@ -110,25 +134,39 @@ constexpr int kThreads = 64 * kWaves;
 constexpr int kMT = 2;                   // 32-query tiles per wave
 constexpr int kQPerWave = 32 * kMT;
 constexpr int kQPerBlock = kWaves * kQPerWave;
-constexpr int kTileLd = kDc + 8;         // LDS row stride in elements (272 B: conflict-free 16-byte reads)
-constexpr int kMaxTilesPerBlock = 16;    // 512 tokens: 136 KB of LDS
-constexpr int kPieces = kMaxTilesPerBlock * 32 * 16 / kThreads;   // 16-byte pieces per thread (16)
+constexpr int kMaxTilesPerBlock = 16;    // 512 tokens: 128 KB of LDS; one load instruction per thread and tile
+constexpr int kTileBytes = 32 * kDc * 2; // one tile of K' in LDS
 
 __host__ __device__ inline int64_t mfma_tiles_per_block(int64_t n) {
   const int64_t n_tiles = (n + 31) / 32;
-  const int64_t per = (n_tiles + 255) / 256;   // about one workgroup per compute unit
-  return per < 1 ? 1 : (per > kMaxTilesPerBlock ? kMaxTilesPerBlock : per);
+  const int64_t per = ((n_tiles + 255) / 256 + 1) / 2 * 2;   // about one workgroup per compute unit; even
+  return per < 2 ? 2 : (per > kMaxTilesPerBlock ? kMaxTilesPerBlock : per);
 }
 __host__ __device__ inline int64_t mfma_blocks(int64_t n) {
   const int64_t per = mfma_tiles_per_block(n);
   return ((n + 31) / 32 + per - 1) / per;
 }
-__host__ __device__ inline size_t mfma_lds_bytes(int64_t per) {       // K' share, column maxima, digit histogram
-  return (size_t)per * 32 * kTileLd * sizeof(bf16_t) + (size_t)per * 32 * sizeof(uint32_t) +
-         (size_t)kRadixBins * sizeof(uint32_t);
+// K' share, column maxima, digit histogram
+__host__ __device__ inline size_t mfma_lds_bytes(int64_t per) {
+  return (size_t)per * kTileBytes + (size_t)(per + 1) * 32 * sizeof(uint32_t) + (size_t)kRadixBins * sizeof(uint32_t);
+}
+// Row maxima of the matrix-core path: one row of mfma_mu_stride(l_c) floats per batch entry, so that groups
+// of four are 16-byte aligned and in bounds for every query tile that holds a query.
+__host__ __device__ inline int mfma_mu_stride(int l_c) { return (l_c + 63) / 64 * 64; }
+
+// Wait until at most `left` (14, 12, 8 or 0) vector-memory loads of this wave are outstanding, then the
+// workgroup barrier.  Only the first one (14) also waits for the LDS operations issued before it, the
+// initialising writes; in the tile loop the fragment reads in flight stay in flight across the barrier.
+__device__ __forceinline__ void wait_loads_then_barrier(int left) {
+  switch (left) {
+    case 0: asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory"); break;
+    case 8: asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory"); break;
+    case 12: asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory"); break;
+    default: asm volatile("s_waitcnt vmcnt(14) lgkmcnt(0)\n\ts_barrier" ::: "memory"); break;
+  }
 }
 
-// PASS 0: partial row maxima into part_max[l_c][blocks].  PASS 1: F into score, using mu[l_c]; with
+// PASS 0: partial row maxima into part_max[l_c][blocks].  PASS 1: F into score, using mu; with
 // first_hist given, also the histogram of the scores' leading 11 key bits (the first digit of the radix
 // selection that follows: the scores are in LDS here, so the selection need not read them for it).
 template <int PASS>
@@ -139,86 +177,178 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
                                                             float* __restrict__ score, int64_t q_bs, int64_t kc_bs,
                                                             int64_t score_bs, int tiles_per_block,
                                                             uint32_t* __restrict__ first_hist, int64_t first_hist_bs) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  const int span = tiles_per_block * 32;                               // tokens of this workgroup
-  bf16_t* ktile = (bf16_t*)lds_raw;                                    // [span][kTileLd]
-  uint32_t* colmax = (uint32_t*)(lds_raw + (size_t)span * kTileLd * sizeof(bf16_t));   // PASS 1: [span] keys
-  uint32_t* digit_hist = colmax + span;                                // PASS 1: [kRadixBins]
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
+  const int tpb = tiles_per_block;
+  const int span = tpb * 32;                                           // tokens of this workgroup
+  uint32_t* colmax = (uint32_t*)(lds_raw + (size_t)tpb * kTileBytes);  // PASS 1: [32 spare + span] keys
+  uint32_t* digit_hist = colmax + 32 + span;                           // PASS 1: [kRadixBins]
   const int b = blockIdx.y;
   const bf16_t* q = qc + (int64_t)b * q_bs;
-  const bf16_t* kmid = kc + (int64_t)b * kc_bs + m_lo * (int64_t)kDc;
-  const float* mu = mu_all + (int64_t)b * l_c;
-  const bool mu_vec = (((int64_t)b * l_c) & 3) == 0;     // 16-byte aligned groups of four row maxima
+  const int mu_stride = mfma_mu_stride(l_c);
+  const float* mu = mu_all + (int64_t)b * mu_stride;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, hi = lane >> 5;
   const int64_t tok_base = (int64_t)blockIdx.x * span;
-  const int n_tiles_here = (int)(((n - tok_base < span ? n - tok_base : span) + 31) / 32);
+  const char* kshare = (const char*)(kc + (int64_t)b * kc_bs + (m_lo + tok_base) * (int64_t)kDc);
+  const uint32_t last_row = (uint32_t)(n - tok_base - 1 < span - 1 ? n - tok_base - 1 : span - 1);
+  const uint32_t lds_tiles = (uint32_t)(uintptr_t)(lds_byte*)lds_raw;  // LDS byte address of the share
+  const uint32_t lds_colmax = lds_tiles + (uint32_t)tpb * kTileBytes;
 
   bf16x8 a[kMT][kKSteps];
   float aux[kMT][16];                    // PASS 0: running row maxima.  PASS 1: mu of the lane's rows.
-  auto load_query_block = [&](int qb) {
+  // Rows past the chunk repeat its last query: a repeated row changes no maximum, and its own results
+  // are never written (PASS 0) or are pushed to -inf by mu = +inf (PASS 1).  Register v of tile mt
+  // belongs to row 8*(v/4) + 4*hi + v%4 of the tile.
+  //
+  // The requests for the fragments and (PASS 1) the row maxima are instructions written out here, and so
+  // is the wait that ends them (queries_arrived): had the compiler generated the loads, its own wait for them
+  // would be a wait for everything once loads into LDS are outstanding behind them (it does not count on
+  // those completing in order with ordinary loads), which would put a round trip in front of the share's
+  // requests.  Between request and wait the registers are only named by that wait.
+  f32x4 mu4[kMT][4];
+  int qb_now = 0;
+  auto wave_has_queries = [&](int qb) { return qb * kQPerBlock + wave * kQPerWave < l_c; };
+  auto request_query_block = [&](int qb) {
     const int q0 = qb * kQPerBlock + wave * kQPerWave;
+    if (!wave_has_queries(qb)) {          // a wave without queries only takes part in the loads and barriers
+#pragma unroll
+      for (int mt = 0; mt < kMT; ++mt) {
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks) a[mt][ks] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) mu4[mt][g4] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      }
+      return;
+    }
 #pragma unroll
     for (int mt = 0; mt < kMT; ++mt) {
-      const int row = q0 + 32 * mt + r;
-      const bool ok = row < l_c;
-      const bf16_t* p = q + (int64_t)(ok ? row : 0) * kDc + hi * 8;
+      int row = q0 + 32 * mt + r;
+      row = row < l_c ? row : l_c - 1;
+      const bf16_t* p = q + (int64_t)row * kDc + hi * 8;
 #pragma unroll
-      for (int ks = 0; ks < kKSteps; ++ks) {
-        bf16x8 v = *(const bf16x8*)(p + ks * 16);
-        if (!ok) v = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
-        a[mt][ks] = v;
-      }
+      for (int ks = 0; ks < kKSteps; ++ks)
+        asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(a[mt][ks]) : "v"(p), "n"(ks * 32));
+      if (PASS == 1) {
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const int qrow = q0 + 32 * mt + 8 * g4 + 4 * hi;    // rows qrow .. qrow+3 live in registers 4*g4 .. 4*g4+3
-        if (PASS == 0) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) aux[mt][4 * g4 + e] = -INFINITY;
-        } else if (mu_vec && qrow + 4 <= l_c) {
-          const float4 m4 = *(const float4*)(mu + qrow);
-          aux[mt][4 * g4 + 0] = m4.x;
-          aux[mt][4 * g4 + 1] = m4.y;
-          aux[mt][4 * g4 + 2] = m4.z;
-          aux[mt][4 * g4 + 3] = m4.w;
-        } else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) aux[mt][4 * g4 + e] = (qrow + e < l_c) ? mu[qrow + e] : INFINITY;
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int qrow = q0 + 32 * mt + 8 * g4 + 4 * hi;
+          const float* mp = mu + (qrow < mu_stride - 4 ? qrow : mu_stride - 4);
+          asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(mu4[mt][g4]) : "v"(mp));
         }
       }
     }
   };
-
-  // One 32-token tile against this wave's queries.
-  auto compute_tile = [&](int nt) {
-    bf16x8 bfr[kKSteps];
-#pragma unroll
-    for (int ks = 0; ks < kKSteps; ++ks)
-      bfr[ks] = *(const bf16x8*)&ktile[(32 * nt + r) * kTileLd + 16 * ks + 8 * hi];
-    f32x16 acc[kMT];
+#define ESA_QUERY_REGS(mt)                                                                                     \
+  "+v"(a[mt][0]), "+v"(a[mt][1]), "+v"(a[mt][2]), "+v"(a[mt][3]), "+v"(a[mt][4]), "+v"(a[mt][5]), "+v"(a[mt][6]), \
+      "+v"(a[mt][7])
+#define ESA_MU_REGS(mt) "+v"(mu4[mt][0]), "+v"(mu4[mt][1]), "+v"(mu4[mt][2]), "+v"(mu4[mt][3])
+  // Everything requested before the share has arrived once at most fourteen of the share's sixteen requests
+  // are outstanding (first block; tiles 0 and 1 are in LDS then as well), or nothing at all (later blocks).
+  auto queries_arrived = [&](bool first) {
+    if (PASS == 0) {
+      if (first) asm volatile("s_waitcnt vmcnt(14)" : ESA_QUERY_REGS(0), ESA_QUERY_REGS(1));
+      else asm volatile("s_waitcnt vmcnt(0)" : ESA_QUERY_REGS(0), ESA_QUERY_REGS(1));
+    } else {
+      if (first) asm volatile("s_waitcnt vmcnt(14)" : ESA_QUERY_REGS(0), ESA_QUERY_REGS(1), ESA_MU_REGS(0), ESA_MU_REGS(1));
+      else asm volatile("s_waitcnt vmcnt(0)" : ESA_QUERY_REGS(0), ESA_QUERY_REGS(1), ESA_MU_REGS(0), ESA_MU_REGS(1));
+    }
 #pragma unroll
     for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
+      for (int g4 = 0; g4 < 4; ++g4) {
+        if (PASS == 0) {
 #pragma unroll
-    for (int ks = 0; ks < kKSteps; ++ks)
+          for (int e = 0; e < 4; ++e) aux[mt][4 * g4 + e] = -INFINITY;
+        } else {
+          const int qrow = (qb_now * kQPerBlock + wave * kQPerWave) + 32 * mt + 8 * g4 + 4 * hi;
+          const f32x4 m4 = mu4[mt][g4];
+          aux[mt][4 * g4 + 0] = qrow + 0 < l_c ? m4.x : INFINITY;
+          aux[mt][4 * g4 + 1] = qrow + 1 < l_c ? m4.y : INFINITY;
+          aux[mt][4 * g4 + 2] = qrow + 2 < l_c ? m4.z : INFINITY;
+          aux[mt][4 * g4 + 3] = qrow + 3 < l_c ? m4.w : INFINITY;
+        }
+      }
+  };
+#undef ESA_QUERY_REGS
+#undef ESA_MU_REGS
+
+  // ---- the pipeline over this workgroup's tiles
+  bf16x8 bfr[kKSteps];
+  f32x16 acc0[kMT], acc1[kMT];
+  // LDS byte address of this lane's fragment ks of tile nt: row r, slot (2 ks + hi) ^ (r % 16).  The share
+  // starts at a multiple of 256 bytes, so the slot's ks bits can be XORed into the address of fragment 0.
+  const uint32_t frag0_at = lds_tiles + (uint32_t)r * (kDc * 2) + (uint32_t)((hi ^ (r & 15)) * 16);
+  auto read_fragment = [&](int nt, int ks) {
+    asm volatile("ds_read_b128 %0, %1" : "=v"(bfr[ks]) : "v"((frag0_at ^ (uint32_t)(ks * 32)) + (uint32_t)nt * kTileBytes));
+  };
+  float best = -INFINITY;
+  // One eighth of the maximum / subtract work on a finished tile's accumulators.
+  auto epilogue_part = [&](f32x16 (&P)[kMT], int part) {
 #pragma unroll
-      for (int mt = 0; mt < kMT; ++mt)
-        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][ks], bfr[ks], acc[mt], 0, 0, 0);
-    if (PASS == 0) {
-#pragma unroll
-      for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) aux[mt][v] = fmaxf(aux[mt][v], acc[mt][v]);
-    } else {
-      float best = -INFINITY;
-#pragma unroll
-      for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) best = fmaxf(best, acc[mt][v] - aux[mt][v]);
-      best = fmaxf(best, __shfl_xor(best, 32, 64));
-      if (hi == 0) atomicMax(&colmax[32 * nt + r], ordered_key(best));   // LDS, exact, order-free
+    for (int e = 4 * part; e < 4 * part + 4; ++e) {
+      const int mt = e / 16, v = e % 16;
+      if (PASS == 0) aux[mt][v] = fmaxf(aux[mt][v], P[mt][v]);
+      else best = fmaxf(best, P[mt][v] - aux[mt][v]);
     }
+  };
+  auto epilogue_end = [&](int nt) {
+    if (PASS == 1) {
+      // The other half-wave's maximum for the same token: a lane swap in the vector unit (an LDS-routed
+      // shuffle would put a wait for every outstanding fragment read into each tile).  Both halves then hold
+      // the column maximum and both fold it into LDS: an integer maximum, exact and order-free.
+      const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(best), __float_as_uint(best), false, false);
+      best = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+      asm volatile("ds_max_u32 %0, %1" ::"v"(lds_colmax + (uint32_t)(32 * (nt + 1) + r) * 4), "v"(ordered_key(best)) : "memory");
+      best = -INFINITY;
+    }
+  };
+  // Tile nt into C; meanwhile the fragments of tile nt+1 are fetched and the epilogue of tile nt-1, held in
+  // P, is done.  The first tile's "previous tile" is a set of -inf (its column maxima go to the spare slots in
+  // front of colmax); behind the last tile the fetch reads what follows the share in LDS and nothing uses it:
+  // every step is the same code.
+  auto step = [&](int nt, f32x16 (&C)[kMT], f32x16 (&P)[kMT]) {
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < kKSteps; ++ks) {
+      asm volatile("s_waitcnt lgkmcnt(7)" : "+v"(bfr[ks]));
+#pragma unroll
+      for (int mt = 0; mt < kMT; ++mt)
+        C[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][ks], bfr[ks], ks == 0 ? zero : C[mt], 0, 0, 0);
+      read_fragment(nt + 1, ks);
+      epilogue_part(P, ks);
+    }
+    epilogue_end(nt - 1);
+    __builtin_amdgcn_sched_barrier(0);                       // a tile's work stays inside its step
+  };
+  // streaming: the share is still landing.  Tiles become usable in growing groups: 0-1 behind the barrier in
+  // front of the loop, then 2-3, 4-7 and 8-15, each behind a barrier in front of the odd step that fetches
+  // the group's first fragments.  Early on this follows the arrival of the data; later, when the data is
+  // ahead of the arithmetic, the waves run free of each other (a barrier per pair of tiles costs more than
+  // it hides: of the two waves of a SIMD one gets ahead, waits, and the other cannot fill the matrix pipe
+  // alone).  The number of tiles is even.
+  auto run_tiles = [&](bool streaming, bool active) {
+    if (!active) {
+      if (streaming)
+        for (int nt = 0; nt + 2 < tpb && nt <= 6; nt += nt + 2)       // nt = 0, 2, 6: the barriers below
+          wait_loads_then_barrier(nt == 0 ? 12 : (nt == 2 ? 8 : 0));
+      return;
+    }
+#pragma unroll
+    for (int ks = 0; ks < kKSteps; ++ks) read_fragment(0, ks);
+#pragma unroll
+    for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc1[mt][v] = -INFINITY;
+    __builtin_amdgcn_s_waitcnt(0xC07F);                      // lgkmcnt(0), where the compiler sees it: not inside the loop
+    for (int nt = 0; nt < tpb; nt += 2) {
+      step(nt, acc0, acc1);
+      if (streaming && nt + 2 < tpb && (nt == 0 || nt == 2 || nt == 6))
+        wait_loads_then_barrier(nt == 0 ? 12 : (nt == 2 ? 8 : 0));
+      step(nt + 1, acc1, acc0);
+    }
+#pragma unroll
+    for (int ks = 0; ks < kKSteps; ++ks) epilogue_part(acc1, ks);
+    epilogue_end(tpb - 1);
   };
 
   // PASS 0: 32 running maxima per lane, each to be reduced over the 32 lanes of a half-wave: a butterfly
@@ -242,70 +372,45 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
     if (qrow < l_c) part_max[((int64_t)b * l_c + qrow) * gridDim.x + blockIdx.x] = red[0];
   };
 
-  // ---- first query block.  Its fragments are requested first, then this workgroup's K' rows, one
-  // 16-byte piece per thread and tile, all in flight at once.  Loads complete in order, so tile t can
-  // be copied to LDS and used as soon as piece t has arrived, while the later pieces are still
-  // landing: memory streaming and matrix work overlap without any dependent round trips.
-  load_query_block(0);
-  auto piece_src = [&](int i) -> const uint4* {
-    const int id = tid + kThreads * i;                   // row = id / 16 (tile i), 16-byte column = id % 16
-    int row = id >> 4;
-    row = row < span ? row : span - 1;                   // short shares: surplus threads repeat the last row
-    int64_t tok = tok_base + row;
-    tok = tok < n ? tok : n - 1;                         // a repeated token changes no maximum and is never stored
-    return (const uint4*)(kmid + tok * kDc + (id & 15) * 8);
-  };
-  auto piece_dst = [&](int i) -> uint4* {
-    const int id = tid + kThreads * i;
-    int row = id >> 4;
-    row = row < span ? row : span - 1;                   // identical data to an identical place
-    return (uint4*)&ktile[row * kTileLd + (id & 15) * 8];
-  };
-  static_assert(kPieces == 16, "the staging below is written out for sixteen pieces");
-  const uint4 p0 = *piece_src(0), p1 = *piece_src(1), p2 = *piece_src(2), p3 = *piece_src(3);
-  const uint4 p4 = *piece_src(4), p5 = *piece_src(5), p6 = *piece_src(6), p7 = *piece_src(7);
-  const uint4 p8 = *piece_src(8), p9 = *piece_src(9), p10 = *piece_src(10), p11 = *piece_src(11);
-  const uint4 p12 = *piece_src(12), p13 = *piece_src(13), p14 = *piece_src(14), p15 = *piece_src(15);
+  // ---- requests, in the order their results are needed (loads complete in order): query fragments and row
+  // maxima, then the K' share.  Instruction i of wave w fills row group 8*i + w (four rows, 1 KB of
+  // LDS); lane l fetches, for slot l%16 of row l/16 of the group, the piece that undoes the swizzle.
+  // Rows past the end of the middle segment repeat its last token (no maximum changes, nothing of theirs
+  // is stored); shares shorter than sixteen tiles repeat their last instruction, identical data to an
+  // identical place, so that the count of outstanding loads means the same in every workgroup.
   if (PASS == 1) {
-    for (int i = tid; i < span; i += kThreads) colmax[i] = kOrderedKeyOfMinusInf;
+    for (int i = tid; i < span + 32; i += kThreads) colmax[i] = kOrderedKeyOfMinusInf;
     if (first_hist)
       for (int i = tid; i < kRadixBins; i += kThreads) digit_hist[i] = 0u;
   }
+  request_query_block(0);
+  __builtin_amdgcn_sched_barrier(0);
   {
-    int n_mt = (l_c - wave * kQPerWave + 31) / 32;       // 32-query tiles of this wave that hold a query
-    n_mt = n_mt < 0 ? 0 : (n_mt > kMT ? kMT : n_mt);
-#define ESA_SCORE_STAGE(s, pa, pb)                              \
-  do {                                                          \
-    *piece_dst(2 * (s)) = pa;                                   \
-    *piece_dst(2 * (s) + 1) = pb;                               \
-    __syncthreads();                                            \
-    if (n_mt > 0) {                                             \
-      if (2 * (s) < n_tiles_here) compute_tile(2 * (s));        \
-      if (2 * (s) + 1 < n_tiles_here) compute_tile(2 * (s) + 1); \
-    }                                                           \
-  } while (0)
-    ESA_SCORE_STAGE(0, p0, p1);
-    ESA_SCORE_STAGE(1, p2, p3);
-    ESA_SCORE_STAGE(2, p4, p5);
-    ESA_SCORE_STAGE(3, p6, p7);
-    ESA_SCORE_STAGE(4, p8, p9);
-    ESA_SCORE_STAGE(5, p10, p11);
-    ESA_SCORE_STAGE(6, p12, p13);
-    ESA_SCORE_STAGE(7, p14, p15);
-#undef ESA_SCORE_STAGE
-    if (PASS == 0 && n_mt > 0) flush_row_maxima(wave * kQPerWave);
-  }
-
-  // ---- further query blocks (chunks longer than 512 tokens) run against the tile already in LDS
-  for (int qb = 1; qb * kQPerBlock < l_c; ++qb) {
-    const int q0 = qb * kQPerBlock + wave * kQPerWave;
-    int n_mt = (l_c - q0 + 31) / 32;
-    n_mt = n_mt < 0 ? 0 : (n_mt > kMT ? kMT : n_mt);
-    load_query_block(qb);
-    if (n_mt > 0) {
-      for (int nt = 0; nt < n_tiles_here; ++nt) compute_tile(nt);
-      if (PASS == 0) flush_row_maxima(q0);
+    const uint32_t row_in_tile = 4 * wave + (lane >> 4);
+    const uint32_t piece = (lane & 15) ^ (row_in_tile & 15);
+#pragma unroll
+    for (int i = 0; i < kMaxTilesPerBlock; ++i) {
+      const int t = i < tpb ? i : tpb - 1;
+      uint32_t row = 32 * t + row_in_tile;
+      row = row < last_row ? row : last_row;
+      __builtin_amdgcn_global_load_lds((global_void*)(kshare + (size_t)row * (kDc * sizeof(bf16_t)) + piece * 16),
+                                       (lds_void*)(lds_raw + (size_t)(8 * t + wave) * 1024), 16, 0, 0);
     }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  queries_arrived(true);
+  wait_loads_then_barrier(14);                               // tiles 0 and 1 (and this wave's LDS writes above)
+
+  // ---- query blocks (chunks longer than 512 tokens take several); from the second on, the share is in LDS
+  for (int qb = 0; qb * kQPerBlock < l_c; ++qb) {
+    if (qb > 0) {
+      qb_now = qb;
+      request_query_block(qb);
+      queries_arrived(false);
+    }
+    run_tiles(qb == 0, wave_has_queries(qb));
+    if (PASS == 0 && wave_has_queries(qb)) flush_row_maxima(qb * kQPerBlock + wave * kQPerWave);
+    if (qb == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // repeated instructions of a short share
   }
 
   if (PASS == 1) {
@@ -314,7 +419,7 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
       const int i = i0 + tid;
       const int64_t m = tok_base + i;
       const bool ok = i < span && m < n;
-      const uint32_t key = ok ? colmax[i] : 0u;
+      const uint32_t key = ok ? colmax[32 + i] : 0u;
       if (ok) score[(int64_t)b * score_bs + m] = ordered_key_to_f32(key);
       if (first_hist) hist_add(digit_hist, ok, key >> 21);
     }
@@ -330,8 +435,8 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
 // mu[c] = max over workgroups of their partial row maxima ([l_c][blocks] layout): one wave per query.
 // Running between the two sweeps, it also zeroes the selection's three digit histograms when given them.
 __global__ __launch_bounds__(256) void score_rowmax_reduce(const float* __restrict__ part_max, int nblk, int l_c,
-                                                           float* __restrict__ mu, uint32_t* __restrict__ hists,
-                                                           int64_t hists_bs) {
+                                                           float* __restrict__ mu, int mu_stride,
+                                                           uint32_t* __restrict__ hists, int64_t hists_bs) {
   const int lane = threadIdx.x & 63;
   const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int b = blockIdx.y;
@@ -352,7 +457,7 @@ __global__ __launch_bounds__(256) void score_rowmax_reduce(const float* __restri
     m = fmaxf(fmaxf(m, v[0]), fmaxf(fmaxf(v[1], v[2]), v[3]));
   }
   m = wave_max(m);
-  if (lane == 0) mu[(int64_t)b * l_c + c] = m;
+  if (lane == 0) mu[(int64_t)b * mu_stride + c] = m;
 }
 
 // ------------------------------------------------------------------------------------------ decode (l_c = 1)
@@ -589,7 +694,8 @@ int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, in
     }
     score_mfma_bf16<0><<<grid, kThreads, lds0, st>>>((const bf16_t*)qc, l_c, (const bf16_t*)kc_cache, m_lo, n, part, muf,
                                                 raw, q_bs, kc_bs, raw_bs, per, nullptr, 0);
-    score_rowmax_reduce<<<dim3((l_c + 3) / 4, batch), 256, 0, st>>>(part, nblk, l_c, muf, first_hist, first_hist_bs);
+    score_rowmax_reduce<<<dim3((l_c + 3) / 4, batch), 256, 0, st>>>(part, nblk, l_c, muf, mfma_mu_stride(l_c), first_hist,
+                                                                  first_hist_bs);
     score_mfma_bf16<1><<<grid, kThreads, lds1, st>>>((const bf16_t*)qc, l_c, (const bf16_t*)kc_cache, m_lo, n, part, muf,
                                                 raw, q_bs, kc_bs, raw_bs, per, pool_hist ? nullptr : first_hist,
                                                 first_hist_bs);
