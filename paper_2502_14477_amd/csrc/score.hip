@@ -414,6 +414,7 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
   }
 
   if (PASS == 1) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // this wave's column maxima are in LDS
     __syncthreads();
     for (int i0 = 0; i0 < span; i0 += kThreads) {          // whole waves stay in step for hist_add
       const int i = i0 + tid;
