@@ -24,7 +24,7 @@ __device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t bin)
   const int leader = __ffsll((long long)act) - 1;
   const uint32_t lead_bin = __shfl(bin, leader, 64);
   const uint64_t same = __ballot(active && bin == lead_bin);
-  if ((int)(threadIdx.x & 63) == leader) atomicAdd(&h[lead_bin], (uint32_t)__popcll(same));
+  if ((int)(__builtin_amdgcn_workitem_id_x() & 63) == leader) atomicAdd(&h[lead_bin], (uint32_t)__popcll(same));
   if (active && bin != lead_bin) atomicAdd(&h[bin], 1u);
 }
 

@@ -20,6 +20,10 @@
 namespace esa {
 namespace {
 
+// Work-item and workgroup numbers are taken from the hardware builtins in this file: with the IEEE mode bit
+// off (see build.py) the device library's accessors behind threadIdx / blockIdx / gridDim are not inlined (their
+// floating-point mode attributes differ from the kernels'), and every use would be a function call.
+
 // Workspace: [batch][l_c] row maxima (uint32 keys or fp32), [batch][blocks][l_c] fp32 partial row maxima of the
 // matrix-core kernel, then (eps > 0) [batch][n] fp32 unpooled scores.
 __host__ __device__ inline size_t mu_bytes(int l_c, int batch) {      // rows padded to whole groups of 64
@@ -27,7 +31,8 @@ __host__ __device__ inline size_t mu_bytes(int l_c, int batch) {      // rows pa
 }
 
 __global__ void fill_u32(uint32_t* p, int64_t n, uint32_t v) {
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+  const int64_t i = (int64_t)__builtin_amdgcn_workgroup_id_x() * 256 + __builtin_amdgcn_workitem_id_x();   // one thread per word
+  if (i < n) p[i] = v;
 }
 
 // ------------------------------------------------------------------------------------------ generic
@@ -51,17 +56,17 @@ __global__ __launch_bounds__(256) void score_fma(const T* __restrict__ qc, int l
   const int ldk = d_c + 1;
   float* kt = smem;
   float* red = smem + kGTok * ldk;
-  const int b = blockIdx.y;
+  const int b = __builtin_amdgcn_workgroup_id_y();
   const T* q = qc + (int64_t)b * q_bs;
   const T* k = kc + (int64_t)b * kc_bs + m_lo * (int64_t)d_c;
   uint32_t* mu = mu_keys + (int64_t)b * l_c;
-  const int64_t m0 = (int64_t)blockIdx.x * kGTok;
-  for (int e = threadIdx.x; e < kGTok * d_c; e += 256) {
+  const int64_t m0 = (int64_t)__builtin_amdgcn_workgroup_id_x() * kGTok;
+  for (int e = __builtin_amdgcn_workitem_id_x(); e < kGTok * d_c; e += 256) {
     const int t = e / d_c, i = e % d_c;
     kt[t * ldk + i] = (m0 + t < n) ? load_f32(k + (m0 + t) * (int64_t)d_c + i) : 0.f;
   }
   __syncthreads();
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = __builtin_amdgcn_workitem_id_x() & 63, wave = __builtin_amdgcn_workitem_id_x() >> 6;
   const bool valid = (m0 + lane) < n;
   float best = -INFINITY;
   for (int c = wave; c < l_c; c += 4) {
@@ -176,19 +181,21 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
                                                             const float* __restrict__ mu_all,
                                                             float* __restrict__ score, int64_t q_bs, int64_t kc_bs,
                                                             int64_t score_bs, int tiles_per_block,
-                                                            uint32_t* __restrict__ first_hist, int64_t first_hist_bs) {
-  extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
+                                                            uint32_t* __restrict__ first_hist, int64_t first_hist_bs,
+                                                            bf16_t* __restrict__ qfrag, int64_t qfrag_bs, int n_wg) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];   // n_wg: workgroups per batch entry
   const int tpb = tiles_per_block;
   const int span = tpb * 32;                                           // tokens of this workgroup
   uint32_t* colmax = (uint32_t*)(lds_raw + (size_t)tpb * kTileBytes);  // PASS 1: [32 spare + span] keys
   uint32_t* digit_hist = colmax + 32 + span;                           // PASS 1: [kRadixBins]
-  const int b = blockIdx.y;
+  const int b = __builtin_amdgcn_workgroup_id_y();
   const bf16_t* q = qc + (int64_t)b * q_bs;
   const int mu_stride = mfma_mu_stride(l_c);
   const float* mu = mu_all + (int64_t)b * mu_stride;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = __builtin_amdgcn_workitem_id_x(), lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // uniform: lives in a scalar register
   const int r = lane & 31, hi = lane >> 5;
-  const int64_t tok_base = (int64_t)blockIdx.x * span;
+  const int64_t tok_base = (int64_t)__builtin_amdgcn_workgroup_id_x() * span;
   const char* kshare = (const char*)(kc + (int64_t)b * kc_bs + (m_lo + tok_base) * (int64_t)kDc);
   const uint32_t last_row = (uint32_t)(n - tok_base - 1 < span - 1 ? n - tok_base - 1 : span - 1);
   const uint32_t lds_tiles = (uint32_t)(uintptr_t)(lds_byte*)lds_raw;  // LDS byte address of the share
@@ -208,6 +215,12 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
   f32x4 mu4[kMT][4];
   int qb_now = 0;
   auto wave_has_queries = [&](int qb) { return qb * kQPerBlock + wave * kQPerWave < l_c; };
+  // Fragment-ordered copy of Q' in the workspace, [block][wave][tile][step][lane] x 16 bytes: written by the
+  // first workgroups of sweep 0 from their registers (every workgroup holds the same fragments), read by
+  // every workgroup of sweep 1.
+  auto qfrag_of = [&](int qb, int mt) -> bf16_t* {
+    return qfrag + (int64_t)b * qfrag_bs + ((((int64_t)qb * kWaves + wave) * kMT + mt) * kKSteps * 64 + lane) * 8;
+  };
   auto request_query_block = [&](int qb) {
     const int q0 = qb * kQPerBlock + wave * kQPerWave;
     if (!wave_has_queries(qb)) {          // a wave without queries only takes part in the loads and barriers
@@ -222,12 +235,23 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
     }
 #pragma unroll
     for (int mt = 0; mt < kMT; ++mt) {
-      int row = q0 + 32 * mt + r;
-      row = row < l_c ? row : l_c - 1;
-      const bf16_t* p = q + (int64_t)row * kDc + hi * 8;
+      if (PASS == 1) {
+        // the copy of the fragments in register order that sweep 0 left: a wave instruction reads 1 KB in one
+        // piece (eight cache lines) instead of 16 bytes of 32 rows (32 lines), a quarter of the address work
+        const bf16_t* p = qfrag_of(qb, mt);
 #pragma unroll
-      for (int ks = 0; ks < kKSteps; ++ks)
-        asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(a[mt][ks]) : "v"(p), "n"(ks * 32));
+        for (int ks = 0; ks < kKSteps; ++ks) {
+          if (ks < 4) asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(a[mt][ks]) : "v"(p), "n"(ks * 1024));
+          else asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(a[mt][ks]) : "v"(p + 2048), "n"((ks - 4) * 1024));
+        }
+      } else {
+        int row = q0 + 32 * mt + r;
+        row = row < l_c ? row : l_c - 1;
+        const bf16_t* p = q + (int64_t)row * kDc + hi * 8;
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks)
+          asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(a[mt][ks]) : "v"(p), "n"(ks * 32));
+      }
       if (PASS == 1) {
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
@@ -369,7 +393,9 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
     }
     const int mt = r / 16, v = r % 16;
     const int qrow = q0 + 32 * mt + 8 * (v / 4) + 4 * hi + (v % 4);
-    if (qrow < l_c) part_max[((int64_t)b * l_c + qrow) * gridDim.x + blockIdx.x] = red[0];
+    // 32-bit index (batch x l_c x workgroups stays far below 2^32): scalar base + lane offset, no 64-bit address
+    // to carry through the tile loop
+    if (qrow < l_c) part_max[((uint32_t)b * (uint32_t)l_c + (uint32_t)qrow) * (uint32_t)n_wg + __builtin_amdgcn_workgroup_id_x()] = red[0];
   };
 
   // ---- requests, in the order their results are needed (loads complete in order): query fragments and row
@@ -409,6 +435,20 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
       queries_arrived(false);
     }
     run_tiles(qb == 0, wave_has_queries(qb));
+    if (PASS == 0 && wave_has_queries(qb)) {      // the sixteen fragments are shared out over the first workgroups
+      // The lane number is taken afresh here: an address computed at the top of the kernel would be one more
+      // value to keep (or spill) through the tile loop, whose registers are all spoken for.
+      // fragment i goes out from workgroup i (from workgroup 0 on a tiny grid)
+      uint32_t lane_now;
+      asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_now));
+#pragma unroll
+      for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks)
+          if (mt * kKSteps + ks == (int)__builtin_amdgcn_workgroup_id_x() || (__builtin_amdgcn_workgroup_id_x() == 0 && mt * kKSteps + ks >= n_wg))
+            *(bf16x8*)(qfrag + (int64_t)b * qfrag_bs + ((((int64_t)qb * kWaves + wave) * kMT + mt) * kKSteps + ks) * 512 +
+                       lane_now * 8) = a[mt][ks];
+    }
     if (PASS == 0 && wave_has_queries(qb)) flush_row_maxima(qb * kQPerBlock + wave * kQPerWave);
     if (qb == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // repeated instructions of a short share
   }
@@ -438,12 +478,12 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
 __global__ __launch_bounds__(256) void score_rowmax_reduce(const float* __restrict__ part_max, int nblk, int l_c,
                                                            float* __restrict__ mu, int mu_stride,
                                                            uint32_t* __restrict__ hists, int64_t hists_bs) {
-  const int lane = threadIdx.x & 63;
-  const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int b = blockIdx.y;
+  const int lane = __builtin_amdgcn_workitem_id_x() & 63;
+  const int c = __builtin_amdgcn_workgroup_id_x() * 4 + (__builtin_amdgcn_workitem_id_x() >> 6);
+  const int b = __builtin_amdgcn_workgroup_id_y();
   if (hists)
-    for (int i = blockIdx.x * 256 + threadIdx.x; i < 3 * kRadixBins; i += gridDim.x * 256)
-      hists[(int64_t)b * hists_bs + i] = 0u;
+    for (int i = __builtin_amdgcn_workgroup_id_x() * 256 + __builtin_amdgcn_workitem_id_x(); i < 3 * kRadixBins; i += (l_c + 3) / 4 * 256)
+      hists[(int64_t)b * hists_bs + i] = 0u;                 // (l_c + 3) / 4 workgroups of 256 threads
   if (c >= l_c) return;
   const float* p = part_max + ((int64_t)b * l_c + c) * nblk;
   float m = -INFINITY;
@@ -468,6 +508,9 @@ __global__ __launch_bounds__(256) void score_rowmax_reduce(const float* __restri
 // workgroups folding into one word serialise in L2); score_sub_mu then reduces those maxima to mu,
 // every workgroup for itself, and forms F = S - mu.
 constexpr int kGemvRows = 256;           // rows per workgroup
+// grids of the passes over the scores (host and device agree on them; the kernels do not ask the dispatch packet)
+__host__ __device__ inline int sub_mu_blocks(int64_t n) { return (int)((n + 1023) / 1024 < 2048 ? (n + 1023) / 1024 : 2048); }
+__host__ __device__ inline int maxpool_blocks(int64_t n) { return (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096); }
 
 // Sum over groups of LPR consecutive lanes (LPR = 8, 16, 32) with DPP moves; every lane gets the total.
 template <int LPR>
@@ -488,13 +531,14 @@ __global__ __launch_bounds__(256) void score_gemv_bf16(const bf16_t* __restrict_
   constexpr int kDcv = LPR * 8;
   constexpr int kRowsPerStep = 256 / LPR;
   constexpr int kGemvSteps = kGemvRows / kRowsPerStep;
+  const int n_wg = (int)((n + kGemvRows - 1) / kGemvRows);           // workgroups per batch entry (the launch's grid)
   __shared__ float red[4];
-  const int b = blockIdx.y;
+  const int b = __builtin_amdgcn_workgroup_id_y();
   if (hists)       // the selection's digit histograms, zeroed here for the pass that follows
-    for (int i = blockIdx.x * 256 + threadIdx.x; i < 3 * kRadixBins; i += gridDim.x * 256)
+    for (int i = __builtin_amdgcn_workgroup_id_x() * 256 + __builtin_amdgcn_workitem_id_x(); i < 3 * kRadixBins; i += n_wg * 256)
       hists[(int64_t)b * hists_bs + i] = 0u;
   const bf16_t* kmid = kc + (int64_t)b * kc_bs + m_lo * (int64_t)kDcv;
-  const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+  const int sub = __builtin_amdgcn_workitem_id_x() % LPR, grp = __builtin_amdgcn_workitem_id_x() / LPR;
   float qv[8];
   {
     const uint4 u = *(const uint4*)(qc + (int64_t)b * q_bs + sub * 8);
@@ -504,7 +548,7 @@ __global__ __launch_bounds__(256) void score_gemv_bf16(const bf16_t* __restrict_
     qv[6] = __uint_as_float(u.w << 16); qv[7] = __uint_as_float(u.w & 0xFFFF0000u);
   }
   float best = -INFINITY;
-  const int64_t row0 = (int64_t)blockIdx.x * kGemvRows;
+  const int64_t row0 = (int64_t)__builtin_amdgcn_workgroup_id_x() * kGemvRows;
 #pragma unroll
   for (int it = 0; it < kGemvSteps; ++it) {
     const int64_t row = row0 + it * kRowsPerStep + grp;
@@ -525,10 +569,10 @@ __global__ __launch_bounds__(256) void score_gemv_bf16(const bf16_t* __restrict_
     }
   }
   best = wave_max(best);
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = best;
+  if ((__builtin_amdgcn_workitem_id_x() & 63) == 0) red[__builtin_amdgcn_workitem_id_x() >> 6] = best;
   __syncthreads();
-  if (threadIdx.x == 0)
-    part[(int64_t)b * gridDim.x + blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  if (__builtin_amdgcn_workitem_id_x() == 0)
+    part[(int64_t)b * n_wg + __builtin_amdgcn_workgroup_id_x()] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
 __global__ __launch_bounds__(256) void score_sub_mu(float* __restrict__ raw, int64_t n, const float* __restrict__ part,
@@ -536,10 +580,11 @@ __global__ __launch_bounds__(256) void score_sub_mu(float* __restrict__ raw, int
                                                     int64_t first_hist_bs) {
   __shared__ float red[4];
   __shared__ uint32_t digit_hist[kRadixBins];
+  const int n_wg = sub_mu_blocks(n);                          // workgroups per batch entry (the launch's grid)
   if (first_hist)
-    for (int i = threadIdx.x; i < kRadixBins; i += 256) digit_hist[i] = 0u;
-  float* p = raw + (int64_t)blockIdx.y * raw_bs;
-  const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
+    for (int i = __builtin_amdgcn_workitem_id_x(); i < kRadixBins; i += 256) digit_hist[i] = 0u;
+  float* p = raw + (int64_t)__builtin_amdgcn_workgroup_id_y() * raw_bs;
+  const int64_t first = (int64_t)__builtin_amdgcn_workgroup_id_x() * 256 + __builtin_amdgcn_workitem_id_x(), stride = (int64_t)n_wg * 256;
   // this thread's first four scores are requested together with the partial maxima: one round trip
   float x[4];
 #pragma unroll
@@ -548,18 +593,18 @@ __global__ __launch_bounds__(256) void score_sub_mu(float* __restrict__ raw, int
     x[u] = i < n ? p[i] : 0.f;
   }
   float mu = -INFINITY;
-  for (int i0 = threadIdx.x; i0 < n_part; i0 += 4 * 256) {
+  for (int i0 = __builtin_amdgcn_workitem_id_x(); i0 < n_part; i0 += 4 * 256) {
     float v[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int i = i0 + 256 * u;
-      v[u] = part[(int64_t)blockIdx.y * n_part + (i < n_part ? i : 0)];
+      v[u] = part[(int64_t)__builtin_amdgcn_workgroup_id_y() * n_part + (i < n_part ? i : 0)];
       if (i >= n_part) v[u] = -INFINITY;
     }
     mu = fmaxf(fmaxf(mu, v[0]), fmaxf(fmaxf(v[1], v[2]), v[3]));
   }
   mu = wave_max(mu);
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mu;
+  if ((__builtin_amdgcn_workitem_id_x() & 63) == 0) red[__builtin_amdgcn_workitem_id_x() >> 6] = mu;
   __syncthreads();
   mu = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 #pragma unroll
@@ -570,16 +615,16 @@ __global__ __launch_bounds__(256) void score_sub_mu(float* __restrict__ raw, int
     if (first_hist) hist_add(digit_hist, i < n, ordered_key(f) >> 21);
   }
   // whole waves stay in the loop together (hist_add is a wave-wide operation); four scores in flight per lane
-  for (int64_t i0 = (int64_t)blockIdx.x * blockDim.x + (threadIdx.x & ~63) + 4 * stride; i0 < n; i0 += 4 * stride) {
+  for (int64_t i0 = (int64_t)__builtin_amdgcn_workgroup_id_x() * 256 + (__builtin_amdgcn_workitem_id_x() & ~63) + 4 * stride; i0 < n; i0 += 4 * stride) {
     float y[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int64_t i = i0 + u * stride + (threadIdx.x & 63);
+      const int64_t i = i0 + u * stride + (__builtin_amdgcn_workitem_id_x() & 63);
       y[u] = i < n ? p[i] : 0.f;
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int64_t i = i0 + u * stride + (threadIdx.x & 63);
+      const int64_t i = i0 + u * stride + (__builtin_amdgcn_workitem_id_x() & 63);
       const float f = y[u] - mu;
       if (i < n) p[i] = f;
       if (first_hist) hist_add(digit_hist, i < n, ordered_key(f) >> 21);
@@ -587,8 +632,8 @@ __global__ __launch_bounds__(256) void score_sub_mu(float* __restrict__ raw, int
   }
   if (first_hist) {
     __syncthreads();
-    uint32_t* gh = first_hist + (int64_t)blockIdx.y * first_hist_bs;
-    for (int i = threadIdx.x; i < kRadixBins; i += 256)
+    uint32_t* gh = first_hist + (int64_t)__builtin_amdgcn_workgroup_id_y() * first_hist_bs;
+    for (int i = __builtin_amdgcn_workitem_id_x(); i < kRadixBins; i += 256)
       if (digit_hist[i]) atomicAdd(&gh[i], digit_hist[i]);
   }
 }
@@ -599,14 +644,15 @@ __global__ __launch_bounds__(256) void proximity_maxpool(const float* __restrict
                                                          int eps, int64_t in_bs, int64_t out_bs,
                                                          uint32_t* __restrict__ first_hist, int64_t first_hist_bs) {
   __shared__ uint32_t digit_hist[kRadixBins];
+  const int n_wg = maxpool_blocks(n);                         // workgroups per batch entry (the launch's grid)
   if (first_hist)
-    for (int i = threadIdx.x; i < kRadixBins; i += 256) digit_hist[i] = 0u;
+    for (int i = __builtin_amdgcn_workitem_id_x(); i < kRadixBins; i += 256) digit_hist[i] = 0u;
   __syncthreads();
-  const float* src = in + (int64_t)blockIdx.y * in_bs;
-  float* dst = out + (int64_t)blockIdx.y * out_bs;
+  const float* src = in + (int64_t)__builtin_amdgcn_workgroup_id_y() * in_bs;
+  float* dst = out + (int64_t)__builtin_amdgcn_workgroup_id_y() * out_bs;
   // whole waves stay in the loop together (hist_add is a wave-wide operation)
-  for (int64_t j0 = (int64_t)blockIdx.x * 256 + (threadIdx.x & ~63); j0 < n; j0 += (int64_t)gridDim.x * 256) {
-    const int64_t j = j0 + (threadIdx.x & 63);
+  for (int64_t j0 = (int64_t)__builtin_amdgcn_workgroup_id_x() * 256 + (__builtin_amdgcn_workitem_id_x() & ~63); j0 < n; j0 += (int64_t)n_wg * 256) {
+    const int64_t j = j0 + (__builtin_amdgcn_workitem_id_x() & 63);
     float m = 0.f;
     if (j < n) {
       const int64_t lo = j - eps > 0 ? j - eps : 0, hi = j + eps < n - 1 ? j + eps : n - 1;
@@ -618,8 +664,8 @@ __global__ __launch_bounds__(256) void proximity_maxpool(const float* __restrict
   }
   if (first_hist) {
     __syncthreads();
-    uint32_t* gh = first_hist + (int64_t)blockIdx.y * first_hist_bs;
-    for (int i = threadIdx.x; i < kRadixBins; i += 256)
+    uint32_t* gh = first_hist + (int64_t)__builtin_amdgcn_workgroup_id_y() * first_hist_bs;
+    for (int i = __builtin_amdgcn_workitem_id_x(); i < kRadixBins; i += 256)
       if (digit_hist[i]) atomicAdd(&gh[i], digit_hist[i]);
   }
 }
@@ -635,10 +681,16 @@ __host__ inline size_t part_bytes(int l_c, int64_t n_mid, int batch) {
   return align_up(blocks * batch * 4, 256);
 }
 
+// fragment-ordered copy of Q' (matrix-core path): whole blocks of 512 queries, 256 bytes each
+__host__ inline size_t qfrag_bytes_per_batch(int l_c) {
+  return l_c > 1 ? (size_t)((l_c + kQPerBlock - 1) / kQPerBlock) * kQPerBlock * kDc * sizeof(bf16_t) : 0;
+}
+
 size_t score_workspace_bytes(int l_c, int64_t n_mid, int eps, int batch) {
   if (l_c <= 0 || batch <= 0 || n_mid < 0) return 256;
   size_t b = mu_bytes(l_c, batch) + part_bytes(l_c, n_mid, batch);
   if (eps > 0) b += align_up((size_t)n_mid * 4, 256) * (size_t)batch;
+  b += qfrag_bytes_per_batch(l_c) * (size_t)batch;
   return b;
 }
 
@@ -673,7 +725,7 @@ int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, in
     if (lpr == 8) score_gemv_bf16<8><<<grid, 256, 0, st>>>(q, k, m_lo, n, part, raw, q_bs, kc_bs, raw_bs, fh, fbs);
     else if (lpr == 16) score_gemv_bf16<16><<<grid, 256, 0, st>>>(q, k, m_lo, n, part, raw, q_bs, kc_bs, raw_bs, fh, fbs);
     else score_gemv_bf16<32><<<grid, 256, 0, st>>>(q, k, m_lo, n, part, raw, q_bs, kc_bs, raw_bs, fh, fbs);
-    const int blocks = (int)((n + 1023) / 1024 < 2048 ? (n + 1023) / 1024 : 2048);
+    const int blocks = sub_mu_blocks(n);
     score_sub_mu<<<dim3(blocks, batch), 256, 0, st>>>(raw, n, part, nblk, raw_bs, pool_hist ? nullptr : fh, fbs);
     if (fh && !pool_hist && first_hist_done) *first_hist_done = true;
   } else if (vec_ok && d_c == kDc) {
@@ -693,13 +745,17 @@ int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, in
       if (e != hipSuccess) return hip_failed(e, "hipFuncSetAttribute(score_mfma_bf16)");
       lds_limit_raised = true;
     }
+    size_t qfrag_at = mu_bytes(l_c, batch) + part_bytes(l_c, n, batch);
+    if (eps > 0) qfrag_at += align_up((size_t)n * 4, 256) * (size_t)batch;
+    bf16_t* qfrag = (bf16_t*)((char*)ws + qfrag_at);
+    const int64_t qfrag_bs = (int64_t)(qfrag_bytes_per_batch(l_c) / sizeof(bf16_t));
     score_mfma_bf16<0><<<grid, kThreads, lds0, st>>>((const bf16_t*)qc, l_c, (const bf16_t*)kc_cache, m_lo, n, part, muf,
-                                                raw, q_bs, kc_bs, raw_bs, per, nullptr, 0);
+                                                raw, q_bs, kc_bs, raw_bs, per, nullptr, 0, qfrag, qfrag_bs, nblk);
     score_rowmax_reduce<<<dim3((l_c + 3) / 4, batch), 256, 0, st>>>(part, nblk, l_c, muf, mfma_mu_stride(l_c), first_hist,
                                                                   first_hist_bs);
     score_mfma_bf16<1><<<grid, kThreads, lds1, st>>>((const bf16_t*)qc, l_c, (const bf16_t*)kc_cache, m_lo, n, part, muf,
                                                 raw, q_bs, kc_bs, raw_bs, per, pool_hist ? nullptr : first_hist,
-                                                first_hist_bs);
+                                                first_hist_bs, qfrag, qfrag_bs, nblk);
     zeroed = first_hist != nullptr;
     if (first_hist && !pool_hist && first_hist_done) *first_hist_done = true;
   } else {
@@ -727,7 +783,7 @@ int launch_score(const void* qc, int l_c, const void* kc_cache, int64_t m_lo, in
     }
   }
   if (eps > 0) {
-    const int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+    const int blocks = maxpool_blocks(n);
     uint32_t* ph = zeroed ? pool_hist : nullptr;       // only behind kernels that have zeroed the histograms
     proximity_maxpool<<<dim3(blocks, batch), 256, 0, st>>>(raw, score, n, eps, raw_bs, score_bs, ph, first_hist_bs);
     if (ph && first_hist_done) *first_hist_done = true;
