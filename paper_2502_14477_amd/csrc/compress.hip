@@ -8,6 +8,8 @@
 //     workgroup owns a 16-token x 16-output tile; its four (many tokens) or sixteen (few tokens:
 //     latency-bound) waves each reduce an equal share of d_in and the partial tiles are added in a
 //     fixed order (deterministic, no atomics).
+//   * compress_few_packed_bf16 — the same inputs for one to four tokens (a decode step): one workgroup per
+//     output, a dot product per token.
 //   * compress_mfma_bf16 — bf16 storage, weights as given ([d_in, d_c]); W is transposed through LDS.
 //   * compress_fma — any storage type, shape and weight layout, plain fp32 FMAs in ascending
 //     reduction order.
@@ -203,6 +205,53 @@ __global__ __launch_bounds__(64 * NW) void compress_mfma_packed_bf16(CompressJob
   }
 }
 
+// Up to four tokens (a decode step): the matrix-core kernel above would occupy d_c / 16 workgroups per input and
+// leave the chip idle while sixteen compute units pull the weights through; here every output is a workgroup of
+// its own (d_c per input, two inputs per launch), which streams its weight row once, 16 bytes per lane and step,
+// against the one to four token rows, and adds up in a fixed order (in-lane, wave butterfly, four waves through
+// LDS): deterministic, no atomics.  blockIdx.x = output, blockIdx.y = input (job), blockIdx.z = batch entry.
+constexpr int kFewTok = 4;
+constexpr int kFewBatch = 4;     // larger batches re-read the weights once per entry here: the matrix-core kernel wins
+__global__ __launch_bounds__(256) void compress_few_packed_bf16(CompressJob j0, CompressJob j1, int n_tok) {
+  __shared__ float red[4][kFewTok];
+  const bool second = blockIdx.y != 0;
+  const bf16_t* x = second ? j1.x : j0.x;
+  const bf16_t* Wt = second ? j1.Wt : j0.Wt;
+  const bf16_t* bias = second ? j1.bias : j0.bias;
+  bf16_t* out = second ? j1.out : j0.out;
+  const int64_t d_in = second ? j1.d_in : j0.d_in, ldx = second ? j1.ldx : j0.ldx, ldo = second ? j1.ldo : j0.ldo;
+  const int64_t x_bs = second ? j1.x_bs : j0.x_bs, out_bs = second ? j1.out_bs : j0.out_bs;
+  const bf16_t* xb = x + (int64_t)blockIdx.z * x_bs;
+  const int col = blockIdx.x;
+  const bf16_t* wrow = Wt + (int64_t)col * d_in;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float acc[kFewTok] = {0.f, 0.f, 0.f, 0.f};
+  for (int64_t i = (int64_t)tid * 8; i < d_in; i += 256 * 8) {
+    const bf16x8 w = *(const bf16x8*)(wrow + i);
+#pragma unroll
+    for (int t = 0; t < kFewTok; ++t) {
+      if (t < n_tok) {
+        const bf16x8 v = *(const bf16x8*)(xb + (int64_t)t * ldx + i);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[t] = __fmaf_rn((float)v[e], (float)w[e], acc[t]);
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < kFewTok; ++t) {
+    if (t >= n_tok) break;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc[t] += __shfl_xor(acc[t], off, 64);
+    if (lane == 0) red[wave][t] = acc[t];
+  }
+  __syncthreads();
+  if (tid < n_tok) {
+    float v = ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
+    if (bias) v += bf16_to_f32(bias[col]);
+    out[(int64_t)blockIdx.z * out_bs + (int64_t)tid * ldo + col] = f32_to_bf16(v);
+  }
+}
+
 // W [d_in, d_c] -> Wt [d_c, d_in], through a padded LDS tile so both sides are coalesced.
 template <typename T>
 __global__ __launch_bounds__(256) void pack_weights(const T* __restrict__ W, int64_t d_in, int d_c, T* __restrict__ Wt) {
@@ -239,7 +288,9 @@ int launch_compress(const void* x, int64_t n_tok, int64_t d_in, int64_t ldx, con
       const int tiles = (int)((n_tok + 15) / 16);
       const dim3 grid((unsigned)tiles, d_c / 16, batch);
       const CompressJob job{(const bf16_t*)x, (const bf16_t*)W, (const bf16_t*)bias, (bf16_t*)out, d_in, ldx, ldo, x_bs, out_bs};
-      if (d_in % 512 == 0 && n_tok <= 4096)
+      if (n_tok <= kFewTok && batch <= kFewBatch)
+        compress_few_packed_bf16<<<dim3(d_c, 1, batch), 256, 0, st>>>(job, job, (int)n_tok);
+      else if (d_in % 512 == 0 && n_tok <= 4096)
         compress_mfma_packed_bf16<16><<<grid, 1024, 0, st>>>(job, job, n_tok, d_c / 16);
       else
         compress_mfma_packed_bf16<4><<<grid, 256, 0, st>>>(job, job, n_tok, d_c / 16);
@@ -280,7 +331,10 @@ int launch_compress_pair(const void* x0, int64_t d_in0, int64_t ldx0, const void
     const int tiles = (int)((n_tok + 15) / 16);
     const CompressJob j0{(const bf16_t*)x0, (const bf16_t*)W0, (const bf16_t*)bias0, (bf16_t*)out0, d_in0, ldx0, ldo0, x0_bs, out0_bs};
     const CompressJob j1{(const bf16_t*)x1, (const bf16_t*)W1, (const bf16_t*)bias1, (bf16_t*)out1, d_in1, ldx1, ldo1, x1_bs, out1_bs};
-    compress_mfma_packed_bf16<16><<<dim3(tiles, 2 * (d_c / 16), batch), 1024, 0, st>>>(j0, j1, n_tok, d_c / 16);
+    if (n_tok <= kFewTok && batch <= kFewBatch)
+      compress_few_packed_bf16<<<dim3(d_c, 2, batch), 256, 0, st>>>(j0, j1, (int)n_tok);
+    else
+      compress_mfma_packed_bf16<16><<<dim3(tiles, 2 * (d_c / 16), batch), 1024, 0, st>>>(j0, j1, n_tok, d_c / 16);
     ESA_LAUNCH_CHECK("compress (pair)");
     return ESA_OK;
   }

@@ -182,7 +182,11 @@ def test_compress_writes_rows_of_a_strided_cache_in_place(esa):
 @pytest.mark.parametrize("dtype,B,n_tok,hq,hk,d,d_c,packed", [
     ("bf16", 1, 512, 32, 8, 128, 128, True),      # the chunk of configuration 3: one launch for both
     ("bf16", 2, 37, 8, 4, 128, 64, True),         # ragged token count, batched
-    ("bf16", 1, 1, 32, 8, 128, 128, True),        # decode
+    ("bf16", 1, 1, 32, 8, 128, 128, True),        # decode: one workgroup per output
+    ("bf16", 2, 3, 32, 8, 128, 128, True),        # three tokens, batched: the same kernel
+    ("bf16", 3, 4, 8, 4, 128, 64, True),          # four tokens (its limit), short reductions
+    ("bf16", 5, 2, 8, 4, 128, 64, True),          # batch of five: back to the matrix-core kernel
+    ("bf16", 1, 5, 8, 4, 128, 64, True),          # five tokens: back to the matrix-core kernel
     ("bf16", 1, 40, 4, 2, 64, 32, True),          # d_in not a multiple of 512: one launch each
     ("bf16", 1, 40, 8, 4, 128, 64, False),        # row-major weights
     ("f32", 2, 24, 4, 2, 64, 32, False)])
