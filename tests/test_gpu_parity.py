@@ -311,6 +311,21 @@ def test_score_batched_on_the_matrix_core_path_with_proximity_influence(esa):
         assert np.max(np.abs(pooled[b] - orc.proximity(F, eps))) <= F_TOL["bf16"]
 
 
+def test_score_batched_with_two_blocks_of_queries(esa):
+    """Batch of two on the matrix-core path with more than 512 queries: the second sweep reads each batch entry's
+    own copy of the query fragments, one per block of queries."""
+    say("score batch=2 d_c=128 l_c=600")
+    rng = np.random.default_rng(11)
+    B, l_c, S, d_c = 2, 600, 2600, 128
+    qc = orc.round_to_storage(rng.standard_normal((B, l_c, d_c)), "bf16")
+    kc = orc.round_to_storage(rng.standard_normal((B, S, d_c)), "bf16")
+    got = to_f64(esa.esa_score(f64_to_dev(qc, "bf16"), f64_to_dev(kc, "bf16"), 64, 2575))
+    for b in range(B):
+        F = orc.importance(qc[b], kc[b, 64:2575])
+        assert np.max(np.abs(got[b] - F)) <= F_TOL["bf16"]
+        assert np.all(got[b] <= 0.0) and got[b].max() == 0.0
+
+
 # ------------------------------------------------------------------------------------------ score + select + gather fused
 @pytest.mark.parametrize("dtype,B,l_c,n,d_c,m_lo,k,h_kv,d,pad", [
     ("bf16", 1, 512, 30080, 128, 128, 2048, 8, 128, 0),     # matrix-core sweeps, histogram left by the second one
