@@ -136,7 +136,9 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   __shared__ __attribute__((aligned(1024))) bf16_t v_st0[kTileElems];
   __shared__ __attribute__((aligned(1024))) bf16_t v_st1[kTileElems];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, hi = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, hi = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);        // uniform: scalar address arithmetic
+
 
   // ---- which (batch element, KV head, row tile, key slice) is this workgroup
   const int n_slices = a.view[0].n_split + a.view[1].n_split;
