@@ -467,8 +467,7 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
     if (first_hist) {
       __syncthreads();
       uint32_t* gh = first_hist + (int64_t)b * first_hist_bs;
-      for (int i = tid; i < kRadixBins; i += kThreads)
-        if (digit_hist[i]) atomicAdd(&gh[i], digit_hist[i]);
+      hist_flush(gh, digit_hist, __builtin_amdgcn_workgroup_id_x(), tid, kThreads);
     }
   }
 }
@@ -482,7 +481,7 @@ __global__ __launch_bounds__(256) void score_rowmax_reduce(const float* __restri
   const int c = __builtin_amdgcn_workgroup_id_x() * 4 + (__builtin_amdgcn_workitem_id_x() >> 6);
   const int b = __builtin_amdgcn_workgroup_id_y();
   if (hists)
-    for (int i = __builtin_amdgcn_workgroup_id_x() * 256 + __builtin_amdgcn_workitem_id_x(); i < 3 * kRadixBins; i += (l_c + 3) / 4 * 256)
+    for (int i = __builtin_amdgcn_workgroup_id_x() * 256 + __builtin_amdgcn_workitem_id_x(); i < kHistWords; i += (l_c + 3) / 4 * 256)
       hists[(int64_t)b * hists_bs + i] = 0u;                 // (l_c + 3) / 4 workgroups of 256 threads
   if (c >= l_c) return;
   const float* p = part_max + ((int64_t)b * l_c + c) * nblk;
@@ -535,7 +534,7 @@ __global__ __launch_bounds__(256) void score_gemv_bf16(const bf16_t* __restrict_
   __shared__ float red[4];
   const int b = __builtin_amdgcn_workgroup_id_y();
   if (hists)       // the selection's digit histograms, zeroed here for the pass that follows
-    for (int i = __builtin_amdgcn_workgroup_id_x() * 256 + __builtin_amdgcn_workitem_id_x(); i < 3 * kRadixBins; i += n_wg * 256)
+    for (int i = __builtin_amdgcn_workgroup_id_x() * 256 + __builtin_amdgcn_workitem_id_x(); i < kHistWords; i += n_wg * 256)
       hists[(int64_t)b * hists_bs + i] = 0u;
   const bf16_t* kmid = kc + (int64_t)b * kc_bs + m_lo * (int64_t)kDcv;
   const int sub = __builtin_amdgcn_workitem_id_x() % LPR, grp = __builtin_amdgcn_workitem_id_x() / LPR;
@@ -584,7 +583,10 @@ __global__ __launch_bounds__(256) void score_sub_mu(float* __restrict__ raw, int
   if (first_hist)
     for (int i = __builtin_amdgcn_workitem_id_x(); i < kRadixBins; i += 256) digit_hist[i] = 0u;
   float* p = raw + (int64_t)__builtin_amdgcn_workgroup_id_y() * raw_bs;
-  const int64_t first = (int64_t)__builtin_amdgcn_workgroup_id_x() * 256 + __builtin_amdgcn_workitem_id_x(), stride = (int64_t)n_wg * 256;
+  // A workgroup owns chunks of 1024 consecutive scores (the first one is the chunk the selection's workgroup of
+  // the same number reads next: written and read on the same XCD), a thread four scores 256 apart.
+  const int64_t first = (int64_t)__builtin_amdgcn_workgroup_id_x() * 1024 + __builtin_amdgcn_workitem_id_x(), stride = 256;
+  const int64_t chunk_stride = (int64_t)n_wg * 1024;
   // this thread's first four scores are requested together with the partial maxima: one round trip
   float x[4];
 #pragma unroll
@@ -615,16 +617,16 @@ __global__ __launch_bounds__(256) void score_sub_mu(float* __restrict__ raw, int
     if (first_hist) hist_add(digit_hist, i < n, ordered_key(f) >> 21);
   }
   // whole waves stay in the loop together (hist_add is a wave-wide operation); four scores in flight per lane
-  for (int64_t i0 = (int64_t)__builtin_amdgcn_workgroup_id_x() * 256 + (__builtin_amdgcn_workitem_id_x() & ~63) + 4 * stride; i0 < n; i0 += 4 * stride) {
+  for (int64_t c0 = (int64_t)__builtin_amdgcn_workgroup_id_x() * 1024 + chunk_stride; c0 < n; c0 += chunk_stride) {
     float y[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int64_t i = i0 + u * stride + (__builtin_amdgcn_workitem_id_x() & 63);
+      const int64_t i = c0 + u * stride + __builtin_amdgcn_workitem_id_x();
       y[u] = i < n ? p[i] : 0.f;
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int64_t i = i0 + u * stride + (__builtin_amdgcn_workitem_id_x() & 63);
+      const int64_t i = c0 + u * stride + __builtin_amdgcn_workitem_id_x();
       const float f = y[u] - mu;
       if (i < n) p[i] = f;
       if (first_hist) hist_add(digit_hist, i < n, ordered_key(f) >> 21);
@@ -633,8 +635,7 @@ __global__ __launch_bounds__(256) void score_sub_mu(float* __restrict__ raw, int
   if (first_hist) {
     __syncthreads();
     uint32_t* gh = first_hist + (int64_t)__builtin_amdgcn_workgroup_id_y() * first_hist_bs;
-    for (int i = __builtin_amdgcn_workitem_id_x(); i < kRadixBins; i += 256)
-      if (digit_hist[i]) atomicAdd(&gh[i], digit_hist[i]);
+    hist_flush(gh, digit_hist, __builtin_amdgcn_workgroup_id_x(), __builtin_amdgcn_workitem_id_x(), 256);
   }
 }
 
@@ -665,8 +666,7 @@ __global__ __launch_bounds__(256) void proximity_maxpool(const float* __restrict
   if (first_hist) {
     __syncthreads();
     uint32_t* gh = first_hist + (int64_t)__builtin_amdgcn_workgroup_id_y() * first_hist_bs;
-    for (int i = __builtin_amdgcn_workitem_id_x(); i < kRadixBins; i += 256)
-      if (digit_hist[i]) atomicAdd(&gh[i], digit_hist[i]);
+    hist_flush(gh, digit_hist, __builtin_amdgcn_workgroup_id_x(), __builtin_amdgcn_workitem_id_x(), 256);
   }
 }
 

@@ -74,12 +74,17 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* total,
 
 __device__ __forceinline__ void load_keys(const float* row, int64_t n, int64_t first, uint32_t (&key)[kItems],
                                           bool (&ok)[kItems]) {
+  // unconditional loads (a position past the end reads score 0 instead): both are in flight together, and with
+  // the histogram loads that follow, rather than one round trip each behind a branch
+  float v[kItems];
 #pragma unroll
   for (int e = 0; e < kItems; ++e) {
-    int64_t i = first + e;
+    const int64_t i = first + e;
     ok[e] = i < n;
-    key[e] = ok[e] ? ordered_key(row[i]) : 0u;
+    v[e] = row[ok[e] ? i : 0];
   }
+#pragma unroll
+  for (int e = 0; e < kItems; ++e) key[e] = ok[e] ? ordered_key(v[e]) : 0u;
 }
 
 // One thread's share of a finished 2048-bin histogram; thread 0 owns the highest bins.
@@ -87,11 +92,19 @@ constexpr int kBinsPerThread = kBins / kThreads;
 struct BinSlice {
   uint32_t c[kBinsPerThread];
 };
-__device__ __forceinline__ BinSlice load_slice(const uint32_t* __restrict__ gh) {
+__device__ __forceinline__ BinSlice load_slice(const uint32_t* __restrict__ gh) {   // gh: [kHistReplicas][kBins]
+  static_assert(kBinsPerThread == 4, "one 16-byte load per copy");
   BinSlice s;
-  const int top = kBins - 1 - threadIdx.x * kBinsPerThread;
+  const uint4* lowest = (const uint4*)gh + (kThreads - 1 - threadIdx.x);      // bins top-3 .. top of this thread
+  uint4 c[kHistReplicas];
 #pragma unroll
-  for (int e = 0; e < kBinsPerThread; ++e) s.c[e] = gh[top - e];
+  for (int r = 0; r < kHistReplicas; ++r) c[r] = lowest[r * (kBins / 4)];
+  uint4 t = c[0];
+#pragma unroll
+  for (int r = 1; r < kHistReplicas; ++r) {
+    t.x += c[r].x; t.y += c[r].y; t.z += c[r].z; t.w += c[r].w;
+  }
+  s.c[0] = t.w; s.c[1] = t.z; s.c[2] = t.y; s.c[3] = t.x;
   return s;
 }
 
@@ -143,7 +156,7 @@ __device__ __forceinline__ void resolve_prefix(uint32_t* __restrict__ w, uint32_
     *k_rem = k;
     return;
   }
-  const BinSlice sl = load_slice(w + TopkLayout::hist + (PASS - 1) * kBins);
+  const BinSlice sl = load_slice(w + TopkLayout::hist + (PASS - 1) * kHistReplicas * kBins);
   uint32_t b0 = 0, k0 = 0, b1 = 0, k1 = 0;
   if (PASS >= 2) {
     b0 = w[TopkLayout::pick + 0];
@@ -180,7 +193,7 @@ __device__ __forceinline__ void resolve_prefix(uint32_t* __restrict__ w, uint32_
 
 __global__ void topk_init(uint32_t* ws, int64_t row_words) {
   uint32_t* w = ws + (int64_t)blockIdx.y * row_words;
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < 3 * kBins; i += gridDim.x * blockDim.x) w[i] = 0u;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < kHistWords; i += gridDim.x * blockDim.x) w[i] = 0u;
 }
 
 // PASS 0: bits 31..21, PASS 1: bits 20..10, PASS 2: bits 9..0.
@@ -229,9 +242,7 @@ __global__ __launch_bounds__(kThreads) void topk_hist(const float* __restrict__ 
     if ((threadIdx.x & 63) == 0) atomicAdd(&n_above, above);
   }
   __syncthreads();
-  uint32_t* gh = w + TopkLayout::hist + PASS * kBins;
-  for (int i = threadIdx.x; i < kBins; i += kThreads)
-    if (h[i]) atomicAdd(&gh[i], h[i]);
+  hist_flush(w + TopkLayout::hist + PASS * kHistReplicas * kBins, h, blockIdx.x, threadIdx.x, kThreads);
   if (PASS == 2 && threadIdx.x == 0) {
     w[TopkLayout::blk + blockIdx.x] = n_above;
     w[TopkLayout::blk + nblk + blockIdx.x] = n_cand;
@@ -400,7 +411,7 @@ int launch_topk(const float* score, int64_t n, int k, int64_t base, int32_t* idx
   uint32_t* w = (uint32_t*)ws;
   const dim3 grid(nblk, batch);
   if (!first_hist_ready) {     // otherwise the score call has zeroed the histograms and filled the first one
-    topk_init<<<dim3(3, batch), 1024, 0, st>>>(w, row_words);
+    topk_init<<<dim3(3 * kHistReplicas, batch), 1024, 0, st>>>(w, row_words);
     topk_hist<0><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, (uint32_t)k, sub);
   }
   topk_hist<1><<<grid, kThreads, 0, st>>>(score, n, score_bs, w, row_words, nblk, (uint32_t)k, sub);
