@@ -145,6 +145,16 @@ class Workload:
         return w
 
 
+def step_reads_through_indices(args, l_c):
+    """Gather as a call of its own (esa_gather_kv, then esa_attend on the gathered rows) or inside the attention
+    kernel (esa_attend_indexed).  Measured: equal for a chunk (the gathered rows are cache-warm when the attention
+    reads them), 3 us of 52 and 29 us of 370 in favour of the index-driven form for a decode step at batch 1 and 16
+    (one kernel and one write + read of the selected rows fewer): decode steps take it unless told otherwise."""
+    if args.fused_gather:
+        return True
+    return l_c < 16 and not args.gathered_decode
+
+
 def make_step(esa, torch, w, args, side=None):
     """The five calls for one step of workload w, as a function to call (and to capture)."""
     cfg, t0, l_c, B = w.cfg, w.t0, w.l_c, w.B
@@ -152,6 +162,7 @@ def make_step(esa, torch, w, args, side=None):
     Q, K, V, kc, W_q, W_k = w.Q, w.K, w.V, w.kc, w.W_q, w.W_k
     no_scores = torch.empty(((B,) if B > 1 else ()) + (n_mid,), dtype=torch.float32, device="cuda")
     single_stream = args.single_stream or l_c < 16
+    indexed = step_reads_through_indices(args, l_c)
 
     def step():
         # The five calls on one stream.  With --two-branches (Algorithm 1's split of the key set) the key
@@ -172,7 +183,10 @@ def make_step(esa, torch, w, args, side=None):
             if args.fork_after == "start":
                 fork()
             qc = esa.esa_compress(Q, W_q)
-        if single_stream and not args.separate_calls and not args.fused_gather:
+        if single_stream and not args.separate_calls:
+            if indexed:    # the attention kernel reads the selected rows through the index list
+                _, idx, _, _ = esa.esa_score_select_gather(qc, kc, i_end, l_start, cfg.k)
+                return esa.esa_attend_indexed(Q, K, V, t0, cfg.l_I, cfg.l_L, idx)
             # score, select and gather as one call (the same results with three kernels fewer)
             _, idx, ks, vs = esa.esa_score_select_gather(qc, kc, i_end, l_start, cfg.k, K, V)
             return esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks, vs)
@@ -181,7 +195,7 @@ def make_step(esa, torch, w, args, side=None):
         if not single_stream and args.fork_after == "score":
             fork()
         idx = esa.esa_select_topk(score, cfg.k, base=i_end)
-        if args.fused_gather:
+        if indexed:
             if not single_stream:
                 main.wait_stream(side)
             return esa.esa_attend_indexed(Q, K, V, t0, cfg.l_I, cfg.l_L, idx)
@@ -268,9 +282,10 @@ def per_call_times(esa, torch, np, w, args, with_variants):
         "attend": lambda: esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s),
     }
     single["score_select_gather"] = lambda: esa.esa_score_select_gather(qc_s, kc, i_end, l_start, cfg.k, K, V)
+    if with_variants or step_reads_through_indices(args, l_c):
+        single["attend_indexed"] = lambda: esa.esa_attend_indexed(Q, K, V, t0, cfg.l_I, cfg.l_L, idx_s)
     if with_variants:
         single.update({
-            "attend_indexed": lambda: esa.esa_attend_indexed(Q, K, V, t0, cfg.l_I, cfg.l_L, idx_s),
             "attend_local": lambda: esa.esa_attend_local(Q, K, V, t0, cfg.l_I, cfg.l_L),
             "attend_finish": lambda: esa.esa_attend_finish(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s),
             # Section 3.2 inside the library (the inputs stand in for un-encoded ones: same work)
@@ -345,12 +360,15 @@ def decode_record(esa, torch, np, args):
         eager, replay, mode, graph = time_steps(torch, [step], n, args.warmup, args.eager)
         call_ms = per_call_times(esa, torch, np, w, args, with_variants=False)
         work, rep = call_report(w, call_ms)
+        indexed = step_reads_through_indices(args, w.l_c)
         step_bytes = sum(x["bytes"] for x in work.values())
         rec = {"us_per_step": round(1e3 * replay, 2), "eager_us_per_step": round(1e3 * eager, 2),
                "tokens_per_s": round(B / (replay * 1e-3), 1),
                "step_gbs": round(step_bytes / (replay * 1e-3) / 1e9, 1),
                "step_hbm_frac": round(step_bytes / (replay * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                "algorithmic_bytes": round(step_bytes), "per_call": rep, "launch_mode": mode,
+               "calls": "esa_compress_qk, esa_score_select_gather (no gather), esa_attend_indexed" if indexed else
+                        "esa_compress_qk, esa_score_select_gather, esa_attend",
                "setup_s": round(w.setup_s, 1)}
         if B == 1:
             # one sequence's step touches about 100 MB, which the 256 MB memory-side cache keeps between
@@ -392,6 +410,9 @@ def main():
     ap.add_argument("--fused-gather", action="store_true",
                     help="variant: esa_attend_indexed follows the indices itself instead of esa_gather_kv + esa_attend "
                          "(four calls; not the default step)")
+    ap.add_argument("--gathered-decode", action="store_true",
+                    help="decode steps call esa_gather_kv + esa_attend like the chunk steps, instead of their default, "
+                         "the index-driven esa_attend_indexed")
     ap.add_argument("--fork-after", choices=("start", "score"), default="score",
                     help="where the second stream starts (the score sweeps want every CU for themselves)")
     ap.add_argument("--batch", type=int, default=1,
@@ -486,6 +507,7 @@ def main():
         cpu_baseline = cpu_oracle_baseline(w.layer, cfg, w.t0, w.l_c)
     workload = workload_text(w)
     n_tok = B * w.l_c
+    indexed = step_reads_through_indices(args, w.l_c)
 
     decode = None
     if not args.no_decode and not cfg.decode and B == 1 and not args.seq:
@@ -506,9 +528,10 @@ def main():
         "config": {"workload": workload, "global_batch": B, "seq_len": cfg.S, "parallelism": "single GPU"},
         "roofline": roofline, "decode": decode, "cpu_baseline": cpu_baseline,
         "launch_mode": mode + (", one stream" if args.single_stream else ", two branches")
-        + (", gather fused into attend" if args.fused_gather else "")
+        + (", gather inside the attention kernel (esa_attend_indexed)" if indexed else "")
         + (", five separate calls" if args.separate_calls or not args.single_stream else
-           ("" if args.fused_gather else ", score+select+gather as one call")), "eager_ms_per_step": round(eager_ms, 4),
+           (", score+select as one call" if indexed else
+            ", score+select+gather as one call")), "eager_ms_per_step": round(eager_ms, 4),
         "cold_ms_per_step": None if cold_ms is None else round(cold_ms, 4),
     }
     print(json.dumps(result))

@@ -34,6 +34,34 @@ __device__ __forceinline__ float row16_sum(float v) {
   return v;
 }
 
+// The same value summed / maximised over the lanes 16 and 32 apart, in the vector unit (row swaps), where a
+// general shuffle goes through the LDS crossbar and waits for it.
+__device__ __forceinline__ float across_rows_sum(float v) {
+  auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+  sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+}
+__device__ __forceinline__ float across_rows_max(float v) {
+  auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+  sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+// Maximum over the 16 lanes of a DPP row; every lane receives it.
+__device__ __forceinline__ float row16_max(float v) {
+  int x;
+  x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true);
+  v = fmaxf(v, __int_as_float(x));
+  x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true);
+  v = fmaxf(v, __int_as_float(x));
+  x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true);
+  v = fmaxf(v, __int_as_float(x));
+  x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true);
+  v = fmaxf(v, __int_as_float(x));
+  return v;
+}
+
 __device__ __forceinline__ void unpack8(const uint4& r, float* f) {
   f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xFFFF0000u);
   f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xFFFF0000u);
@@ -57,6 +85,7 @@ struct DecodeArgs {
 template <int G>
 __global__ __launch_bounds__(256) void attend_decode_bf16(DecodeArgs a) {
   __shared__ float logit[G][kMaxSlice];
+  __shared__ int32_t src_row[kMaxSlice];     // where key jj of the slice lives: cache row r as r, gathered row r as ~r
   __shared__ float red[4][G * kD];
   __shared__ float head_m[G], head_l[G];
 
@@ -87,49 +116,107 @@ __global__ __launch_bounds__(256) void attend_decode_bf16(DecodeArgs a) {
     return;
   }
 
-  // this lane's 8 elements of each of the G queries, pre-scaled so that logits are base-2 exponents
+  // this lane's 8 elements of each of the G queries (scaled below so that logits are base-2 exponents)
+  uint4 q_raw[G];
+#pragma unroll
+  for (int hh = 0; hh < G; ++hh)
+    q_raw[hh] = *(const uint4*)(a.q + (int64_t)b * a.q_bs + ((int64_t)c * h + g * G + hh) * kD + sub * 8);
+
+  // ---- where every key of the slice lives.  Resolved for the whole slice up front, with the index list's
+  // entries requested together: done key by key in front of each row load, every look-up is a round trip of
+  // its own that the row loads behind it wait for.
+  {
+    constexpr int kPerThread = kMaxSlice / 256;
+    int32_t picked[kPerThread];
+#pragma unroll
+    for (int u = 0; u < kPerThread; ++u) picked[u] = 0;
+    if (ks.sel_idx && ks.n_sel > 0) {      // unconditional loads (entry 0 where there is nothing to look up): all in flight together
+#pragma unroll
+      for (int u = 0; u < kPerThread; ++u) {
+        const int jj = tid + 256 * u;
+        const int64_t js = j_lo + jj - ks.i_end;
+        picked[u] = ks.sel_idx[(jj < cnt && js >= 0 && js < ks.n_sel) ? js : 0];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kPerThread; ++u) {
+      const int jj = tid + 256 * u;
+      if (jj < cnt) {
+        const int64_t j = j_lo + jj, js = j - ks.i_end;
+        int64_t row;
+        bool gathered = false;
+        if (js < 0) {
+          row = j;
+        } else if (js < ks.n_sel) {
+          if (ks.sel_idx) {     // a middle token: clamped so that a bad index cannot leave the cache
+            row = picked[u];
+            row = row < ks.l_start ? row : ks.l_start - 1;
+            row = row < 0 ? 0 : row;
+          } else {
+            row = js;
+            gathered = true;
+          }
+        } else {
+          row = ks.l_start + (js - ks.n_sel);
+        }
+        src_row[jj] = gathered ? ~(int32_t)row : (int32_t)row;
+      }
+    }
+  }
   float qf[G][8];
 #pragma unroll
   for (int hh = 0; hh < G; ++hh) {
-    const uint4 r = *(const uint4*)(a.q + (int64_t)b * a.q_bs + ((int64_t)c * h + g * G + hh) * kD + sub * 8);
-    unpack8(r, qf[hh]);
+    unpack8(q_raw[hh], qf[hh]);
 #pragma unroll
     for (int i = 0; i < 8; ++i) qf[hh][i] *= a.scale_log2e;
   }
+  __syncthreads();
+
+  // byte offset of key jj's row and whether it is a gathered row (a key past the slice's end stands for key 0:
+  // its row is loaded and not used)
+  auto locate = [&](int jj, bool* gathered) -> int64_t {
+    const int32_t code = src_row[jj < cnt ? jj : 0];
+    *gathered = code < 0;
+    return code < 0 ? (int64_t)(~code) * ks.sel_bytes : (int64_t)code * ks.tok_bytes;
+  };
 
   // values of the first round of keys: requested now, used after the softmax
   uint4 v_first[kUnroll];
-#pragma unroll
-  for (int u = 0; u < kUnroll; ++u) {
-    const int jj = u * kGroups + group;
-    v_first[u] = make_uint4(0, 0, 0, 0);
-    if (jj < cnt) v_first[u] = *(const uint4*)(key_row(ks, j_lo + jj, true) + head_off);
-  }
-
-  // ---- logits of the slice: 16 lanes per key, kUnroll keys per lane group in flight
-  for (int j0 = 0; j0 < cnt; j0 += kGroups * kUnroll) {
+  {
     uint4 r[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-      const int jj = j0 + u * kGroups + group;
-      r[u] = make_uint4(0, 0, 0, 0);
-      if (jj < cnt) r[u] = *(const uint4*)(key_row(ks, j_lo + jj, false) + head_off);
+      bool gathered;
+      const int64_t off = locate(u * kGroups + group, &gathered) + head_off;
+      v_first[u] = *(const uint4*)((gathered ? ks.v_sel : ks.v_cache) + off);
+      r[u] = *(const uint4*)((gathered ? ks.k_sel : ks.k_cache) + off);
     }
+    // ---- logits of the slice: 16 lanes per key, kUnroll keys per lane group in flight
+    for (int j0 = 0; j0 < cnt; j0 += kGroups * kUnroll) {
+      if (j0 > 0) {
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int jj = j0 + u * kGroups + group;
-      float kf[8];
-      unpack8(r[u], kf);
-      float mine = 0.f;
-#pragma unroll
-      for (int hh = 0; hh < G; ++hh) {
-        float s = 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) s = __fmaf_rn(qf[hh][i], kf[i], s);
-        s = row16_sum(s);
-        if (sub == hh) mine = s;
+        for (int u = 0; u < kUnroll; ++u) {
+          bool gathered;
+          const int64_t off = locate(j0 + u * kGroups + group, &gathered) + head_off;
+          r[u] = *(const uint4*)((gathered ? ks.k_sel : ks.k_cache) + off);
+        }
       }
-      if (sub < G && jj < cnt) logit[sub][jj] = mine;
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int jj = j0 + u * kGroups + group;
+        float kf[8];
+        unpack8(r[u], kf);
+        float mine = 0.f;
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) {
+          float s = 0.f;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) s = __fmaf_rn(qf[hh][i], kf[i], s);
+          s = row16_sum(s);
+          if (sub == hh) mine = s;
+        }
+        if (sub < G && jj < cnt) logit[sub][jj] = mine;
+      }
     }
   }
   __syncthreads();
@@ -139,14 +226,14 @@ __global__ __launch_bounds__(256) void attend_decode_bf16(DecodeArgs a) {
     const int lane = tid & 63;
     float m = -INFINITY;
     for (int jj = lane; jj < cnt; jj += 64) m = fmaxf(m, logit[hh][jj]);
-    m = wave_max(m);
+    m = across_rows_max(row16_max(m));
     float l = 0.f;
     for (int jj = lane; jj < cnt; jj += 64) {
-      const float p = exp2f(logit[hh][jj] - m);
+      const float p = __builtin_amdgcn_exp2f(logit[hh][jj] - m);      // arguments <= 0: no range handling needed
       logit[hh][jj] = p;
       l += p;
     }
-    l = wave_sum(l);
+    l = across_rows_sum(row16_sum(l));
     if (lane == 0) {
       head_m[hh] = m;
       head_l[hh] = l;
@@ -167,8 +254,9 @@ __global__ __launch_bounds__(256) void attend_decode_bf16(DecodeArgs a) {
       const int jj = j0 + u * kGroups + group;
       r[u] = v_first[u];
       if (j0 > 0) {
-        r[u] = make_uint4(0, 0, 0, 0);
-        if (jj < cnt) r[u] = *(const uint4*)(key_row(ks, j_lo + jj, true) + head_off);
+        bool gathered;
+        const int64_t off = locate(jj, &gathered) + head_off;
+        r[u] = *(const uint4*)((gathered ? ks.v_sel : ks.v_cache) + off);
       }
     }
 #pragma unroll
@@ -191,10 +279,7 @@ __global__ __launch_bounds__(256) void attend_decode_bf16(DecodeArgs a) {
   for (int hh = 0; hh < G; ++hh)
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      float v = acc[hh][i];
-      v += __shfl_xor(v, 16, 64);
-      v += __shfl_xor(v, 32, 64);
-      acc[hh][i] = v;
+      acc[hh][i] = across_rows_sum(acc[hh][i]);
     }
   if ((tid & 63) < kLanesPerKey) {
 #pragma unroll
@@ -216,50 +301,64 @@ __global__ __launch_bounds__(256) void attend_decode_bf16(DecodeArgs a) {
 }
 
 // One workgroup per output row (batch element, current token, query head): slices combined by their
-// maxima and sums.  Every lane first fetches the (max, sum) pairs of up to two slices, so the weights
-// are known after one round trip; the four waves then each add a quarter of the slices' partial
-// outputs (independent loads, two output dims per lane) and the quarters meet in LDS.
-__global__ __launch_bounds__(256) void attend_decode_merge(const float* __restrict__ part_o,
-                                                           const float* __restrict__ part_ml, int splits, int stride,
-                                                           int l_c, int h, bf16_t* __restrict__ out, int64_t out_bs,
-                                                           float* __restrict__ lse) {
-  __shared__ float red[4][kD];
+// maxima and sums.  The call is two dependent round trips at most if nothing is done about it (the weights come
+// from the (max, sum) pairs, the sum needs the weights), and round trips are all it costs: so every lane requests
+// the pairs of up to two slices and, without waiting for them, the partial outputs of all the slices of its wave
+// (wave w takes slices w, w + 8, ...: eight or sixteen independent loads, two output dims per lane).  The eight
+// waves' shares meet in LDS and are added in a fixed order.
+constexpr int kMergeWaves = 8;
+__global__ __launch_bounds__(kMergeWaves * 64) void attend_decode_merge(const float* __restrict__ part_o,
+                                                                        const float* __restrict__ part_ml, int splits,
+                                                                        int stride, int l_c, int h,
+                                                                        bf16_t* __restrict__ out, int64_t out_bs,
+                                                                        float* __restrict__ lse) {
+  static_assert(kMaxSplits <= 128 && kMaxSplits <= 16 * kMergeWaves, "two pairs per lane, sixteen slices per wave");
+  __shared__ float red[kMergeWaves][kD];
   const int64_t row = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const float2* ml = (const float2*)(part_ml + row * stride * 2);   // slots [0, splits) of `stride` are in use
   float2 a0 = make_float2(-INFINITY, 0.f), a1 = make_float2(-INFINITY, 0.f);
   if (lane < splits) a0 = ml[lane];
   if (lane + 64 < splits) a1 = ml[lane + 64];
+  const float* po = part_o + row * stride * kD + lane * 2;
+  float2 o[16];
+  // a slice past the end re-reads slice 0 and gets weight 0
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const int s = wave + kMergeWaves * u;
+    o[u] = *(const float2*)(po + (int64_t)(s < splits ? s : 0) * kD);
+  }
+  if (splits > 8 * kMergeWaves) {
+#pragma unroll
+    for (int u = 8; u < 16; ++u) {
+      const int s = wave + kMergeWaves * u;
+      o[u] = *(const float2*)(po + (int64_t)(s < splits ? s : 0) * kD);
+    }
+  } else {
+#pragma unroll
+    for (int u = 8; u < 16; ++u) o[u] = make_float2(0.f, 0.f);
+  }
   const float m = wave_max(fmaxf(a0.x, a1.x));
   const float w0 = a0.y > 0.f ? exp2f(a0.x - m) : 0.f;
   const float w1 = a1.y > 0.f ? exp2f(a1.x - m) : 0.f;
   const float l = wave_sum(__fmaf_rn(w0, a0.y, w1 * a1.y));
   float o0 = 0.f, o1 = 0.f;
-  const float* po = part_o + row * stride * kD + lane * 2;
-  // eight slices per trip, their loads issued together (a slice past the end re-reads slice 0 with weight 0)
-  for (int s0 = wave; s0 < splits; s0 += 4 * 8) {
-    float2 o[8];
-    float w[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int s = s0 + 4 * u;
-      const bool in = s < splits;
-      o[u] = *(const float2*)(po + (int64_t)(in ? s : 0) * kD);
-      const float ws = s < 64 ? __shfl(w0, s & 63, 64) : __shfl(w1, (s - 64) & 63, 64);
-      w[u] = in ? ws : 0.f;
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      o0 += w[u] != 0.f ? w[u] * o[u].x : 0.f;    // slices past the causal limit hold no output
-      o1 += w[u] != 0.f ? w[u] * o[u].y : 0.f;
-    }
+  for (int u = 0; u < 16; ++u) {
+    const int s = wave + kMergeWaves * u;              // below 64 for u < 8, from 64 on otherwise
+    const float ws = u < 8 ? __shfl(w0, s, 64) : __shfl(w1, s - 64, 64);
+    const float w = s < splits ? ws : 0.f;
+    o0 += w != 0.f ? w * o[u].x : 0.f;                 // slices past the causal limit hold no output
+    o1 += w != 0.f ? w * o[u].y : 0.f;
   }
   red[wave][lane * 2] = o0;
   red[wave][lane * 2 + 1] = o1;
   __syncthreads();
   if (wave == 0) {
-    o0 = (red[0][lane * 2] + red[1][lane * 2]) + (red[2][lane * 2] + red[3][lane * 2]);
-    o1 = (red[0][lane * 2 + 1] + red[1][lane * 2 + 1]) + (red[2][lane * 2 + 1] + red[3][lane * 2 + 1]);
+    o0 = ((red[0][lane * 2] + red[1][lane * 2]) + (red[2][lane * 2] + red[3][lane * 2])) +
+         ((red[4][lane * 2] + red[5][lane * 2]) + (red[6][lane * 2] + red[7][lane * 2]));
+    o1 = ((red[0][lane * 2 + 1] + red[1][lane * 2 + 1]) + (red[2][lane * 2 + 1] + red[3][lane * 2 + 1])) +
+         ((red[4][lane * 2 + 1] + red[5][lane * 2 + 1]) + (red[6][lane * 2 + 1] + red[7][lane * 2 + 1]));
     const int64_t b = row / ((int64_t)l_c * h), r = row % ((int64_t)l_c * h);
     const float inv = 1.f / l;
     const uint32_t packed = (uint32_t)f32_to_bf16(o0 * inv) | ((uint32_t)f32_to_bf16(o1 * inv) << 16);
@@ -341,6 +440,8 @@ int launch_attend_decode(int part, const void* q, int l_c, int h, int h_kv, cons
     ESA_FAIL(ESA_EUNSUPPORTED, "attend_decode: %lld keys exceed the kernel's range", (long long)(n_fixed + l_c));
   }
   if (ws_bytes < attend_decode_workspace_bytes(l_c, h, batch)) ESA_FAIL(ESA_EWORKSPACE, "attend_decode: workspace too small");
+  if (t0 + l_c > (int64_t)INT32_MAX || n_sel < 0)     // the kernel keeps row numbers as 32-bit integers
+    ESA_FAIL(ESA_EUNSUPPORTED, "attend_decode: %lld cache rows exceed the kernel's range", (long long)(t0 + l_c));
   const size_t rows = (size_t)batch * l_c * h;
   DecodeArgs a;
   a.q = (const bf16_t*)q;
@@ -379,7 +480,7 @@ int launch_attend_decode(int part, const void* q, int l_c, int h, int h_kv, cons
     ESA_LAUNCH_CHECK("attend_decode_bf16");
   }
   if (part != 1) {
-    attend_decode_merge<<<(unsigned)rows, 256, 0, st>>>(a.part_o, a.part_ml, used, stride, l_c, h, (bf16_t*)out, out_bs, lse);
+    attend_decode_merge<<<(unsigned)rows, kMergeWaves * 64, 0, st>>>(a.part_o, a.part_ml, used, stride, l_c, h, (bf16_t*)out, out_bs, lse);
     ESA_LAUNCH_CHECK("attend_decode_merge");
   }
   return ESA_OK;

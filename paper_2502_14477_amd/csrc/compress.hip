@@ -226,14 +226,30 @@ __global__ __launch_bounds__(256) void compress_few_packed_bf16(CompressJob j0, 
   const bf16_t* wrow = Wt + (int64_t)col * d_in;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   float acc[kFewTok] = {0.f, 0.f, 0.f, 0.f};
-  for (int64_t i = (int64_t)tid * 8; i < d_in; i += 256 * 8) {
-    const bf16x8 w = *(const bf16x8*)(wrow + i);
+  // Two steps of the reduction per trip, every load of the trip requested before the first is used and none of
+  // them behind a branch (a step past the end re-reads the trip's first, a token past the last re-reads token 0;
+  // neither is added): the kernel is a handful of round trips long, and loads that wait for each other are
+  // most of them.
+  constexpr int kAhead = 2;
+  for (int64_t i0 = (int64_t)tid * 8; i0 < d_in; i0 += 256 * 8 * kAhead) {
+    bf16x8 w[kAhead], v[kAhead][kFewTok];
 #pragma unroll
-    for (int t = 0; t < kFewTok; ++t) {
-      if (t < n_tok) {
-        const bf16x8 v = *(const bf16x8*)(xb + (int64_t)t * ldx + i);
+    for (int a = 0; a < kAhead; ++a) {
+      const int64_t i = i0 + a * 256 * 8, ic = i < d_in ? i : i0;
+      w[a] = *(const bf16x8*)(wrow + ic);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[t] = __fmaf_rn((float)v[e], (float)w[e], acc[t]);
+      for (int t = 0; t < kFewTok; ++t) v[a][t] = *(const bf16x8*)(xb + (int64_t)(t < n_tok ? t : 0) * ldx + ic);
+    }
+#pragma unroll
+    for (int a = 0; a < kAhead; ++a) {
+      if (i0 + a * 256 * 8 < d_in) {
+#pragma unroll
+        for (int t = 0; t < kFewTok; ++t) {
+          if (t < n_tok) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[t] = __fmaf_rn((float)v[a][t][e], (float)w[a][e], acc[t]);
+          }
+        }
       }
     }
   }
