@@ -147,12 +147,11 @@ class Workload:
 
 def step_reads_through_indices(args, l_c):
     """Gather as a call of its own (esa_gather_kv, then esa_attend on the gathered rows) or inside the attention
-    kernel (esa_attend_indexed).  Measured: equal for a chunk (the gathered rows are cache-warm when the attention
-    reads them), 3 us of 52 and 29 us of 370 in favour of the index-driven form for a decode step at batch 1 and 16
-    (one kernel and one write + read of the selected rows fewer): decode steps take it unless told otherwise."""
-    if args.fused_gather:
-        return True
-    return l_c < 16 and not args.gathered_decode
+    kernel (esa_attend_indexed reads the selected cache rows through the index list: one kernel and one write +
+    read of the selected rows fewer).  Measured on the step: 122.0 against 126.6 us at configuration 3, 452.8 / 464.0
+    at 5, 136.8 / 141.3 at 6, 46.7 / 52.1 for a decode step, 314 / 370 at decode batch 16: the step takes the
+    index-driven form unless told otherwise (--gather-call)."""
+    return not args.gather_call or args.fused_gather
 
 
 def make_step(esa, torch, w, args, side=None):
@@ -282,8 +281,12 @@ def per_call_times(esa, torch, np, w, args, with_variants):
         "attend": lambda: esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s),
     }
     single["score_select_gather"] = lambda: esa.esa_score_select_gather(qc_s, kc, i_end, l_start, cfg.k, K, V)
-    if with_variants or step_reads_through_indices(args, l_c):
-        single["attend_indexed"] = lambda: esa.esa_attend_indexed(Q, K, V, t0, cfg.l_I, cfg.l_L, idx_s)
+    single["attend_indexed"] = lambda: esa.esa_attend_indexed(Q, K, V, t0, cfg.l_I, cfg.l_L, idx_s)
+    if args.eager:      # under the profiler every attention launch is of the step's kind, so that per-kernel averages are the step's
+        if step_reads_through_indices(args, l_c):
+            single["attend"] = single["attend_indexed"]
+        else:
+            del single["attend_indexed"]
     if with_variants:
         single.update({
             "attend_local": lambda: esa.esa_attend_local(Q, K, V, t0, cfg.l_I, cfg.l_L),
@@ -359,9 +362,9 @@ def decode_record(esa, torch, np, args):
         n = max(args.steps, 10)
         eager, replay, mode, graph = time_steps(torch, [step], n, args.warmup, args.eager)
         call_ms = per_call_times(esa, torch, np, w, args, with_variants=False)
-        work, rep = call_report(w, call_ms)
         indexed = step_reads_through_indices(args, w.l_c)
-        step_bytes = sum(x["bytes"] for x in work.values())
+        work, rep = call_report(w, call_ms)
+        step_bytes = sum(x["bytes"] for c, x in work.items() if not (indexed and c == "gather"))
         rec = {"us_per_step": round(1e3 * replay, 2), "eager_us_per_step": round(1e3 * eager, 2),
                "tokens_per_s": round(B / (replay * 1e-3), 1),
                "step_gbs": round(step_bytes / (replay * 1e-3) / 1e9, 1),
@@ -408,11 +411,11 @@ def main():
                     help="issue esa_score, esa_select_topk and esa_gather_kv as three calls instead of the one fused call "
                          "esa_score_select_gather (same results, three kernels more)")
     ap.add_argument("--fused-gather", action="store_true",
-                    help="variant: esa_attend_indexed follows the indices itself instead of esa_gather_kv + esa_attend "
-                         "(four calls; not the default step)")
-    ap.add_argument("--gathered-decode", action="store_true",
-                    help="decode steps call esa_gather_kv + esa_attend like the chunk steps, instead of their default, "
-                         "the index-driven esa_attend_indexed")
+                    help="(the default now; kept so that older command lines still run)")
+    ap.add_argument("--gather-call", action="store_true",
+                    help="the step gathers the selected rows into a buffer (inside esa_score_select_gather, or by "
+                         "esa_gather_kv with --separate-calls) and calls esa_attend on it, instead of the default, the "
+                         "index-driven esa_attend_indexed")
     ap.add_argument("--fork-after", choices=("start", "score"), default="score",
                     help="where the second stream starts (the score sweeps want every CU for themselves)")
     ap.add_argument("--batch", type=int, default=1,
@@ -480,15 +483,17 @@ def main():
     # is the longest-running call for the prefill configurations; for one-token chunks the longest-running call is
     # the selection, a chain of launch-bound kernels over 1 MB of scores that no roofline describes
     dominant = max(CALLS, key=lambda c: max(work[c]["flops"] / (PEAK_BF16_TFLOPS * 1e12), work[c]["bytes"] / (PEAK_HBM_GBS * 1e9)))
+    # the call of that name as the step makes it: the attention reads the selected rows through the index list
+    timed_as = "attend_indexed" if dominant == "attend" and step_reads_through_indices(args, w.l_c) else dominant
     if work[dominant]["flops"] / (PEAK_BF16_TFLOPS * 1e12) > work[dominant]["bytes"] / (PEAK_HBM_GBS * 1e9):
-        achieved = work[dominant]["flops"] / (call_ms[dominant] * 1e-3) / 1e12
-        roofline = {"kernel": "esa_" + dominant, "bound": "mfma", "achieved": round(achieved, 2),
+        achieved = work[dominant]["flops"] / (call_ms[timed_as] * 1e-3) / 1e12
+        roofline = {"kernel": "esa_" + timed_as, "bound": "mfma", "achieved": round(achieved, 2),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                     "traffic": None}
         roofline["algorithmic_flops"] = round(work[dominant]["flops"])
     else:
-        achieved = work[dominant]["bytes"] / (call_ms[dominant] * 1e-3) / 1e9
-        roofline = {"kernel": "esa_" + dominant, "bound": "hbm", "achieved": round(achieved, 1),
+        achieved = work[dominant]["bytes"] / (call_ms[timed_as] * 1e-3) / 1e9
+        roofline = {"kernel": "esa_" + timed_as, "bound": "hbm", "achieved": round(achieved, 1),
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4),
                     "traffic": None}
     # `traffic` and `algorithmic_bytes` are both HBM bytes per launch of the dominant call
@@ -555,6 +560,8 @@ def whole_prompt(args, cfg, esa, torch, np):
     # k covers the middle segment in early chunks: every middle token is taken and no scores are read; the
     # buffer is allocated before the capture so that no fill is recorded into the graph
     no_scores = torch.empty(max(cfg.k, 1), dtype=torch.float32, device="cuda")
+    no_q = torch.zeros((min(cfg.l_C, cfg.S), cfg.d_c), dtype=K.dtype, device="cuda")     # never read: stands in for Q'
+    indexed = step_reads_through_indices(args, cfg.l_C)
 
     def prefill():
         out = None
@@ -567,7 +574,15 @@ def whole_prompt(args, cfg, esa, torch, np):
             else:
                 esa.esa_compress(K[t0:t1], W_k, out=kc[t0:t1])
             ks = vs = None
-            if n_mid > 0:
+            if n_mid > 0 and not args.separate_calls:
+                # the step of the last-chunk benchmark: score + select as one call, the attention reads the
+                # selected rows through the index list (or, with --gather-call, a gathered copy of them)
+                if indexed:
+                    _, idx, _, _ = esa.esa_score_select_gather(qc if n_mid > cfg.k else no_q, kc, i_end, l_start, cfg.k)
+                    out = esa.esa_attend_indexed(Q[t0:t1], K, V, t0, cfg.l_I, cfg.l_L, idx)
+                    continue
+                _, idx, ks, vs = esa.esa_score_select_gather(qc if n_mid > cfg.k else no_q, kc, i_end, l_start, cfg.k, K, V)
+            elif n_mid > 0:
                 score = esa.esa_score(qc, kc, i_end, l_start) if n_mid > cfg.k else no_scores[:n_mid]
                 idx = esa.esa_select_topk(score, cfg.k, base=i_end)
                 ks, vs = esa.esa_gather_kv(K, V, idx)
@@ -595,7 +610,10 @@ def whole_prompt(args, cfg, esa, torch, np):
         "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": "%s: whole prompt of %d tokens, %d chunks of %d, one layer" % (cfg.name, cfg.S, len(starts), cfg.l_C),
                    "global_batch": 1, "seq_len": cfg.S, "parallelism": "single GPU"},
-        "launch_mode": "one HIP graph for the whole prefill", "eager_tokens_per_s": round(cfg.S / eager_s, 1),
+        "launch_mode": "one HIP graph for the whole prefill"
+        + (", five separate calls per chunk" if args.separate_calls else
+           ", score+select as one call, gather inside the attention kernel" if indexed else
+           ", score+select+gather as one call"), "eager_tokens_per_s": round(cfg.S / eager_s, 1),
         "eager_ms": round(1e3 * eager_s, 3)}))
 
 

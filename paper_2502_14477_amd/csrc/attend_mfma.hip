@@ -225,14 +225,19 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   // for a tile that lies inside the selected segment are looked up one tile ahead of the tile's loads,
   // so that the look-up is not a dependent round trip in front of them.
   const int32_t* sidx = V.sel_idx ? V.sel_idx + (int64_t)b * V.idx_bs : nullptr;
-  uint32_t idx_a = 0, idx_b = 0;
+  // The entries are kept as loaded and clamped where tile_load uses them, a whole tile later: clamping here
+  // would be a use, and the wait in front of it would also wait for the tile loads issued just before, which
+  // are meant to land during the tile's arithmetic.
+  int32_t idx_a = 0, idx_b = 0;
   auto idx_prefetch = [&](uint32_t t) {
     const uint32_t j0 = t * kKT;
     if (sidx && t < tile_end && j0 >= V.i_end && j0 + kKT <= V.i_end + V.n_sel) {
-      idx_a = clamped_index(V, sidx, j0 - V.i_end + st_row);
-      idx_b = clamped_index(V, sidx, j0 - V.i_end + st_row + 32);
+      idx_a = sidx[j0 - V.i_end + st_row];
+      idx_b = sidx[j0 - V.i_end + st_row + 32];
     }
   };
+  // a middle token's position, clamped so that a bad index cannot leave the cache
+  auto cache_row = [&](int32_t v) -> uint32_t { return v < 0 ? 0u : ((uint32_t)v < V.idx_limit ? (uint32_t)v : V.idx_limit - 1); };
   auto tile_load = [&](uint32_t j0, bf16_t* kt, bf16_t* vt) {
     const uint32_t sel_end = V.i_end + V.n_sel;
     int seg = -1;                                                  // 0: cache rows, 1: gathered rows
@@ -255,10 +260,11 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     bf16_t* vd0 = vt + wave * 512;
     bf16_t* vd1 = vt + (wave + 8) * 512;
     if (seg == 1 && sidx) {             // rows idx_a / idx_b of the cache, looked up by idx_prefetch for this tile
-      dma16(kc + ((uint64_t)idx_a * V.tok_bytes + kcol), kd0);
-      dma16(kc + ((uint64_t)idx_b * V.tok_bytes + kcol), kd1);
-      dma16(vc + ((uint64_t)idx_a * V.tok_bytes + vcol), vd0);
-      dma16(vc + ((uint64_t)idx_b * V.tok_bytes + vcol), vd1);
+      const uint32_t row_a = cache_row(idx_a), row_b = cache_row(idx_b);
+      dma16(kc + ((uint64_t)row_a * V.tok_bytes + kcol), kd0);
+      dma16(kc + ((uint64_t)row_b * V.tok_bytes + kcol), kd1);
+      dma16(vc + ((uint64_t)row_a * V.tok_bytes + vcol), vd0);
+      dma16(vc + ((uint64_t)row_b * V.tok_bytes + vcol), vd1);
     } else if (seg >= 0) {
       const uint32_t stride = seg ? a.sel_bytes : V.tok_bytes;
       const char* kb = (seg ? ksl : kc) + (uint64_t)row0 * stride;
