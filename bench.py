@@ -39,28 +39,28 @@ VARIANT_CALLS = ("score_select_gather", "attend_indexed", "attend_local", "atten
 # x2.0 for FETCH_SIZE, x1.0 for WRITE_SIZE), summed over the kernels of the call.  Counters cannot be
 # read from inside this script, so a figure is attached only to the workload it was measured on and only
 # while the kernel sources are the ones it was measured on (TRAFFIC_TREE, see csrc_tree_hash).
-TRAFFIC_TREE = "f97d4e66f3c55e19"
+TRAFFIC_TREE = "d21ed0601422cb40"
 MEASURED_TRAFFIC_BYTES = {
-    ("C3", 131072, "score"): 73435616,
-    ("C3", 131072, "attend"): 62744576,
+    ("C3", 131072, "score"): 73488608,
+    ("C3", 131072, "attend"): 62822272,
     ("C3", 131072, "compress"): 16025600,
     ("C3", 131072, "gather"): 16861184,
-    ("C3", 131072, "select"): 2104896,
-    ("C5", 262144, "attend"): 125659136,
-    ("C5", 262144, "score"): 156842016,
-    ("C5", 262144, "gather"): 67393664,
+    ("C3", 131072, "select"): 2815552,
+    ("C5", 262144, "attend"): 125923328,
+    ("C5", 262144, "score"): 156882688,
+    ("C5", 262144, "gather"): 67393280,
     ("C5", 262144, "compress"): 21530624,
-    ("C5", 262144, "select"): 4085280,
-    ("C6", 131072, "score"): 72324032,
-    ("C6", 131072, "attend"): 71133184,
+    ("C5", 262144, "select"): 4913824,
+    ("C6", 131072, "score"): 72377024,
+    ("C6", 131072, "attend"): 71357568,
     ("C6", 131072, "compress"): 16025600,
     ("C6", 131072, "gather"): 16861184,
-    ("C6", 131072, "select"): 2079680,
-    ("C4", 262144, "score"): 69930848,
-    ("C4", 262144, "attend"): 19942144,
+    ("C6", 131072, "select"): 2785216,
+    ("C4", 262144, "score"): 70007648,
+    ("C4", 262144, "attend"): 19964672,
     ("C4", 262144, "gather"): 16861184,
-    ("C4", 262144, "compress"): 1440768,
-    ("C4", 262144, "select"): 4466944,
+    ("C4", 262144, "select"): 5285248,
+    ("C4", 262144, "compress"): 1459200,
 }
 
 
@@ -280,7 +280,10 @@ def per_call_times(esa, torch, np, w, args, with_variants):
         "gather": lambda: esa.esa_gather_kv(K, V, idx_s),
         "attend": lambda: esa.esa_attend(Q, K, V, t0, cfg.l_I, cfg.l_L, ks_s, vs_s),
     }
-    single["score_select_gather"] = lambda: esa.esa_score_select_gather(qc_s, kc, i_end, l_start, cfg.k, K, V)
+    if step_reads_through_indices(args, l_c):      # as the step calls it: no gathered copy
+        single["score_select_gather"] = lambda: esa.esa_score_select_gather(qc_s, kc, i_end, l_start, cfg.k)
+    else:
+        single["score_select_gather"] = lambda: esa.esa_score_select_gather(qc_s, kc, i_end, l_start, cfg.k, K, V)
     single["attend_indexed"] = lambda: esa.esa_attend_indexed(Q, K, V, t0, cfg.l_I, cfg.l_L, idx_s)
     if args.eager:      # under the profiler every attention launch is of the step's kind, so that per-kernel averages are the step's
         if step_reads_through_indices(args, l_c):

@@ -273,9 +273,11 @@ __global__ __launch_bounds__(kThreads) void topk_write(const float* __restrict__
   if ((int)threadIdx.x < (int)blockIdx.x) {
     above0 = w[TopkLayout::blk + threadIdx.x];
     c0 = w[TopkLayout::blk + nblk + threadIdx.x];
+    // read whether or not that workgroup left so many (its slots exist either way; the count decides below what
+    // is used): asking for the count first would put a second round trip in front of them
+    static_assert(kPeek <= kTile, "a workgroup's candidate slots");
 #pragma unroll
-    for (int j = 0; j < kPeek; ++j)
-      if ((uint32_t)j < c0) peek[j] = cand_all[threadIdx.x * cap + j];
+    for (int j = 0; j < kPeek; ++j) peek[j] = cand_all[threadIdx.x * cap + j];
   }
   uint32_t T, need;                                      // need: equal-to-T scores to take, lowest positions first
   resolve_prefix<3>(w, k, wave_sums, result, &T, &need);
