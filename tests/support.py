@@ -43,7 +43,7 @@ def oracle_step(layer, kc64, t0, eps=0):
     return O, lse, sel, F, qc
 
 
-def gpu_step(esa, dev, cfg, t0, kc_dev=None, two_calls=False, eps=0, fused=False):
+def gpu_step(esa, dev, cfg, t0, kc_dev=None, two_calls=False, eps=0, fused=False, indexed=False):
     """The five library calls for the step at t0.  dev: dict of device tensors Q,K,V,W_q,W_k
     (Q may start at row dev['q_row0']).  kc_dev: compressed-key cache [S, d_c]; rows of the current
     tokens are (re)written by esa_compress.  Returns dict of device tensors."""
@@ -59,6 +59,12 @@ def gpu_step(esa, dev, cfg, t0, kc_dev=None, two_calls=False, eps=0, fused=False
     assert (i_end, l_start) == segment_bounds(t0, cfg.l_I, cfg.l_L)
     n_mid = l_start - i_end
     out = {"qc": qc, "kc": kc_dev, "score": None}
+    if n_mid > 0 and indexed:
+        # the benchmark's default step: score + select as one call, the attention follows the index list itself
+        out["score"], idx, _, _ = esa.esa_score_select_gather(qc, kc_dev, i_end, l_start, cfg.k, eps=eps)
+        O, lse = esa.esa_attend_indexed(q, dev["K"], dev["V"], t0, cfg.l_I, cfg.l_L, idx, return_lse=True)
+        out.update(idx=idx, k_sel=None, v_sel=None, O=O, lse=lse)
+        return out
     if n_mid > 0 and fused:
         out["score"], idx, ks, vs = esa.esa_score_select_gather(qc, kc_dev, i_end, l_start, cfg.k, dev["K"], dev["V"], eps=eps)
     elif n_mid > 0:

@@ -713,6 +713,28 @@ def test_attend_indexed_equals_gather_then_attend(esa, dtype, B, H, H_kv, d, t0,
         assert np.max(np.abs(got - o64)) <= O_TOL[dtype]
 
 
+@pytest.mark.parametrize("l_C", [1, 3, 96])
+def test_attend_indexed_clamps_indices_that_leave_the_cache(esa, l_C):
+    """Entries below 0 or at or beyond the local window's start cannot be selected tokens; the kernels
+    clamp them into [0, l_start) instead of following them (decode kernel and matrix-core kernel alike)."""
+    say(f"attend_indexed with out-of-range entries, l_C={l_C}")
+    rng = np.random.default_rng(31 + l_C)
+    H, H_kv, d, t0, l_I, l_L, n_sel = 8, 2, 128, 1500, 16, 300, 200
+    S = t0 + l_C
+    bf = torch.bfloat16
+    q = torch.from_numpy(rng.standard_normal((l_C, H, d)).astype(np.float32)).cuda().to(bf)
+    K = torch.from_numpy(rng.standard_normal((S, H_kv, d)).astype(np.float32)).cuda().to(bf)
+    V = torch.from_numpy(rng.standard_normal((S, H_kv, d)).astype(np.float32)).cuda().to(bf)
+    i_end, l_start = segment_bounds(t0, l_I, l_L)
+    sel = np.sort(rng.choice(np.arange(i_end, l_start), n_sel, replace=False)).astype(np.int64)
+    bad = sel.copy()
+    bad[[0, 7, 64, 65, 130, 199]] = [-5, -(2 ** 31), l_start, 2 ** 31 - 1, S + 100000, l_start + 1]
+    clamped = np.clip(bad, 0, l_start - 1).astype(np.int32)
+    got = esa.esa_attend_indexed(q, K, V, t0, l_I, l_L, torch.from_numpy(bad.astype(np.int32)).cuda())
+    want = esa.esa_attend_indexed(q, K, V, t0, l_I, l_L, torch.from_numpy(clamped).cuda())
+    assert torch.equal(got, want)
+
+
 # ------------------------------------------------------------------------------------------ whole steps
 def _check_step(esa, layer, dev, kc64, kc_dev, t0, two_calls=False, eps=0):
     cfg = layer.cfg
@@ -902,6 +924,11 @@ def test_full_size_step_in_the_benchmark_launch_configuration(esa, name, chunk):
     if one["score"] is not None:
         assert torch.equal(fused["score"], one["score"])
         assert torch.equal(fused["k_sel"], one["k_sel"]) and torch.equal(fused["v_sel"], one["v_sel"])
+    # ... and with the gather left to the attention kernel (what the benchmark times): the same arithmetic in the same order
+    via_idx = gpu_step(esa, dev, cfg, t0, kc_dev, indexed=True)
+    assert torch.equal(via_idx["idx"], one["idx"]) and torch.equal(via_idx["O"], one["O"]) and torch.equal(via_idx["lse"], one["lse"])
+    if one["score"] is not None:
+        assert torch.equal(via_idx["score"], one["score"])
     if t0 in layer.plan.positions:
         needles = np.setdiff1d(layer.plan.positions[t0], replaced)
         assert needles.size and set(needles.tolist()) <= set(g["idx"].cpu().numpy().tolist())
@@ -909,7 +936,7 @@ def test_full_size_step_in_the_benchmark_launch_configuration(esa, name, chunk):
         assert chunk == 0 and g["idx"].numel() == 0          # the first chunk has no middle segment
 
 
-@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("fused", [False, True, "indexed"])
 def test_step_captured_as_a_graph_replays_identically(esa, fused):
     """The five calls captured once and replayed, with eager work and synchronisations between the
     replays: every replay must reproduce the eager result bit for bit (nothing in the library
@@ -920,17 +947,18 @@ def test_step_captured_as_a_graph_replays_identically(esa, fused):
     dev = pack_layer_weights(esa, layer_to_dev(layer))
     t0 = 7680
     kc_dev = esa.esa_compress(dev["K"], dev["W_k"])
-    eager = gpu_step(esa, dev, cfg, t0, kc_dev, fused=fused)
+    form = dict(indexed=True) if fused == "indexed" else dict(fused=fused)
+    eager = gpu_step(esa, dev, cfg, t0, kc_dev, **form)
     torch.cuda.synchronize()
     want_O, want_idx = eager["O"].clone(), eager["idx"].clone()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        gpu_step(esa, dev, cfg, t0, kc_dev, fused=fused)
+        gpu_step(esa, dev, cfg, t0, kc_dev, **form)
     torch.cuda.current_stream().wait_stream(side)
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        g = gpu_step(esa, dev, cfg, t0, kc_dev, fused=fused)
+        g = gpu_step(esa, dev, cfg, t0, kc_dev, **form)
     for rep in range(4):
         g["O"].zero_()
         g["idx"].zero_()
