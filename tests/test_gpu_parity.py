@@ -57,7 +57,8 @@ def _scores(rng, n, kind):
 
 @pytest.mark.parametrize("kind", ["normal", "ties", "importance", "constant"])
 @pytest.mark.parametrize("n,k", [(1, 1), (5, 3), (300, 1), (2047, 256), (2048, 2048), (2049, 2048), (2049, 5000),
-                                 (5000, 17), (40000, 2048), (128384, 2048), (259967, 2048), (70000, 69999)])
+                                 (5000, 17), (40000, 2048), (128384, 2048), (259967, 2048), (70000, 69999),
+                                 (700001, 4096)])     # more workgroups than compute units, one tile each
 def test_select_topk_is_bit_exact(esa, kind, n, k):
     say(f"topk kind={kind} n={n} k={k}")
     rng = np.random.default_rng(n * 7919 + k)
