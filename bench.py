@@ -151,7 +151,9 @@ def step_reads_through_indices(args, l_c):
     read of the selected rows fewer).  Measured on the step: 122.0 against 126.6 us at configuration 3, 452.8 / 464.0
     at 5, 136.8 / 141.3 at 6, 46.7 / 52.1 for a decode step, 314 / 370 at decode batch 16: the step takes the
     index-driven form unless told otherwise (--gather-call)."""
-    return not args.gather_call or args.fused_gather
+    if args.fused_gather:
+        return True
+    return not args.gather_call and not args.two_branches     # the two-branch form finishes on gathered rows
 
 
 def make_step(esa, torch, w, args, side=None):
@@ -409,7 +411,7 @@ def main():
     ap.add_argument("--two-branches", action="store_true",
                     help="variant: the selection-independent part (key compression, attention over I, L, C) runs on a "
                          "second stream beside select and gather and esa_attend_finish adds the selected keys; measured "
-                         "equal to the one-stream step at configuration 3, slower at configuration 5")
+                         "slower than the one-stream step (144 against 123 us at configuration 3)")
     ap.add_argument("--separate-calls", action="store_true",
                     help="issue esa_score, esa_select_topk and esa_gather_kv as three calls instead of the one fused call "
                          "esa_score_select_gather (same results, three kernels more)")
