@@ -96,6 +96,17 @@ struct AttendArgs {
   int64_t out_bs, sel_bs_bytes;
 };
 
+// Maximum / sum of a value over the two lanes 32 places apart: a lane swap in the vector unit.  (A general
+// shuffle goes through the LDS crossbar, and the wait for it is a wait for every LDS read in flight.)
+__device__ __forceinline__ float halves_max(float v) {
+  const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));     // lower half's value, upper half's value
+}
+__device__ __forceinline__ float halves_sum(float v) {
+  const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+}
+
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   f32x2 f = {lo, hi};
   bf16x2 b = __builtin_convertvector(f, bf16x2);
@@ -338,7 +349,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
       for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[mt][v]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    mx = halves_max(mx);
     // The reference m_run of the exponentials follows the running maximum lazily: it moves only when
     // a tile's maximum exceeds it by more than 2^kLazy, so probabilities stay below 2^kLazy (harmless
     // in bf16 and fp32) and the accumulators are rescaled once or twice per row instead of per tile.
@@ -437,7 +448,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
   // rounding well below that of the bf16 output, and any magnitude bf16 inputs can produce fits); beside
   // them go m + E and l * 2^-E, so that the merge's sums of 2^(m+E-M) * (O 2^-E) and 2^(m+E-M) * (l 2^-E)
   // are the plain log-sum-exp combination of Algorithm 1 with no trace of E.
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float l_tot = halves_sum(l_run);
   const bool final_out = n_slices == 1 && !a.to_slots;
   float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   float m_store = m_run, l_store = l_tot;
@@ -447,7 +458,7 @@ __global__ __launch_bounds__(kThreads) void attend_mfma_bf16(AttendArgs a) {
     for (int md = 0; md < 4; ++md)
 #pragma unroll
       for (int v = 0; v < 16; ++v) amax = fmaxf(amax, __builtin_fabsf(o[md][v]));
-    amax = fmaxf(amax, __shfl_xor(amax, 32, 64));
+    amax = halves_max(amax);
     int s_exp = 267 - (int)((__float_as_uint(amax) >> 23) & 0xFFu);      // biased exponent of 2^-E
     s_exp = s_exp < 17 ? 17 : (s_exp > 167 ? 167 : s_exp);              // 2^-110 .. 2^40
     inv = __uint_as_float((uint32_t)s_exp << 23);

@@ -256,8 +256,7 @@ __global__ __launch_bounds__(256) void compress_few_packed_bf16(CompressJob j0, 
 #pragma unroll
   for (int t = 0; t < kFewTok; ++t) {
     if (t >= n_tok) break;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) acc[t] += __shfl_xor(acc[t], off, 64);
+    acc[t] = wave_sum(acc[t]);
     if (lane == 0) red[wave][t] = acc[t];
   }
   __syncthreads();

@@ -27,7 +27,7 @@ __device__ __forceinline__ void hist_add(uint32_t* h, bool active, uint32_t bin)
   const uint64_t act = __ballot(active);
   if (act == 0ull) return;
   const int leader = __ffsll((long long)act) - 1;
-  const uint32_t lead_bin = __shfl(bin, leader, 64);
+  const uint32_t lead_bin = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);     // leader is the same in every lane
   const uint64_t same = __ballot(active && bin == lead_bin);
   if ((int)(__builtin_amdgcn_workitem_id_x() & 63) == leader) atomicAdd(&h[lead_bin], (uint32_t)__popcll(same));
   if (active && bin != lead_bin) atomicAdd(&h[bin], 1u);

@@ -49,15 +49,53 @@ __host__ inline int64_t topk_row_words(const TopkPlan& p) {
   return TopkLayout::blk + 2 * p.nblk + cand_words;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave in the vector unit: shifts inside the 16-lane rows, then the
+// last lane of row 0 / 2 is added into row 1 / 3 and lane 31 into the upper half (every lane of the wave must be
+// active).  The LDS-routed shuffles this replaces cost a crossbar round trip per step.
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, false);   // row_shr:1 (lanes without a source add 0)
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, false);   // row_shr:2
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);   // row_shr:4
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);   // row_shr:8
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1 and 3
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
+// Exclusive prefix sums of two values per thread over the block (one pair of barriers for both); *total_a and
+// *total_b get the block sums.  wave_sums: 2 * kThreads / 64 words.
+__device__ __forceinline__ void block_excl_scan2(uint32_t a, uint32_t b, uint32_t* before_a, uint32_t* before_b,
+                                                 uint32_t* total_a, uint32_t* total_b, uint32_t* wave_sums) {
+  constexpr int kWavesPerBlock = kThreads / 64;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const uint32_t ia = wave_incl_scan(a), ib = wave_incl_scan(b);
+  __syncthreads();                       // wave_sums may still be read from a previous call
+  if (lane == 63) {
+    wave_sums[w] = ia;
+    wave_sums[kWavesPerBlock + w] = ib;
+  }
+  __syncthreads();
+  uint32_t base_a = 0, tot_a = 0, base_b = 0, tot_b = 0;
+#pragma unroll
+  for (int i = 0; i < kWavesPerBlock; ++i) {
+    const uint32_t sa = wave_sums[i], sb = wave_sums[kWavesPerBlock + i];
+    if (i < w) {
+      base_a += sa;
+      base_b += sb;
+    }
+    tot_a += sa;
+    tot_b += sb;
+  }
+  *total_a = tot_a;
+  *total_b = tot_b;
+  *before_a = base_a + ia - a;
+  *before_b = base_b + ib - b;
+}
+
 // Exclusive prefix sum of one value per thread over the block; *total gets the block sum.
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* total, uint32_t* wave_sums) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  uint32_t incl = v;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    uint32_t t = __shfl_up(incl, off, 64);
-    if (lane >= off) incl += t;
-  }
+  const uint32_t incl = wave_incl_scan(v);
   __syncthreads();                       // wave_sums may still be read from a previous call
   if (lane == 63) wave_sums[w] = incl;
   __syncthreads();
@@ -238,8 +276,8 @@ __global__ __launch_bounds__(kThreads) void topk_hist(const float* __restrict__ 
     }
   }
   if (PASS == 2) {
-    above = (uint32_t)wave_sum((float)above);      // at most 64 * 8 * 8 per wave: exact in fp32
-    if ((threadIdx.x & 63) == 0) atomicAdd(&n_above, above);
+    above = wave_incl_scan(above);                 // lane 63 holds the wave's total
+    if ((threadIdx.x & 63) == 63) atomicAdd(&n_above, above);
   }
   __syncthreads();
   hist_flush(w + TopkLayout::hist + PASS * kHistReplicas * kBins, h, blockIdx.x, threadIdx.x, kThreads);
@@ -253,7 +291,7 @@ __global__ __launch_bounds__(kThreads) void topk_write(const float* __restrict__
                                                        uint32_t* __restrict__ ws, int64_t row_words, int nblk,
                                                        int64_t base, int32_t* __restrict__ idx, int64_t idx_bs,
                                                        uint32_t k, int sub) {
-  __shared__ uint32_t wave_sums[kThreads / 64];
+  __shared__ uint32_t wave_sums[2 * kThreads / 64];
   __shared__ uint32_t result[2];
   const float* row = score + (int64_t)blockIdx.y * score_bs;
   uint32_t* w = ws + (int64_t)blockIdx.y * row_words;
@@ -304,9 +342,8 @@ __global__ __launch_bounds__(kThreads) void topk_write(const float* __restrict__
       my_eq += dgt == t_digit ? 1u : 0u;
     }
   }
-  uint32_t off_gt, off_eq;
-  block_excl_scan(my_gt, &off_gt, wave_sums);
-  block_excl_scan(my_eq, &off_eq, wave_sums);
+  uint32_t off_gt, off_eq, unused_a, unused_b;
+  block_excl_scan2(my_gt, my_eq, &unused_a, &unused_b, &off_gt, &off_eq, wave_sums);
   for (int st = 0; st < sub; ++st) {                     // tiles in position order; the offsets run on
     const int64_t first = first0 + (int64_t)st * kTile;
     if (st > 0) load_keys(row, n, first, key, ok);
@@ -316,9 +353,10 @@ __global__ __launch_bounds__(kThreads) void topk_write(const float* __restrict__
       gt += (ok[e] && key[e] > T) ? 1u : 0u;
       eq += (ok[e] && key[e] == T) ? 1u : 0u;
     }
-    uint32_t tot_g, tot_e;
-    uint32_t g_before = off_gt + block_excl_scan(gt, &tot_g, wave_sums);
-    uint32_t e_before = off_eq + block_excl_scan(eq, &tot_e, wave_sums);
+    uint32_t tot_g, tot_e, g_before, e_before;
+    block_excl_scan2(gt, eq, &g_before, &e_before, &tot_g, &tot_e, wave_sums);
+    g_before += off_gt;
+    e_before += off_eq;
 #pragma unroll
     for (int e = 0; e < kItems; ++e) {
       if (!ok[e]) continue;
