@@ -376,22 +376,36 @@ __global__ __launch_bounds__(kThreads) void score_mfma_bf16(const bf16_t* __rest
   };
 
   // PASS 0: 32 running maxima per lane, each to be reduced over the 32 lanes of a half-wave: a butterfly
-  // that halves the number of values per step (31 exchanges instead of 160); lane r ends up with value r.
+  // that halves the number of values per step (31 exchanges instead of 160).  Every exchange is a vector-unit
+  // move: the two 16-lane rows of the half-wave swap (v_permlane16_swap hands both directions over at once),
+  // then inside a row lane i pairs with i ^ 8 (row rotation by 8), with 7 - i inside its group of eight
+  // (half-row mirror), with i ^ 1 and with i ^ 2 (quad permutations).  The side a lane keeps is decided by its
+  // bits 4, 3, 2, 0, 1 in that order, so lane r ends up with value (r & 28) | (r & 1) << 1 | (r >> 1) & 1.
   auto flush_row_maxima = [&](int q0) {
     float red[32];
 #pragma unroll
     for (int i = 0; i < 32; ++i) red[i] = aux[i / 16][i % 16];
 #pragma unroll
-    for (int off = 16, cnt = 32; off > 0; off >>= 1, cnt >>= 1) {
-      const bool upper = (r & off) != 0;
-#pragma unroll
-      for (int i = 0; i < cnt / 2; ++i) {
-        const float lo_v = red[i], hi_v = red[i + cnt / 2];
-        const float keep = upper ? hi_v : lo_v, send = upper ? lo_v : hi_v;
-        red[i] = fmaxf(keep, __shfl_xor(send, off, 64));
-      }
+    for (int i = 0; i < 16; ++i) {     // rows: an even row keeps values 0..15, the odd row 16..31
+      const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(red[i]), __float_as_uint(red[i + 16]), false, false);
+      red[i] = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
     }
-    const int mt = r / 16, v = r % 16;
+#define ESA_EXCHANGE_STEP(cnt, bit, ctrl)                                                                          \
+    {                                                                                                              \
+      const bool upper = (r & (bit)) != 0;                                                                         \
+      _Pragma("unroll") for (int i = 0; i < (cnt) / 2; ++i) {                                                      \
+        const float lo_v = red[i], hi_v = red[i + (cnt) / 2];                                                      \
+        const float keep = upper ? hi_v : lo_v, send = upper ? lo_v : hi_v;                                        \
+        red[i] = fmaxf(keep, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(send), (ctrl), 0xF, 0xF, true))); \
+      }                                                                                                            \
+    }
+    ESA_EXCHANGE_STEP(16, 8, 0x128)    // row_ror:8
+    ESA_EXCHANGE_STEP(8, 4, 0x141)     // row_half_mirror
+    ESA_EXCHANGE_STEP(4, 1, 0xB1)      // quad_perm [1,0,3,2]
+    ESA_EXCHANGE_STEP(2, 2, 0x4E)      // quad_perm [2,3,0,1]
+#undef ESA_EXCHANGE_STEP
+    const int held = (r & 28) | ((r & 1) << 1) | ((r >> 1) & 1);
+    const int mt = held / 16, v = held % 16;
     const int qrow = q0 + 32 * mt + 8 * (v / 4) + 4 * hi + (v % 4);
     // 32-bit index (batch x l_c x workgroups stays far below 2^32): scalar base + lane offset, no 64-bit address
     // to carry through the tile loop
