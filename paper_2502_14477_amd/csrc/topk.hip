@@ -325,7 +325,8 @@ __global__ __launch_bounds__(kThreads) void topk_write(const float* __restrict__
   uint32_t my_gt = 0, my_eq = 0;
   for (int i = threadIdx.x; i < (int)blockIdx.x; i += kThreads) {
     const bool head = i == (int)threadIdx.x;
-    const uint32_t c = head ? c0 : w[TopkLayout::blk + nblk + i];
+    uint32_t c = head ? c0 : w[TopkLayout::blk + nblk + i];
+    c = c < (uint32_t)cap ? c : (uint32_t)cap;           // a workgroup cannot have left more than its scores: the reads below stay inside its slots
     my_gt += head ? above0 : w[TopkLayout::blk + i];
     uint32_t j0 = 0;
     if (head) {
